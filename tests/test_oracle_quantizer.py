@@ -1,0 +1,142 @@
+"""Pins of the oracle's quantizers against exact rational arithmetic, closed
+forms and hand-checkable examples (CPU only)."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import taq_oracle as O
+from oracle import brute
+
+
+def _fp16_rows(seed, rows, n, scale=1.0):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return (rng.standard_normal((rows, n)) * scale).astype(np.float16)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("n", [40, 320])
+def test_symq_equals_exact_rational_on_fp16_inputs(bits, n):
+    x = _fp16_rows(11 + bits + n, 24, n)
+    code, scale = O.symq(x.astype(np.float32), bits)
+    qmax = (1 << (bits - 1)) - 1
+    for r in range(x.shape[0]):
+        ref, amax = brute.symq_exact([float(v) for v in x[r]], bits)
+        assert list(code[r]) == ref
+        # scale is the float32 nearest to amax/qmax
+        exact = amax / qmax
+        s = Fraction(float(scale[r]))
+        ulp = Fraction(float(np.spacing(scale[r])))
+        assert abs(s - exact) <= ulp / 2
+
+
+def test_symq_ties_are_common_and_go_to_even():
+    # x = [-1, .5, .25, 1] at 4 bits: x*7 = [-7, 3.5, 1.75, 7]; 3.5 is a tie -> 4
+    code, scale = O.symq(np.array([[-1.0, 0.5, 0.25, 1.0]], dtype=np.float32), 4)
+    assert list(code[0]) == [-7, 4, 2, 7]
+    assert scale[0] == np.float32(1.0) / np.float32(7.0)
+    # 2.5 -> 2 (even), 4.5 -> 4, 5.5 -> 6 : x = k/7 is not fp16-exact, so build ties at 8 bits
+    x = np.array([[127.0, 2.5, 4.5, 5.5, -2.5, -5.5]], dtype=np.float32)
+    code, _ = O.symq(x, 8)
+    assert list(code[0]) == [127, 2, 4, 6, -2, -6]
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_symq_invariants(bits):
+    qmax = (1 << (bits - 1)) - 1
+    x = _fp16_rows(5, 64, 80, scale=2.5).astype(np.float32)
+    code, scale = O.symq(x, bits)
+    deq = code.astype(np.float64) * scale.astype(np.float64)[:, None]
+    # error bound: half a step (plus float32 rounding of the scale)
+    assert np.all(np.abs(x - deq) <= scale[:, None].astype(np.float64) * (0.5 + 1e-6))
+    # the row maximum hits the end of the grid
+    assert np.all(np.abs(code).max(axis=1) == qmax)
+    assert code.min() >= -qmax and code.max() <= qmax
+    # sign symmetry
+    code_neg, scale_neg = O.symq(-x, bits)
+    assert np.array_equal(code_neg, -code) and np.array_equal(scale_neg, scale)
+    # idempotence on the dequantised values (computed in float32 as code*scale)
+    deq32 = (code.astype(np.float32) * scale[:, None]).astype(np.float32)
+    code2, scale2 = O.symq(deq32, bits)
+    assert np.array_equal(code2, code)
+    assert np.allclose(scale2, scale, rtol=2e-7, atol=0)
+
+
+def test_symq_zero_row_and_axis():
+    x = np.zeros((3, 8), dtype=np.float32)
+    x[1, 2] = -3.0
+    code, scale = O.symq(x, 8)
+    assert np.array_equal(code[0], np.zeros(8, dtype=np.int32)) and scale[0] == 1.0
+    assert code[1, 2] == -127 and scale[1] == np.float32(3.0) / np.float32(127.0)
+    # axis argument: quantizing columns equals quantizing the transpose's rows
+    y = _fp16_rows(3, 6, 10).astype(np.float32)
+    c0, s0 = O.symq(y, 8, axis=0)
+    c1, s1 = O.symq(y.T.copy(), 8, axis=1)
+    assert np.array_equal(c0, c1.T) and np.array_equal(s0, s1)
+
+
+def test_symq_float32_sequence_matches_scalar_float32_brute_on_full_mantissa_inputs():
+    # inputs with full float32 mantissas (as the dequantised projection rows have)
+    rng = np.random.Generator(np.random.PCG64(99))
+    x = (rng.standard_normal((16, 40)) * 1.7).astype(np.float32)
+    for bits in (4, 8):
+        code, scale = O.symq(x, bits)
+        for r in range(x.shape[0]):
+            cr, sc = brute.symq_f32(list(x[r]), bits)
+            assert list(code[r]) == cr and scale[r] == sc
+
+
+def test_uq8_known_values():
+    p = np.array([0.0, 1.0, 1.0 / 77.0, 0.5, 2.5 / 255.0, 3.5 / 255.0, 1e-4, 0.999])
+    # 0.5*255 = 127.5 -> 128 (even); 2.5/255 and 3.5/255 are not exact, so only the clear cases are pinned
+    code = O.uq8(p)
+    assert code[0] == 0 and code[1] == 255 and code[2] == 3 and code[3] == 128
+    assert code[6] == 0 and code[7] == 255
+    # error bound 1/510 on a fine grid, and monotonicity
+    grid = np.linspace(0.0, 1.0, 20001)
+    c = O.uq8(grid)
+    assert np.all(np.abs(c / 255.0 - grid) <= 1.0 / 510.0 + 1e-7)
+    assert np.all(np.diff(c) >= 0) and c.min() == 0 and c.max() == 255
+
+
+def test_pack_int4_layout():
+    packed = O.pack_int4(np.array([[-7, 7, 0, -1, 3, -4]]))
+    # low nibble = even element, two's complement: -7 -> 0x9, -1 -> 0xF, -4 -> 0xC
+    assert list(packed[0]) == [0x79, 0xF0, 0xC3]
+
+
+def test_quantize_weight_per_output_channel():
+    W = _fp16_rows(17, 12, 48, scale=0.05)
+    code, scale = O.quantize_weight(W)
+    assert code.dtype == np.int8 and code.shape == W.shape and scale.shape == (12,)
+    for c in range(12):
+        ref, amax = brute.symq_exact([float(v) for v in W[c]], 8)
+        assert list(code[c].astype(int)) == ref
+    # scaling one output channel changes only that channel's scale, not its codes
+    W2 = W.copy()
+    W2[3] = (W2[3].astype(np.float32) * 4).astype(np.float16)
+    code2, scale2 = O.quantize_weight(W2)
+    assert np.array_equal(code2, code)
+    assert scale2[3] == pytest.approx(4 * scale[3], rel=1e-6) and np.array_equal(np.delete(scale2, 3), np.delete(scale, 3))
+
+
+def test_bops_ratios_match_table1():
+    # closed form: BOPs scale with b_w*b_a, so 32/32 -> 8/8 is 16x and -> 8/4 is 32x
+    args = dict(B=2, N=4096, C=320, T=77, Cc=768)
+    full = O.block_bops(**args, b_w=32, b_a=32)
+    assert full / O.block_bops(**args, b_w=8, b_a=8) == 16.0
+    assert full / O.block_bops(**args, b_w=8, b_a=4) == 32.0
+    # the paper's own whole-model figures show the same ratios (to its printed precision)
+    import os
+    rows = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "table1_bops.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            model, bits, val = line.split()
+            rows[(model, bits)] = float(val)
+    for model in ("sd15", "sdxl_turbo"):
+        assert rows[(model, "32/32")] / rows[(model, "8/8")] == pytest.approx(16.0, rel=0.02)
+        assert rows[(model, "32/32")] / rows[(model, "8/4")] == pytest.approx(32.0, rel=0.02)
+    # MAC count of the block, by hand, for a 1-token case
+    assert O.block_bops(B=1, N=1, C=2, T=3, Cc=5, b_w=1, b_a=1) == 2.0 * (4 + 2 * 3 * 5 * 2 + 2 * 3 * 2 + 4)
