@@ -1,0 +1,165 @@
+/*
+ * libtaq — Trigger-Aware Quantized (TAQ) cross-attention for AMD MI355X (gfx950).
+ *
+ * C ABI of the library. It implements the quantized UNet cross-attention block of
+ * PersonalQ, Section III-B ("Trigger-Aware Quantization"):
+ *
+ *   K~ = M_KV*K + (1-M_KV)*Q_a(K),  V~ likewise,  Q~ = Q_a(Q)          (Eq. 2)
+ *   A  = softmax(Q~ K~^T / sqrt(d))                                     (attention definition)
+ *   A^ = M_A*A + (1-M_A)*Q_a(A)                                         (Eq. 3)
+ *   out = to_out(A^ V~)
+ *
+ * where the masks are 1 on the trigger-token rows of K/V (and the same columns
+ * of A). Details the paper leaves open are fixed as follows:
+ *   - Q_a on signed data is the symmetric quantizer  code = clamp(rint(x*qmax/amax)),
+ *     scale = amax/qmax, qmax = 2^(b-1)-1, all in IEEE float32, rint half-to-even;
+ *   - rows: K/V per (head, text token); Q per (image token, head); hidden states and
+ *     the attention output per image token; weights per output channel (8 bit);
+ *   - Q_a on probabilities is the fixed grid code = rint(255*A), A^ = code/255;
+ *   - to_q, to_out and the K/V projections of unprotected tokens are W8A8 integer
+ *     contractions; protected K/V rows are computed from the unquantized fp16 context
+ *     row (with the 8-bit weight codes) and stored as fp16.
+ *
+ * General rules
+ *   - Every data pointer is DEVICE memory owned by the caller, 16-byte aligned, unless
+ *     said otherwise. The library allocates nothing and keeps no state between calls.
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and return without waiting; the caller synchronises.
+ *   - Return value: TAQ_OK (0) or a negative taq_status. On error nothing is launched.
+ *     Inputs are assumed finite; NaN/Inf give unspecified results.
+ *   - Shapes: B batch elements, N image (query) tokens, C = H*d channels, T text
+ *     tokens, Cc text-context channels. Supported: T <= 96, d % 8 == 0, d <= 160,
+ *     C % 32 == 0, Cc % 32 == 0, H <= 64.
+ */
+#ifndef TAQ_H
+#define TAQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum taq_status {
+    TAQ_OK = 0,
+    TAQ_ERR_INVALID_ARG = -1,      /* NULL pointer, non-positive size, inconsistent arguments */
+    TAQ_ERR_UNSUPPORTED_BITS = -2, /* a bit width outside what this build implements        */
+    TAQ_ERR_BAD_SHAPE = -3,        /* shape outside the supported set listed above          */
+    TAQ_ERR_MISALIGNED = -4,       /* a pointer is not 16-byte aligned                      */
+    TAQ_ERR_HIP = -5               /* the HIP runtime reported an error at launch           */
+} taq_status;
+
+/* Problem description shared by all calls. */
+typedef struct taq_shape {
+    int B, N, C, H, T, Cc;   /* d = C / H                                                   */
+    int bits_kv;             /* 4 | 8 : width of unprotected K/V rows; 16 : keep every row fp16 */
+    int bits_prob;           /* 8 : probabilities on the 1/255 grid outside trigger columns  */
+    int bits_q;              /* 8 : Q~ = Q_a(Q)                                              */
+    int bits_proj;           /* 8 : W8A8 projections                                         */
+    float softmax_scale;     /* 0 => 1/sqrt(d)                                               */
+} taq_shape;
+
+/* Optional taps for tests and profiling (all pointers device memory or NULL). */
+typedef struct taq_debug {
+    int8_t* h_code;  /* i8  [B,N,C]  per-token codes of `hidden`                             */
+    float*  s_h;     /* f32 [B,N]                                                            */
+    int8_t* q_code;  /* i8  [B,N,C]  Q~ codes                                                */
+    float*  s_Q;     /* f32 [B,N,H]                                                          */
+    float*  O;       /* f32 [B,N,C]  A^ V~ before its quantization                           */
+    int8_t* o_code;  /* i8  [B,N,C]                                                          */
+    float*  s_o;     /* f32 [B,N]                                                            */
+    unsigned stage_mask; /* 0 = whole block; else OR of TAQ_STAGE_* to run only those stages
+                            (they then read what earlier calls left in `workspace`)          */
+} taq_debug;
+
+#define TAQ_STAGE_HIDDEN_QUANT 1u  /* per-token int8 codes of hidden            */
+#define TAQ_STAGE_TO_Q         2u  /* to_q integer GEMM + dequantisation         */
+#define TAQ_STAGE_Q_QUANT      4u  /* Q~ = Q_a(Q), Eq. (2) third line            */
+#define TAQ_STAGE_ATTN_CORE    8u  /* scores, softmax, Eq. (3), A^ V~            */
+#define TAQ_STAGE_O_QUANT      16u /* per-token int8 codes of the attention out  */
+#define TAQ_STAGE_TO_OUT       32u /* to_out integer GEMM + bias, fp16 store     */
+
+/* One request of a batched call: the arguments of taq_cross_attn, per request. */
+typedef struct taq_request {
+    const void*    hidden;
+    const void*    qkv_packed;
+    const int8_t*  Wq;
+    const int8_t*  Wo;
+    const float*   scales;
+    const uint8_t* trigger_mask;
+    void*          out;
+} taq_request;
+
+/* Bytes the caller must allocate for `qkv_packed` (the mixed-precision K~/V~ of
+ * Eq. 2 for every batch element) and for `workspace` (scratch of either call) at
+ * this shape. Host-only; no GPU work. */
+int taq_kv_packed_bytes(const taq_shape* shape, size_t* bytes);
+int taq_workspace_bytes(const taq_shape* shape, size_t* bytes);
+
+/* Per-output-channel symmetric int8 codes of an fp16 weight matrix
+ * (8-bit weights as in every setting of the paper's Table 1; round-to-nearest).
+ *   W_f16  : f16 [rows, cols] row-major (rows = output channels), cols % 8 == 0
+ *   codes  : i8  [rows, cols]  out
+ *   scales : f32 [rows]        out */
+int taq_quantize_weight(const void* W_f16, int rows, int cols, int8_t* codes, float* scales,
+                        void* hip_stream);
+
+/* Eq. (2), K and V lines: project the text context and build K~, V~.
+ *   context      : f16 [B, T, Cc]
+ *   trigger_mask : u8  [B, T], non-zero = trigger token (protected row). Read on the
+ *                  device; any number of rows, contiguous or not, may be set.
+ *   Wk, Wv       : f16 [C, Cc] row-major (out x in)
+ *   bits         : must equal shape->bits_kv (4, 8 or 16)
+ *   qkv_packed   : out, taq_kv_packed_bytes() bytes. Holds, per batch element: the
+ *                  protected-token list, per-(head,token) scales, int8 or packed int4
+ *                  codes (element 2j in the low nibble of byte j) of unprotected rows,
+ *                  and the fp16 protected rows. Opaque to the caller; see taq_unpack_kv.
+ *   workspace    : taq_workspace_bytes() bytes of scratch, contents undefined after.
+ * shape->N is ignored. */
+int taq_quantize_kv(const void* context, const uint8_t* trigger_mask, const void* Wk,
+                    const void* Wv, int bits, const taq_shape* shape, void* qkv_packed,
+                    void* workspace, void* hip_stream);
+
+/* Eq. (2) third line, the attention definition and Eq. (3): the block for image tokens.
+ *   hidden       : f16 [B, N, C]
+ *   qkv_packed   : as written by taq_quantize_kv for the same B, T, C, H, bits_kv
+ *   Wq, Wo       : i8  [C, C] row-major (out x in) weight codes (taq_quantize_weight)
+ *   scales       : f32 [3*C] = s_wq[C] | s_wo[C] | bias_o[C] (bias of to_out; zeros if none)
+ *   trigger_mask : u8 [B, T] or NULL. The protected-token list recorded in qkv_packed is
+ *                  what the kernels use; this argument is accepted for symmetry only.
+ *   out          : f16 [B, N, C]
+ *   workspace    : taq_workspace_bytes() bytes of scratch */
+int taq_cross_attn(const void* hidden, const void* qkv_packed, const int8_t* Wq, const int8_t* Wo,
+                   const float* scales, const uint8_t* trigger_mask, const taq_shape* shape,
+                   void* out, void* workspace, void* hip_stream);
+
+/* Same as taq_cross_attn with optional taps on the intermediate codes and scales
+ * (dbg may be NULL). Taps are copied out of the workspace on the same stream. */
+int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* Wq,
+                      const int8_t* Wo, const float* scales, const uint8_t* trigger_mask,
+                      const taq_shape* shape, void* out, void* workspace, void* hip_stream,
+                      const taq_debug* dbg);
+
+/* R independent requests of one shape, each with its own weights, K~/V~ and hidden
+ * states (e.g. R personalised checkpoints served together). `table` is HOST memory,
+ * R entries, read before the call returns. `workspace` must hold R times
+ * taq_workspace_bytes(). */
+int taq_cross_attn_batched(int R, const taq_request* table, const taq_shape* shape,
+                           void* workspace, void* hip_stream);
+
+/* Expand qkv_packed into plain arrays (for tests). Any output may be NULL.
+ *   k_codes, v_codes : i8  [B, T, C]  (int4 codes sign-extended; zeros on protected rows)
+ *   k_scales,v_scales: f32 [B, H, T]  (zeros on protected rows)
+ *   k_trig, v_trig   : f16 [B, T, C]  (protected rows in place, zeros elsewhere) */
+int taq_unpack_kv(const void* qkv_packed, const taq_shape* shape, int8_t* k_codes, int8_t* v_codes,
+                  float* k_scales, float* v_scales, void* k_trig_f16, void* v_trig_f16,
+                  void* hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char* taq_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAQ_H */

@@ -137,6 +137,19 @@ class QuantKV:
         return np.where(M, full, code.astype(f64) * sc)
 
 
+def _int_matmul(x_code, w_code):
+    """Exact integer contraction sum_k x[..., k] * w[c, k] -> int64 [..., c].
+
+    Done as a float64 matrix product: every product is below 2^14 and every
+    partial sum below K * 2^14 << 2^53, so each intermediate is an integer that
+    float64 represents exactly, whatever the summation order."""
+    x = np.asarray(x_code)
+    w = np.asarray(w_code)
+    assert x.shape[-1] * 127 * 127 < 2 ** 52
+    acc = np.matmul(x.astype(f64), w.astype(f64).T)
+    return np.rint(acc).astype(np.int64)
+
+
 def _project_rows(x16, W16, bits_proj, mask, store_f16):
     """One projection of the text context (K or V side).
 
@@ -149,7 +162,7 @@ def _project_rows(x16, W16, bits_proj, mask, store_f16):
         # reading: the projection itself is W8A8 for unprotected tokens
         w_code, s_w = symq(W.astype(f32), 8, axis=1)  # per output channel
         x_code, s_x = symq(x.astype(f32), 8, axis=-1)  # per token
-        acc = np.einsum("btk,ck->btc", x_code.astype(np.int64), w_code.astype(np.int64))
+        acc = _int_matmul(x_code, w_code)
         rows_q = (acc.astype(f32) * (s_x[:, :, None] * s_w[None, None, :]).astype(f32)).astype(f32)
         # reading: a protected token keeps its unquantized fp16 context row and
         # fp accumulation, but meets the same 8-bit weight codes
@@ -211,7 +224,7 @@ def _linear_w8a8(x, w_code, s_w):
     """Per-token int8 activation codes, exact integer contraction with the
     weight codes, float32 dequantisation: acc * (s_x * s_w)."""
     x_code, s_x = symq(np.asarray(x, dtype=f32), 8, axis=-1)
-    acc = np.einsum("bnk,ck->bnc", x_code.astype(np.int64), np.asarray(w_code).astype(np.int64))
+    acc = _int_matmul(x_code, w_code)
     y = (acc.astype(f32) * (s_x[:, :, None] * np.asarray(s_w, dtype=f32)[None, None, :]).astype(f32)).astype(f32)
     return y, x_code, s_x, acc
 

@@ -1,0 +1,54 @@
+"""Build libtaq.so (gfx950 only) in-tree with hipcc.
+
+    python -m paper_2603_22943_amd.build
+
+Flags that matter for parity with the float32-defined quantizers:
+  -ffp-contract=off                          no silent FMA contraction (FMAs are explicit where wanted)
+  -fhip-fp32-correctly-rounded-divide-sqrt   IEEE float32 division
+and packed-fp32 instructions are switched off for the device pass.
+"""
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libtaq.so")
+SOURCES = ["taq_api.hip", "taq_quant.hip", "taq_gemm.hip", "taq_attn.hip"]
+
+
+def hipcc_path() -> str:
+    for cand in (shutil.which("hipcc"), "/opt/rocm/bin/hipcc"):
+        if cand and os.path.exists(cand):
+            return cand
+    raise RuntimeError("hipcc not found: libtaq needs the ROCm toolchain")
+
+
+def build_lib(verbose: bool = True) -> str:
+    srcs = [os.path.join(CSRC, s) for s in SOURCES]
+    cmd = [
+        hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+        "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt",
+        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        "-Wall", "-Wno-unused-function",
+        "-I", os.path.join(os.path.dirname(HERE), "include"),
+        "-o", LIB,
+    ] + srcs
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if verbose and out.strip():
+        print(out, flush=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    return LIB
+
+
+if __name__ == "__main__":
+    build_lib()
+    print("built", LIB)
+    sys.exit(0)

@@ -1,0 +1,225 @@
+// C ABI of libtaq: argument checks and the launch sequences of the two calls
+// (PersonalQ, Section III-B: Eq. 2 for taq_quantize_kv, Eq. 2 third line + Eq. 3 for
+// taq_cross_attn). No allocation, no synchronisation, no state.
+#include "taq_internal.h"
+
+using namespace taq;
+
+namespace {
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_shape(const taq_shape* s, bool need_n) {
+    if (!s) return TAQ_ERR_INVALID_ARG;
+    if (s->B <= 0 || s->C <= 0 || s->H <= 0 || s->T <= 0 || s->Cc <= 0) return TAQ_ERR_INVALID_ARG;
+    if (need_n && s->N <= 0) return TAQ_ERR_INVALID_ARG;
+    if (s->bits_kv != 4 && s->bits_kv != 8 && s->bits_kv != 16) return TAQ_ERR_UNSUPPORTED_BITS;
+    if (s->bits_prob != 8 || s->bits_q != 8 || s->bits_proj != 8) return TAQ_ERR_UNSUPPORTED_BITS;
+    if (s->C % s->H != 0) return TAQ_ERR_BAD_SHAPE;
+    const int d = s->C / s->H;
+    if (d % 8 != 0 || d > TAQ_MAX_D) return TAQ_ERR_BAD_SHAPE;
+    if (s->T > TAQ_MAX_T || s->H > TAQ_MAX_H) return TAQ_ERR_BAD_SHAPE;
+    if (s->C % 32 != 0 || s->Cc % 32 != 0 || s->Cc > 4096) return TAQ_ERR_BAD_SHAPE;
+    if (!(s->softmax_scale >= 0.f)) return TAQ_ERR_INVALID_ARG;
+    // index arithmetic inside the kernels is 32-bit for token counts
+    if ((long long)s->B * (need_n ? s->N : 1) > (1ll << 30)) return TAQ_ERR_BAD_SHAPE;
+    return TAQ_OK;
+}
+
+#define TAQ_TRY_HIP(expr)                      \
+    do {                                       \
+        hipError_t e_ = (expr);                \
+        if (e_ != hipSuccess) return TAQ_ERR_HIP; \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char* taq_status_string(int status) {
+    switch (status) {
+        case TAQ_OK: return "TAQ_OK";
+        case TAQ_ERR_INVALID_ARG: return "TAQ_ERR_INVALID_ARG: null pointer, non-positive size or inconsistent arguments";
+        case TAQ_ERR_UNSUPPORTED_BITS: return "TAQ_ERR_UNSUPPORTED_BITS: bit width not implemented";
+        case TAQ_ERR_BAD_SHAPE: return "TAQ_ERR_BAD_SHAPE: shape outside the supported set";
+        case TAQ_ERR_MISALIGNED: return "TAQ_ERR_MISALIGNED: pointer not 16-byte aligned";
+        case TAQ_ERR_HIP: return "TAQ_ERR_HIP: HIP runtime error at launch";
+        default: return "unknown taq_status";
+    }
+}
+
+int taq_kv_packed_bytes(const taq_shape* shape, size_t* bytes) {
+    if (!bytes) return TAQ_ERR_INVALID_ARG;
+    int rc = check_shape(shape, false);
+    if (rc != TAQ_OK) return rc;
+    *bytes = kv_layout(*shape).total;
+    return TAQ_OK;
+}
+
+int taq_workspace_bytes(const taq_shape* shape, size_t* bytes) {
+    if (!bytes) return TAQ_ERR_INVALID_ARG;
+    int rc = check_shape(shape, false);
+    if (rc != TAQ_OK) return rc;
+    taq_shape s = *shape;
+    if (s.N <= 0) s.N = 1;
+    const size_t a = attn_workspace(s).total, k = kv_workspace(s).total;
+    *bytes = a > k ? a : k;
+    return TAQ_OK;
+}
+
+int taq_quantize_weight(const void* W_f16, int rows, int cols, int8_t* codes, float* scales, void* hip_stream) {
+    if (!W_f16 || !codes || !scales || rows <= 0 || cols <= 0) return TAQ_ERR_INVALID_ARG;
+    if (cols % 8 != 0) return TAQ_ERR_BAD_SHAPE;
+    if (misaligned(W_f16) || misaligned(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return TAQ_ERR_MISALIGNED;
+    TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(W_f16), rows, cols, codes, scales,
+                                    static_cast<hipStream_t>(hip_stream)));
+    return TAQ_OK;
+}
+
+int taq_quantize_kv(const void* context, const uint8_t* trigger_mask, const void* Wk, const void* Wv, int bits,
+                    const taq_shape* shape, void* qkv_packed, void* workspace, void* hip_stream) {
+    int rc = check_shape(shape, false);
+    if (rc != TAQ_OK) return rc;
+    if (!context || !trigger_mask || !Wk || !Wv || !qkv_packed || !workspace) return TAQ_ERR_INVALID_ARG;
+    if (bits != shape->bits_kv) return TAQ_ERR_INVALID_ARG;
+    if (misaligned(context) || misaligned(Wk) || misaligned(Wv) || misaligned(qkv_packed) || misaligned(workspace))
+        return TAQ_ERR_MISALIGNED;
+    const taq_shape& s = *shape;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const KvLayout L = kv_layout(s);
+    const KvWorkspace W = kv_workspace(s);
+    uint8_t* pk = static_cast<uint8_t*>(qkv_packed);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    int8_t* w_code = reinterpret_cast<int8_t*>(ws + W.w_code);
+    float* s_w = reinterpret_cast<float*>(ws + W.s_w);
+    int8_t* x_code = reinterpret_cast<int8_t*>(ws + W.x_code);
+    float* s_x = reinterpret_cast<float*>(ws + W.s_x);
+    float* rows_f = reinterpret_cast<float*>(ws + W.rows_f);
+    int* ntrig = reinterpret_cast<int*>(pk + L.ntrig);
+    int* trig_idx = reinterpret_cast<int*>(pk + L.trig_idx);
+    int* slot_of = reinterpret_cast<int*>(pk + L.slot_of);
+    const int M = s.B * s.T;
+
+    TAQ_TRY_HIP(launch_kv_mask_scan(trigger_mask, s.B, s.T, s.bits_kv, ntrig, trig_idx, slot_of, st));
+    // 8-bit weight codes, Wk rows then Wv rows
+    TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(Wk), s.C, s.Cc, w_code, s_w, st));
+    TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(Wv), s.C, s.Cc, w_code + (size_t)s.C * s.Cc, s_w + s.C, st));
+    if (s.bits_kv != 16) {
+        // unprotected tokens: per-token int8 context codes, integer GEMM, float32 dequantisation
+        TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(context), M, s.Cc, x_code, s_x, st));
+        TAQ_TRY_HIP(launch_gemm_i8(x_code, s_x, w_code, s_w, nullptr, M, 2 * s.C, s.Cc, rows_f, nullptr, 2 * s.C, st));
+    }
+    // Eq. (2): per-(head, token) codes of unprotected rows; zero codes/scales on protected rows
+    TAQ_TRY_HIP(launch_kv_pack(rows_f, slot_of, s.B, s.T, s.C, s.H, s.bits_kv, pk + L.k_code, pk + L.v_code,
+                               reinterpret_cast<float*>(pk + L.s_k), reinterpret_cast<float*>(pk + L.s_v), st));
+    // protected rows in fp16
+    TAQ_TRY_HIP(launch_kv_trigger_rows(static_cast<const __half*>(context), w_code, s_w, ntrig, trig_idx, s.B, s.T,
+                                       s.C, s.Cc, reinterpret_cast<__half*>(pk + L.k16),
+                                       reinterpret_cast<__half*>(pk + L.v16), st));
+    return TAQ_OK;
+}
+
+int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* Wq, const int8_t* Wo,
+                      const float* scales, const uint8_t* trigger_mask, const taq_shape* shape, void* out,
+                      void* workspace, void* hip_stream, const taq_debug* dbg) {
+    (void)trigger_mask;  // the protected-token list travels inside qkv_packed
+    int rc = check_shape(shape, true);
+    if (rc != TAQ_OK) return rc;
+    if (!hidden || !qkv_packed || !Wq || !Wo || !scales || !out || !workspace) return TAQ_ERR_INVALID_ARG;
+    if (misaligned(hidden) || misaligned(qkv_packed) || misaligned(Wq) || misaligned(Wo) || misaligned(scales) ||
+        misaligned(out) || misaligned(workspace))
+        return TAQ_ERR_MISALIGNED;
+    const taq_shape& s = *shape;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const AttnWorkspace W = attn_workspace(s);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    int8_t* h_code = reinterpret_cast<int8_t*>(ws + W.h_code);
+    float* s_h = reinterpret_cast<float*>(ws + W.s_h);
+    float* q_f = reinterpret_cast<float*>(ws + W.q_f);
+    int8_t* q_code = reinterpret_cast<int8_t*>(ws + W.q_code);
+    float* s_q = reinterpret_cast<float*>(ws + W.s_q);
+    float* o_f = reinterpret_cast<float*>(ws + W.o_f);
+    int8_t* o_code = reinterpret_cast<int8_t*>(ws + W.o_code);
+    float* s_o = reinterpret_cast<float*>(ws + W.s_o);
+    const float* s_wq = scales;
+    const float* s_wo = scales + s.C;
+    const float* bias_o = scales + 2 * s.C;
+    const int M = s.B * s.N;
+    const unsigned stages = (dbg && dbg->stage_mask) ? dbg->stage_mask : ~0u;
+
+    if (stages & TAQ_STAGE_HIDDEN_QUANT)
+        TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(hidden), M, s.C, h_code, s_h, st));
+    if (stages & TAQ_STAGE_TO_Q)
+        TAQ_TRY_HIP(launch_gemm_i8(h_code, s_h, Wq, s_wq, nullptr, M, s.C, s.C, q_f, nullptr, s.C, st));
+    if (stages & TAQ_STAGE_Q_QUANT)
+        TAQ_TRY_HIP(launch_headquant_f32(q_f, M, s.C, s.H, q_code, s_q, st));
+    if (stages & TAQ_STAGE_ATTN_CORE)
+        TAQ_TRY_HIP(launch_attn_core(q_code, s_q, static_cast<const uint8_t*>(qkv_packed), s, o_f, st));
+    if (stages & TAQ_STAGE_O_QUANT)
+        TAQ_TRY_HIP(launch_rowquant_f32(o_f, M, s.C, o_code, s_o, st));
+    if (stages & TAQ_STAGE_TO_OUT)
+        TAQ_TRY_HIP(launch_gemm_i8(o_code, s_o, Wo, s_wo, bias_o, M, s.C, s.C, nullptr, static_cast<__half*>(out), s.C, st));
+
+    if (dbg) {
+        const size_t MC = (size_t)M * s.C;
+        if (dbg->h_code) TAQ_TRY_HIP(hipMemcpyAsync(dbg->h_code, h_code, MC, hipMemcpyDeviceToDevice, st));
+        if (dbg->s_h) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_h, s_h, (size_t)M * 4, hipMemcpyDeviceToDevice, st));
+        if (dbg->q_code) TAQ_TRY_HIP(hipMemcpyAsync(dbg->q_code, q_code, MC, hipMemcpyDeviceToDevice, st));
+        if (dbg->s_Q) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_Q, s_q, (size_t)M * s.H * 4, hipMemcpyDeviceToDevice, st));
+        if (dbg->O) TAQ_TRY_HIP(hipMemcpyAsync(dbg->O, o_f, MC * 4, hipMemcpyDeviceToDevice, st));
+        if (dbg->o_code) TAQ_TRY_HIP(hipMemcpyAsync(dbg->o_code, o_code, MC, hipMemcpyDeviceToDevice, st));
+        if (dbg->s_o) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_o, s_o, (size_t)M * 4, hipMemcpyDeviceToDevice, st));
+    }
+    return TAQ_OK;
+}
+
+int taq_cross_attn(const void* hidden, const void* qkv_packed, const int8_t* Wq, const int8_t* Wo,
+                   const float* scales, const uint8_t* trigger_mask, const taq_shape* shape, void* out,
+                   void* workspace, void* hip_stream) {
+    return taq_cross_attn_ex(hidden, qkv_packed, Wq, Wo, scales, trigger_mask, shape, out, workspace, hip_stream,
+                             nullptr);
+}
+
+int taq_cross_attn_batched(int R, const taq_request* table, const taq_shape* shape, void* workspace,
+                           void* hip_stream) {
+    if (R <= 0 || !table) return TAQ_ERR_INVALID_ARG;
+    int rc = check_shape(shape, true);
+    if (rc != TAQ_OK) return rc;
+    if (!workspace || misaligned(workspace)) return workspace ? TAQ_ERR_MISALIGNED : TAQ_ERR_INVALID_ARG;
+    // validate every request before launching anything
+    for (int r = 0; r < R; ++r) {
+        const taq_request& q = table[r];
+        if (!q.hidden || !q.qkv_packed || !q.Wq || !q.Wo || !q.scales || !q.out) return TAQ_ERR_INVALID_ARG;
+        if (misaligned(q.hidden) || misaligned(q.qkv_packed) || misaligned(q.Wq) || misaligned(q.Wo) ||
+            misaligned(q.scales) || misaligned(q.out))
+            return TAQ_ERR_MISALIGNED;
+    }
+    size_t per = 0;
+    rc = taq_workspace_bytes(shape, &per);
+    if (rc != TAQ_OK) return rc;
+    {
+        taq_shape s = *shape;
+        per = attn_workspace(s).total > per ? attn_workspace(s).total : per;
+    }
+    for (int r = 0; r < R; ++r) {
+        const taq_request& q = table[r];
+        rc = taq_cross_attn_ex(q.hidden, q.qkv_packed, q.Wq, q.Wo, q.scales, q.trigger_mask, shape, q.out,
+                               static_cast<uint8_t*>(workspace) + (size_t)r * per, hip_stream, nullptr);
+        if (rc != TAQ_OK) return rc;
+    }
+    return TAQ_OK;
+}
+
+int taq_unpack_kv(const void* qkv_packed, const taq_shape* shape, int8_t* k_codes, int8_t* v_codes,
+                  float* k_scales, float* v_scales, void* k_trig_f16, void* v_trig_f16, void* hip_stream) {
+    int rc = check_shape(shape, false);
+    if (rc != TAQ_OK) return rc;
+    if (!qkv_packed) return TAQ_ERR_INVALID_ARG;
+    if (misaligned(qkv_packed)) return TAQ_ERR_MISALIGNED;
+    TAQ_TRY_HIP(launch_kv_unpack(static_cast<const uint8_t*>(qkv_packed), *shape, k_codes, v_codes, k_scales,
+                                 v_scales, static_cast<__half*>(k_trig_f16), static_cast<__half*>(v_trig_f16),
+                                 static_cast<hipStream_t>(hip_stream)));
+    return TAQ_OK;
+}
+
+}  // extern "C"

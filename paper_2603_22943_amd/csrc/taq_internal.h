@@ -1,0 +1,140 @@
+// Internal declarations shared by the libtaq translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/taq.h"
+
+#define TAQ_MAX_T 96        // text tokens the attention core holds in LDS (3 tiles of 32)
+#define TAQ_MAX_D 160       // largest head dimension (5 steps of 32)
+#define TAQ_MAX_H 64
+
+namespace taq {
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Layout of qkv_packed: fixed by the shape alone, every section 256-byte aligned.
+struct KvLayout {
+    size_t ntrig;     // i32 [B]        number of protected tokens
+    size_t trig_idx;  // i32 [B][T]     token index of protected slot s (first ntrig valid)
+    size_t slot_of;   // i32 [B][T]     slot of token t, or -1 if unprotected
+    size_t s_k;       // f32 [B][H][T]  0 on protected tokens
+    size_t s_v;       // f32 [B][H][T]
+    size_t k_code;    // u8  [B][T][Cb] Cb = C (8 bit) | C/2 (4 bit) | 0 (16 bit)
+    size_t v_code;
+    size_t k16;       // f16 [B][T][C]  protected rows, compacted by slot
+    size_t v16;
+    size_t total;
+    int Cb;
+};
+
+static inline KvLayout kv_layout(const taq_shape& s) {
+    KvLayout L;
+    size_t off = 0;
+    const size_t B = s.B, T = s.T, C = s.C, H = s.H;
+    L.Cb = s.bits_kv == 8 ? s.C : (s.bits_kv == 4 ? s.C / 2 : 0);
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    L.ntrig = take(B * 4);
+    L.trig_idx = take(B * T * 4);
+    L.slot_of = take(B * T * 4);
+    L.s_k = take(B * H * T * 4);
+    L.s_v = take(B * H * T * 4);
+    L.k_code = take(B * T * (size_t)L.Cb);
+    L.v_code = take(B * T * (size_t)L.Cb);
+    L.k16 = take(B * T * C * 2);
+    L.v16 = take(B * T * C * 2);
+    L.total = off;
+    return L;
+}
+
+// Workspace of taq_quantize_kv.
+struct KvWorkspace {
+    size_t w_code;  // i8  [2C][Cc]   Wk rows then Wv rows
+    size_t s_w;     // f32 [2C]
+    size_t x_code;  // i8  [B*T][Cc]
+    size_t s_x;     // f32 [B*T]
+    size_t rows_f;  // f32 [B*T][2C]  dequantised projection rows (K then V channels)
+    size_t total;
+};
+
+static inline KvWorkspace kv_workspace(const taq_shape& s) {
+    KvWorkspace W;
+    size_t off = 0;
+    const size_t M = (size_t)s.B * s.T, C2 = 2 * (size_t)s.C, Cc = s.Cc;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    W.w_code = take(C2 * Cc);
+    W.s_w = take(C2 * 4);
+    W.x_code = take(M * Cc);
+    W.s_x = take(M * 4);
+    W.rows_f = take(M * C2 * 4);
+    W.total = off;
+    return W;
+}
+
+// Workspace of taq_cross_attn (per request).
+struct AttnWorkspace {
+    size_t h_code;  // i8  [B*N][C]
+    size_t s_h;     // f32 [B*N]
+    size_t q_f;     // f32 [B*N][C]
+    size_t q_code;  // i8  [B*N][C]
+    size_t s_q;     // f32 [B*N][H]
+    size_t o_f;     // f32 [B*N][C]
+    size_t o_code;  // i8  [B*N][C]
+    size_t s_o;     // f32 [B*N]
+    size_t total;
+};
+
+static inline AttnWorkspace attn_workspace(const taq_shape& s) {
+    AttnWorkspace W;
+    size_t off = 0;
+    const size_t M = (size_t)s.B * s.N, C = s.C, H = s.H;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    W.h_code = take(M * C);
+    W.s_h = take(M * 4);
+    W.q_f = take(M * C * 4);
+    W.q_code = take(M * C);
+    W.s_q = take(M * H * 4);
+    W.o_f = take(M * C * 4);
+    W.o_code = take(M * C);
+    W.s_o = take(M * 4);
+    W.total = off;
+    return W;
+}
+
+// ---- kernel launchers (each returns a hipError_t from the launch) ----------------
+
+// Per-row symmetric int8 codes of fp16 rows: x [M][K] -> code [M][K], scale [M].
+hipError_t launch_rowquant_f16(const __half* x, int M, int K, int8_t* code, float* scale, hipStream_t st);
+// Same for float32 rows.
+hipError_t launch_rowquant_f32(const float* x, int M, int K, int8_t* code, float* scale, hipStream_t st);
+// Per-(row, head) symmetric int8 codes of float32 rows: x [M][C] -> code [M][C], scale [M][H].
+hipError_t launch_headquant_f32(const float* x, int M, int C, int H, int8_t* code, float* scale, hipStream_t st);
+
+// Protected-token bookkeeping of qkv_packed from the mask (all tokens when bits == 16).
+hipError_t launch_kv_mask_scan(const uint8_t* mask, int B, int T, int bits, int* ntrig, int* trig_idx,
+                               int* slot_of, hipStream_t st);
+// Per-(head, token) codes and scales of unprotected K/V rows, written into qkv_packed.
+hipError_t launch_kv_pack(const float* rows_f, const int* slot_of, int B, int T, int C, int H, int bits,
+                          uint8_t* k_code, uint8_t* v_code, float* s_k, float* s_v, hipStream_t st);
+// Protected K/V rows: fp16 context row x int8 weight codes, fp32 accumulate, fp16 store.
+hipError_t launch_kv_trigger_rows(const __half* context, const int8_t* w_code, const float* s_w,
+                                  const int* ntrig, const int* trig_idx, int B, int T, int C, int Cc,
+                                  __half* k16, __half* v16, hipStream_t st);
+// Expansion of qkv_packed for tests.
+hipError_t launch_kv_unpack(const uint8_t* packed, const taq_shape& s, int8_t* k_codes, int8_t* v_codes,
+                            float* k_scales, float* v_scales, __half* k_trig, __half* v_trig, hipStream_t st);
+
+// int8 GEMM  acc[m][n] = sum_k A[m][k]*W[n][k]  with dequantisation acc*(sa[m]*sw[n]):
+//   out_f32 != NULL: float32 result [M][ldo];  out_f16 != NULL: fp16(result + bias[n]).
+hipError_t launch_gemm_i8(const int8_t* A, const float* sa, const int8_t* W, const float* sw,
+                          const float* bias, int M, int N, int K, float* out_f32, __half* out_f16,
+                          int ldo, hipStream_t st);
+
+// Attention core: scores, softmax, Eq. (3), A^ V~ for all (batch, head, token).
+hipError_t launch_attn_core(const int8_t* q_code, const float* s_q, const uint8_t* packed,
+                            const taq_shape& s, float* o_f, hipStream_t st);
+
+}  // namespace taq

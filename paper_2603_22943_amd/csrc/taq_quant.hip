@@ -1,0 +1,333 @@
+// Quantizer kernels of libtaq (gfx950): per-row / per-(row, head) symmetric codes,
+// K~/V~ packing (Eq. 2 of PersonalQ, Section III-B), protected-row projection.
+//
+// The symmetric quantizer is a fixed float32 sequence so that codes are reproducible
+// bit for bit:  amax = max|x|;  scale = amax/qmax;  code = clamp(rint((x*qmax)/amax)).
+// The build disables FMA contraction and keeps IEEE-correct float32 division.
+#include "taq_internal.h"
+
+namespace taq {
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+// One code of the symmetric quantizer; amax > 0.
+__device__ __forceinline__ int symq_code(float x, float qmaxf, float amax) {
+    float t = x * qmaxf;
+    float q = t / amax;  // correctly rounded float32 division
+    float r = __builtin_rintf(q);  // half-to-even
+    r = fminf(fmaxf(r, -qmaxf), qmaxf);
+    return (int)r;
+}
+
+__device__ __forceinline__ void unpack_half8(const uint4& u, float f[8]) {
+    const __half2* h = reinterpret_cast<const __half2*>(&u);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float2 p = __half22float2(h[i]);
+        f[2 * i] = p.x;
+        f[2 * i + 1] = p.y;
+    }
+}
+
+__device__ __forceinline__ unsigned pack4_i8(int a, int b, int c, int d) {
+    return (unsigned)(a & 0xFF) | ((unsigned)(b & 0xFF) << 8) | ((unsigned)(c & 0xFF) << 16) |
+           ((unsigned)(d & 0xFF) << 24);
+}
+
+// ---------------------------------------------------------------- fp16 rows -> int8
+// One wavefront per row. K % 8 == 0.
+__global__ __launch_bounds__(256) void rowquant_f16_kernel(const __half* __restrict__ x, int M, int K,
+                                                           int8_t* __restrict__ code,
+                                                           float* __restrict__ scale) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= M) return;
+    const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)row * K);
+    const int nv = K >> 3;
+    float amax = 0.f;
+    for (int v = lane; v < nv; v += 64) {
+        float f[8];
+        unpack_half8(xr[v], f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
+    }
+    amax = wave_max(amax);
+    const bool zero = amax == 0.f;
+    const float sc = zero ? 1.f : amax / 127.f;
+    const float safe = zero ? 1.f : amax;
+    if (lane == 0) scale[row] = sc;
+    uint2* cr = reinterpret_cast<uint2*>(code + (size_t)row * K);
+    for (int v = lane; v < nv; v += 64) {
+        float f[8];
+        unpack_half8(xr[v], f);
+        int c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c[i] = symq_code(f[i], 127.f, safe);
+        uint2 o;
+        o.x = pack4_i8(c[0], c[1], c[2], c[3]);
+        o.y = pack4_i8(c[4], c[5], c[6], c[7]);
+        cr[v] = o;
+    }
+}
+
+hipError_t launch_rowquant_f16(const __half* x, int M, int K, int8_t* code, float* scale, hipStream_t st) {
+    if (M <= 0) return hipSuccess;
+    hipLaunchKernelGGL(rowquant_f16_kernel, dim3((M + 3) / 4), dim3(256), 0, st, x, M, K, code, scale);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- f32 rows -> int8
+// One wavefront per row. K % 4 == 0.
+__global__ __launch_bounds__(256) void rowquant_f32_kernel(const float* __restrict__ x, int M, int K,
+                                                           int8_t* __restrict__ code,
+                                                           float* __restrict__ scale) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= M) return;
+    const float4* xr = reinterpret_cast<const float4*>(x + (size_t)row * K);
+    const int nv = K >> 2;
+    float amax = 0.f;
+    for (int v = lane; v < nv; v += 64) {
+        float4 f = xr[v];
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w))));
+    }
+    amax = wave_max(amax);
+    const bool zero = amax == 0.f;
+    const float sc = zero ? 1.f : amax / 127.f;
+    const float safe = zero ? 1.f : amax;
+    if (lane == 0) scale[row] = sc;
+    unsigned* cr = reinterpret_cast<unsigned*>(code + (size_t)row * K);
+    for (int v = lane; v < nv; v += 64) {
+        float4 f = xr[v];
+        cr[v] = pack4_i8(symq_code(f.x, 127.f, safe), symq_code(f.y, 127.f, safe),
+                         symq_code(f.z, 127.f, safe), symq_code(f.w, 127.f, safe));
+    }
+}
+
+hipError_t launch_rowquant_f32(const float* x, int M, int K, int8_t* code, float* scale, hipStream_t st) {
+    if (M <= 0) return hipSuccess;
+    hipLaunchKernelGGL(rowquant_f32_kernel, dim3((M + 3) / 4), dim3(256), 0, st, x, M, K, code, scale);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- f32 rows -> int8 per head
+// One wavefront per row; per-head maxima through LDS atomics on the bit pattern of |x|
+// (non-negative floats order like unsigned integers). d % 4 == 0, H <= TAQ_MAX_H.
+__global__ __launch_bounds__(256) void headquant_f32_kernel(const float* __restrict__ x, int M, int C, int H,
+                                                            int8_t* __restrict__ code,
+                                                            float* __restrict__ scale) {
+    __shared__ unsigned smax[4][TAQ_MAX_H];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + wave;
+    const bool live = row < M;
+    const int d = C / H;
+    for (int h = lane; h < H; h += 64) smax[wave][h] = 0u;
+    __syncthreads();
+    const float4* xr = reinterpret_cast<const float4*>(x + (size_t)(live ? row : 0) * C);
+    const int nv = C >> 2;
+    if (live) {
+        for (int v = lane; v < nv; v += 64) {
+            float4 f = xr[v];
+            float a = fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w)));
+            atomicMax(&smax[wave][(v * 4) / d], __float_as_uint(a));
+        }
+    }
+    __syncthreads();
+    if (!live) return;
+    for (int h = lane; h < H; h += 64) {
+        float amax = __uint_as_float(smax[wave][h]);
+        scale[(size_t)row * H + h] = amax == 0.f ? 1.f : amax / 127.f;
+    }
+    unsigned* cr = reinterpret_cast<unsigned*>(code + (size_t)row * C);
+    for (int v = lane; v < nv; v += 64) {
+        float4 f = xr[v];
+        float amax = __uint_as_float(smax[wave][(v * 4) / d]);
+        float safe = amax == 0.f ? 1.f : amax;
+        cr[v] = pack4_i8(symq_code(f.x, 127.f, safe), symq_code(f.y, 127.f, safe),
+                         symq_code(f.z, 127.f, safe), symq_code(f.w, 127.f, safe));
+    }
+}
+
+hipError_t launch_headquant_f32(const float* x, int M, int C, int H, int8_t* code, float* scale,
+                                hipStream_t st) {
+    if (M <= 0) return hipSuccess;
+    hipLaunchKernelGGL(headquant_f32_kernel, dim3((M + 3) / 4), dim3(256), 0, st, x, M, C, H, code, scale);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- protected-token list
+__global__ void kv_mask_scan_kernel(const uint8_t* __restrict__ mask, int T, int bits, int* __restrict__ ntrig,
+                                    int* __restrict__ trig_idx, int* __restrict__ slot_of) {
+    const int b = blockIdx.x;
+    if (threadIdx.x != 0) return;
+    int n = 0;
+    for (int t = 0; t < T; ++t) {
+        const bool prot = bits == 16 || mask[b * T + t] != 0;
+        slot_of[b * T + t] = prot ? n : -1;
+        if (prot) trig_idx[b * T + n++] = t;
+    }
+    for (int s = n; s < T; ++s) trig_idx[b * T + s] = -1;
+    ntrig[b] = n;
+}
+
+hipError_t launch_kv_mask_scan(const uint8_t* mask, int B, int T, int bits, int* ntrig, int* trig_idx,
+                               int* slot_of, hipStream_t st) {
+    hipLaunchKernelGGL(kv_mask_scan_kernel, dim3(B), dim3(64), 0, st, mask, T, bits, ntrig, trig_idx, slot_of);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- K~/V~ codes, Eq. (2)
+// One wavefront per (batch, token). rows_f holds that token's K channels then V channels;
+// each head's d channels are one quantization row. Protected tokens get zero codes/scales.
+__global__ __launch_bounds__(64) void kv_pack_kernel(const float* __restrict__ rows_f,
+                                                     const int* __restrict__ slot_of, int T, int C, int H,
+                                                     int bits, uint8_t* __restrict__ k_code,
+                                                     uint8_t* __restrict__ v_code, float* __restrict__ s_k,
+                                                     float* __restrict__ s_v) {
+    __shared__ unsigned smax[2 * TAQ_MAX_H];
+    const int bt = blockIdx.x, b = bt / T, t = bt % T, lane = threadIdx.x;
+    const int d = C / H;
+    const bool prot = slot_of[bt] >= 0;
+    const float qmaxf = bits == 4 ? 7.f : 127.f;
+    for (int g = lane; g < 2 * H; g += 64) smax[g] = 0u;
+    __syncthreads();
+    const float4* xr = reinterpret_cast<const float4*>(rows_f + (size_t)bt * 2 * C);
+    const int nv = (2 * C) >> 2;
+    if (!prot) {
+        for (int v = lane; v < nv; v += 64) {
+            float4 f = xr[v];
+            float a = fmaxf(fmaxf(fabsf(f.x), fabsf(f.y)), fmaxf(fabsf(f.z), fabsf(f.w)));
+            atomicMax(&smax[(v * 4) / d], __float_as_uint(a));
+        }
+    }
+    __syncthreads();
+    for (int g = lane; g < 2 * H; g += 64) {
+        float amax = __uint_as_float(smax[g]);
+        float sc = prot ? 0.f : (amax == 0.f ? 1.f : amax / qmaxf);
+        float* dst = g < H ? s_k : s_v;
+        dst[((size_t)b * H + (g % H)) * T + t] = sc;
+    }
+    if (bits == 16) return;  // every row protected: there is no code section
+    for (int v = lane; v < nv; v += 64) {
+        const int ch = v * 4;  // channel within the 2C-wide row
+        int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
+        if (!prot) {
+            float4 f = xr[v];
+            float amax = __uint_as_float(smax[ch / d]);
+            float safe = amax == 0.f ? 1.f : amax;
+            c0 = symq_code(f.x, qmaxf, safe);
+            c1 = symq_code(f.y, qmaxf, safe);
+            c2 = symq_code(f.z, qmaxf, safe);
+            c3 = symq_code(f.w, qmaxf, safe);
+        }
+        uint8_t* base = ch < C ? k_code : v_code;
+        const int c = ch < C ? ch : ch - C;
+        if (bits == 8) {
+            *reinterpret_cast<unsigned*>(base + (size_t)bt * C + c) = pack4_i8(c0, c1, c2, c3);
+        } else {
+            unsigned short w = (unsigned short)((c0 & 0xF) | ((c1 & 0xF) << 4) | ((c2 & 0xF) << 8) |
+                                                ((c3 & 0xF) << 12));
+            *reinterpret_cast<unsigned short*>(base + (size_t)bt * (C / 2) + c / 2) = w;
+        }
+    }
+}
+
+hipError_t launch_kv_pack(const float* rows_f, const int* slot_of, int B, int T, int C, int H, int bits,
+                          uint8_t* k_code, uint8_t* v_code, float* s_k, float* s_v, hipStream_t st) {
+    hipLaunchKernelGGL(kv_pack_kernel, dim3(B * T), dim3(64), 0, st, rows_f, slot_of, T, C, H, bits, k_code,
+                       v_code, s_k, s_v);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- protected K/V rows
+// One workgroup per (slot, batch): y[c] = s_w[c] * sum_k ctx[t][k] * w_code[c][k], float32
+// accumulation in four partial sums, one rounding to fp16. Cc % 16 == 0, Cc <= 4096.
+__global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __restrict__ context,
+                                                              const int8_t* __restrict__ w_code,
+                                                              const float* __restrict__ s_w,
+                                                              const int* __restrict__ ntrig,
+                                                              const int* __restrict__ trig_idx, int T, int C,
+                                                              int Cc, __half* __restrict__ k16,
+                                                              __half* __restrict__ v16) {
+    __shared__ float xs[4096];
+    const int slot = blockIdx.x, b = blockIdx.y;
+    if (slot >= ntrig[b]) return;
+    const int t = trig_idx[b * T + slot];
+    const __half* xr = context + ((size_t)b * T + t) * Cc;
+    for (int k = threadIdx.x; k < Cc; k += 256) xs[k] = __half2float(xr[k]);
+    __syncthreads();
+    for (int c = threadIdx.x; c < 2 * C; c += 256) {
+        const int4* wr = reinterpret_cast<const int4*>(w_code + (size_t)c * Cc);
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int kv = 0; kv < (Cc >> 4); ++kv) {
+            int4 w = wr[kv];
+            const int wd[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float wf = (float)(int)(int8_t)((wd[q] >> (8 * e)) & 0xFF);
+                    acc[e] = __builtin_fmaf(xs[kv * 16 + q * 4 + e], wf, acc[e]);
+                }
+            }
+        }
+        float sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+        float y = sum * s_w[c];
+        __half* dst = c < C ? k16 : v16;
+        dst[((size_t)b * T + slot) * C + (c < C ? c : c - C)] = __float2half_rn(y);
+    }
+}
+
+hipError_t launch_kv_trigger_rows(const __half* context, const int8_t* w_code, const float* s_w,
+                                  const int* ntrig, const int* trig_idx, int B, int T, int C, int Cc,
+                                  __half* k16, __half* v16, hipStream_t st) {
+    hipLaunchKernelGGL(kv_trigger_rows_kernel, dim3(T, B), dim3(256), 0, st, context, w_code, s_w, ntrig,
+                       trig_idx, T, C, Cc, k16, v16);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- expansion for tests
+__global__ __launch_bounds__(256) void kv_unpack_kernel(const uint8_t* __restrict__ packed, KvLayout L, int T,
+                                                        int C, int H, int bits, int8_t* k_codes,
+                                                        int8_t* v_codes, float* k_scales, float* v_scales,
+                                                        __half* k_trig, __half* v_trig) {
+    const int bt = blockIdx.x, b = bt / T, t = bt % T;
+    const int slot = reinterpret_cast<const int*>(packed + L.slot_of)[bt];
+    const float* s_k = reinterpret_cast<const float*>(packed + L.s_k);
+    const float* s_v = reinterpret_cast<const float*>(packed + L.s_v);
+    for (int h = threadIdx.x; h < H; h += 256) {
+        size_t i = ((size_t)b * H + h) * T + t;
+        if (k_scales) k_scales[i] = s_k[i];
+        if (v_scales) v_scales[i] = s_v[i];
+    }
+    for (int side = 0; side < 2; ++side) {
+        const uint8_t* codes = packed + (side ? L.v_code : L.k_code);
+        const __half* full = reinterpret_cast<const __half*>(packed + (side ? L.v16 : L.k16));
+        int8_t* oc = side ? v_codes : k_codes;
+        __half* ot = side ? v_trig : k_trig;
+        for (int c = threadIdx.x; c < C; c += 256) {
+            int code = 0;
+            if (slot < 0 && bits == 8) code = (int8_t)codes[(size_t)bt * C + c];
+            if (slot < 0 && bits == 4) {
+                int nib = (codes[(size_t)bt * (C / 2) + c / 2] >> (4 * (c & 1))) & 0xF;
+                code = (nib ^ 8) - 8;  // sign-extend the two's-complement nibble
+            }
+            if (oc) oc[(size_t)bt * C + c] = (int8_t)code;
+            if (ot) ot[(size_t)bt * C + c] = slot >= 0 ? full[((size_t)b * T + slot) * C + c] : __float2half(0.f);
+        }
+    }
+}
+
+hipError_t launch_kv_unpack(const uint8_t* packed, const taq_shape& s, int8_t* k_codes, int8_t* v_codes,
+                            float* k_scales, float* v_scales, __half* k_trig, __half* v_trig, hipStream_t st) {
+    KvLayout L = kv_layout(s);
+    hipLaunchKernelGGL(kv_unpack_kernel, dim3(s.B * s.T), dim3(256), 0, st, packed, L, s.T, s.C, s.H, s.bits_kv,
+                       k_codes, v_codes, k_scales, v_scales, k_trig, v_trig);
+    return hipGetLastError();
+}
+
+}  // namespace taq

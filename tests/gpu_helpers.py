@@ -1,0 +1,81 @@
+"""Shared plumbing of the GPU parity tests: move a synthetic layer to the GPU,
+run the HIP path through the C ABI, run the oracle on the same inputs."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import taq_oracle as O
+from paper_2603_22943_amd import taq as T
+
+DEV = "cuda:0"
+
+
+def shape_of(L, bits_kv=None, N=None):
+    return T.make_shape(B=L.B, N=L.N if N is None else N, C=L.C, H=L.H, T=L.T, Cc=L.Cc,
+                        bits_kv=L.bits_kv if bits_kv is None else bits_kv)
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to(DEV)
+
+
+class GpuRun:
+    """Everything the HIP path produces for one layer (tensors brought back as numpy)."""
+
+    def __init__(self, L, taps=True, hidden=None):
+        self.L = L
+        self.shape = s = shape_of(L)
+        ctx, mask = dev(L.context), dev(L.mask)
+        Wq, Wk, Wv, Wo = dev(L.Wq), dev(L.Wk), dev(L.Wv), dev(L.Wo)
+        self.wq_code, self.s_wq = T.taq_quantize_weight(Wq)
+        self.wo_code, self.s_wo = T.taq_quantize_weight(Wo)
+        self.scales = torch.cat([self.s_wq, self.s_wo, dev(L.bias_o)]).contiguous()
+        self.packed = T.taq_quantize_kv(ctx, mask, Wk, Wv, L.bits_kv, s)
+        self.kv = {k: v.cpu().numpy() for k, v in T.taq_unpack_kv(self.packed, s).items()}
+        self.mask_d = mask
+        self.hidden_d = dev(L.hidden if hidden is None else hidden)
+        if hidden is not None:
+            self.shape = s = shape_of(L, N=hidden.shape[1])
+        if taps:
+            dbg, t = T.make_debug(s, DEV)
+            self.out_d = T.taq_cross_attn(self.hidden_d, self.packed, self.wq_code, self.wo_code, self.scales,
+                                          mask, s, debug=dbg)
+            torch.cuda.synchronize()
+            self.taps = {k: v.cpu().numpy() for k, v in t.items()}
+        else:
+            self.out_d = T.taq_cross_attn(self.hidden_d, self.packed, self.wq_code, self.wo_code, self.scales,
+                                          mask, s)
+            torch.cuda.synchronize()
+            self.taps = {}
+        self.out = self.out_d.cpu().numpy()
+
+
+def oracle_run(L, hidden=None):
+    kv = O.quantize_kv(L.context, L.mask, L.Wk, L.Wv, L.bits_kv, L.H)
+    wq_code, s_wq = O.quantize_weight(L.Wq)
+    wo_code, s_wo = O.quantize_weight(L.Wo)
+    out, aux = O.cross_attn(L.hidden if hidden is None else hidden, kv, wq_code, s_wq, wo_code, s_wo, L.bias_o,
+                            return_aux=True)
+    aux.update(kv=kv, wq_code=wq_code, s_wq=s_wq, wo_code=wo_code, s_wo=s_wo)
+    return out, aux
+
+
+def fp16_ulp_distance(a, b):
+    """Distance in units of fp16 steps between two fp16-valued arrays (same sign assumed near 0)."""
+    ia = np.asarray(a, dtype=np.float16).view(np.int16).astype(np.int32)
+    ib = np.asarray(b, dtype=np.float16).view(np.int16).astype(np.int32)
+    ia = np.where(ia < 0, -(ia & 0x7FFF), ia)
+    ib = np.where(ib < 0, -(ib & 0x7FFF), ib)
+    return np.abs(ia - ib)
+
+
+def out_errors(out, ref):
+    o = np.asarray(out, dtype=np.float64)
+    r = np.asarray(ref, dtype=np.float64)
+    max_abs = float(np.max(np.abs(o - r))) if o.size else 0.0
+    rel_l2 = float(np.linalg.norm(o - r) / max(np.linalg.norm(r), 1e-30))
+    return max_abs, rel_l2

@@ -1,0 +1,122 @@
+"""The C-ABI boundary without a GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_22943_amd import taq as T
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000  # 16-byte aligned, never dereferenced on error paths
+ODD = FAKE + 4
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "taq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(taq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = T.load()
+    names = header_functions()
+    assert set(names) == set(T.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_sizes_match_header_layout():
+    assert ctypes.sizeof(T.taq_shape) == 11 * 4
+    assert ctypes.sizeof(T.taq_request) == 7 * 8
+    assert ctypes.sizeof(T.taq_debug) == 7 * 8 + 8
+
+
+def test_status_strings():
+    assert T.taq_status_string(0) == "TAQ_OK"
+    for code in (-1, -2, -3, -4, -5):
+        assert T.taq_status_string(code).startswith("TAQ_ERR_")
+    assert "unknown" in T.taq_status_string(-99)
+
+
+def test_size_queries_are_host_only_and_consistent():
+    s = T.make_shape(B=2, N=4096, C=320, H=8, T=77, Cc=768, bits_kv=8)
+    kv8 = T.taq_kv_packed_bytes(s)
+    ws = T.taq_workspace_bytes(s)
+    s4 = T.make_shape(B=2, N=4096, C=320, H=8, T=77, Cc=768, bits_kv=4)
+    kv4 = T.taq_kv_packed_bytes(s4)
+    s16 = T.make_shape(B=2, N=4096, C=320, H=8, T=77, Cc=768, bits_kv=16)
+    kv16 = T.taq_kv_packed_bytes(s16)
+    # int4 codes take half the bytes of int8 codes; 16-bit has no code section
+    code8 = 2 * 2 * 77 * 320
+    assert kv8 - kv4 == pytest.approx(code8 / 2, abs=1024)
+    assert kv8 - kv16 == pytest.approx(code8, abs=1024)
+    assert kv8 % 256 == 0 and ws % 256 == 0
+    # workspace holds at least the int8 Q~ codes, their float32 source and the float32 O
+    assert ws >= 2 * 4096 * 320 * (1 + 4 + 1 + 4 + 1)
+
+
+@pytest.mark.parametrize("kw,expect", [
+    (dict(bits_kv=5), T.TAQ_ERR_UNSUPPORTED_BITS),
+    (dict(bits_prob=4), T.TAQ_ERR_UNSUPPORTED_BITS),
+    (dict(bits_q=16), T.TAQ_ERR_UNSUPPORTED_BITS),
+    (dict(bits_proj=16), T.TAQ_ERR_UNSUPPORTED_BITS),
+    (dict(C=324), T.TAQ_ERR_BAD_SHAPE),  # C % H != 0
+    (dict(C=96, H=8), T.TAQ_ERR_BAD_SHAPE),  # d = 12, not a multiple of 8
+    (dict(C=2048, H=8), T.TAQ_ERR_BAD_SHAPE),  # d = 256 > 160
+    (dict(T=97), T.TAQ_ERR_BAD_SHAPE),
+    (dict(Cc=100), T.TAQ_ERR_BAD_SHAPE),
+    (dict(B=0), T.TAQ_ERR_INVALID_ARG),
+    (dict(softmax_scale=-1.0), T.TAQ_ERR_INVALID_ARG),
+])
+def test_bad_shapes_are_rejected(kw, expect):
+    base = dict(B=2, N=64, C=320, H=8, T=77, Cc=768)
+    base.update(kw)
+    s = T.make_shape(**base)
+    n = ctypes.c_size_t(0)
+    assert T.load().taq_kv_packed_bytes(ctypes.byref(s), ctypes.byref(n)) == expect
+    with pytest.raises(T.TaqError) as e:
+        T.taq_kv_packed_bytes(s)
+    assert e.value.status == expect
+
+
+def test_entry_points_reject_null_misaligned_and_inconsistent_arguments_without_launching():
+    lib = T.load()
+    s = T.make_shape(B=1, N=64, C=320, H=8, T=77, Cc=768, bits_kv=8)
+    sp = ctypes.byref(s)
+    # taq_quantize_kv
+    assert lib.taq_quantize_kv(None, FAKE, FAKE, FAKE, 8, sp, FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    assert lib.taq_quantize_kv(FAKE, FAKE, FAKE, FAKE, 4, sp, FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG  # bits != shape
+    assert lib.taq_quantize_kv(ODD, FAKE, FAKE, FAKE, 8, sp, FAKE, FAKE, None) == T.TAQ_ERR_MISALIGNED
+    assert lib.taq_quantize_kv(FAKE, FAKE, FAKE, FAKE, 8, None, FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    # taq_cross_attn
+    assert lib.taq_cross_attn(FAKE, FAKE, FAKE, FAKE, FAKE, None, sp, None, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    assert lib.taq_cross_attn(FAKE, FAKE, FAKE, ODD, FAKE, None, sp, FAKE, FAKE, None) == T.TAQ_ERR_MISALIGNED
+    s0 = T.make_shape(B=1, N=0, C=320, H=8, T=77, Cc=768)
+    assert lib.taq_cross_attn(FAKE, FAKE, FAKE, FAKE, FAKE, None, ctypes.byref(s0), FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    # taq_quantize_weight
+    assert lib.taq_quantize_weight(FAKE, 0, 64, FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    assert lib.taq_quantize_weight(FAKE, 8, 60, FAKE, FAKE, None) == T.TAQ_ERR_BAD_SHAPE
+    assert lib.taq_quantize_weight(FAKE, 8, 64, ODD, FAKE, None) == T.TAQ_ERR_MISALIGNED
+    # batched
+    assert lib.taq_cross_attn_batched(0, None, sp, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    tab = (T.taq_request * 2)()
+    tab[0] = T.taq_request(FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE)
+    tab[1] = T.taq_request(FAKE, FAKE, FAKE, FAKE, FAKE, None, None)  # second request lacks `out`
+    assert lib.taq_cross_attn_batched(2, tab, sp, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    # unpack
+    assert lib.taq_unpack_kv(None, sp, None, None, None, None, None, None, None) == T.TAQ_ERR_INVALID_ARG
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2603_22943_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith(".py"):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2603_22943_amd" not in text and "libtaq" not in text.replace("the HIP library", ""), f

@@ -1,0 +1,181 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Bars:
+  * integer codes and float32 scales that are fed by exact inputs or exact integer
+    accumulators (weights, hidden-state codes, Q~ codes, K~/V~ codes, all their scales):
+    bit-exact;
+  * protected K/V rows (float sums of 768..2048 terms rounded once to fp16): within one
+    fp16 step of the oracle's float64 sum;
+  * block output: max-abs <= 2e-2 and relative L2 <= 5e-3 against the oracle's output
+    (the oracle rounds to fp16 at the storage points the method defines);
+  * A^ V~ and its int8 codes sit behind exp() and float sums, so they are compared with
+    a tolerance: a probability that lands within float32 rounding of a k+1/2 tie may
+    take the neighbouring code on either side, which moves one output channel by about
+    s_V*|v|/255 and can move its int8 code by one.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_22943_amd import synth
+from paper_2603_22943_amd import taq as T
+from tests import gpu_helpers as G
+
+pytestmark = pytest.mark.gpu
+
+OUT_MAX_ABS = 2e-2
+OUT_REL_L2 = 5e-3
+
+
+def check_layer(L, label=""):
+    print(f"[case] {label or L.name}: B={L.B} N={L.N} C={L.C} H={L.H} T={L.T} Cc={L.Cc} bits_kv={L.bits_kv} "
+          f"ntrig={L.mask.sum(axis=1).tolist()}", flush=True)
+    g = G.GpuRun(L)
+    ref_out, aux = G.oracle_run(L)
+    kv = aux["kv"]
+    # ---- weights
+    assert np.array_equal(g.wq_code.cpu().numpy(), aux["wq_code"])
+    assert np.array_equal(g.s_wq.cpu().numpy(), aux["s_wq"])
+    assert np.array_equal(g.wo_code.cpu().numpy(), aux["wo_code"])
+    assert np.array_equal(g.s_wo.cpu().numpy(), aux["s_wo"])
+    # ---- K~ / V~ (Eq. 2)
+    assert np.array_equal(g.kv["k_code"].astype(np.int32), kv.k_code)
+    assert np.array_equal(g.kv["v_code"].astype(np.int32), kv.v_code)
+    assert np.array_equal(g.kv["s_K"], kv.s_K)
+    assert np.array_equal(g.kv["s_V"], kv.s_V)
+    for name, full in (("K16", kv.K16), ("V16", kv.V16)):
+        dist = G.fp16_ulp_distance(g.kv[name], full.astype(np.float16))
+        assert dist.max() <= 1, (name, int(dist.max()))
+        assert np.all(g.kv[name][~kv.mask] == 0)
+        if kv.mask.any():
+            assert np.mean(dist[kv.mask] == 0) > 0.98
+    # ---- query side (Eq. 2 third line)
+    assert np.array_equal(g.taps["h_code"].astype(np.int32), aux["h_code"])
+    assert np.array_equal(g.taps["s_h"], aux["s_h"])
+    assert np.array_equal(g.taps["q_code"].astype(np.int32), aux["q_code"])
+    assert np.array_equal(g.taps["s_Q"], aux["s_Q"])
+    # ---- A^ V~ and its codes
+    O_ref = aux["O"]
+    scale_o = max(np.abs(O_ref).max(), 1e-30)
+    dO = np.abs(g.taps["O"].astype(np.float64) - O_ref)
+    frac_far = float(np.mean(dO > 2e-5 * scale_o))
+    dcode = np.abs(g.taps["o_code"].astype(np.int32) - aux["o_code"])
+    print(f"    O: max|d|/max|O|={dO.max() / scale_o:.3e} frac(>2e-5)={frac_far:.3e}  "
+          f"o_code mismatches={float(np.mean(dcode != 0)):.3e} max={int(dcode.max())}", flush=True)
+    assert dO.max() <= 0.02 * scale_o
+    assert frac_far < 5e-3
+    assert dcode.max() <= 1 and np.mean(dcode != 0) < 2e-3
+    assert np.allclose(g.taps["s_o"], aux["s_o"], rtol=2e-2, atol=0)
+    assert np.mean(np.abs(g.taps["s_o"] / aux["s_o"] - 1.0) < 1e-5) > 0.99
+    # ---- block output
+    max_abs, rel_l2 = G.out_errors(g.out, ref_out)
+    print(f"    out: max_abs={max_abs:.3e} rel_l2={rel_l2:.3e}", flush=True)
+    assert np.all(np.isfinite(g.out.astype(np.float32)))
+    assert max_abs <= OUT_MAX_ABS and rel_l2 <= OUT_REL_L2
+    return g
+
+
+def test_quantize_weight_bit_exact_and_edge_rows():
+    from oracle import taq_oracle as O
+    rng = np.random.Generator(np.random.PCG64(5))
+    W = (rng.standard_normal((70, 328)) * 0.05).astype(np.float16)
+    W[3] = 0  # zero row -> scale 1, codes 0
+    W[4, :] = 0
+    W[4, 17] = -0.25  # single non-zero
+    W[5] = np.float16(6e-8)  # fp16 subnormals
+    code, scale = T.taq_quantize_weight(G.dev(W))
+    rc, rs = O.quantize_weight(W)
+    assert np.array_equal(code.cpu().numpy(), rc)
+    assert np.array_equal(scale.cpu().numpy(), rs)
+    assert rs[3] == 1.0 and rc[4, 17] == -127
+
+
+@pytest.mark.parametrize("bits", [8, 4, 16])
+@pytest.mark.parametrize("trig", [(), (5,), (1, 2), tuple(range(3, 43)), "all"])
+def test_small_layer_all_mask_kinds(bits, trig):
+    T_ = 77
+    pos = tuple(range(T_)) if trig == "all" else trig
+    L = synth.make_layer("small", seed=20 + bits + len(pos), B=2, N=200, C=96, H=4, Cc=64, T=T_, bits_kv=bits,
+                         trigger_positions=pos, trigger_scale=3.0, bias=True)
+    check_layer(L, f"small bits={bits} ntrig={len(pos)}")
+
+
+@pytest.mark.parametrize("C,H,N,T_", [
+    (320, 8, 300, 77),   # d = 40 (SD1.5 64x64 layer)
+    (128, 2, 129, 77),   # d = 64 (SDXL heads), one token past a tile
+    (320, 2, 64, 77),    # d = 160 (SD1.5 8x8 layer heads)
+    (160, 2, 33, 33),    # d = 80, T one past a tile
+    (64, 8, 1, 1),       # d = 8, one image token, one text token
+    (96, 1, 127, 96),    # d = 96, the largest T
+    (64, 2, 257, 13),
+])
+@pytest.mark.parametrize("bits", [8, 4])
+def test_head_dims_and_ragged_sizes(C, H, N, T_, bits):
+    trig = (0,) if T_ == 1 else (1, T_ - 1) if T_ > 2 else ()
+    if T_ == 1 and bits == 4:
+        trig = ()
+    L = synth.make_layer("dims", seed=C + N + bits, B=1, N=N, C=C, H=H, Cc=96, T=T_, bits_kv=bits,
+                         trigger_positions=trig, trigger_scale=3.0, outlier_frac=0.02)
+    check_layer(L, f"dims C={C} H={H} N={N} T={T_} bits={bits}")
+
+
+def test_degenerate_values():
+    L = synth.make_layer("degenerate", seed=77, B=2, N=70, C=64, H=2, Cc=64, T=20, bits_kv=8,
+                         trigger_positions=(4,), trigger_scale=3.0)
+    L.hidden[0, 3] = 0  # an all-zero image token: scale 1, codes 0, uniform attention
+    L.hidden[1, 5, :32] = 0  # one head's input half zero (still non-zero Q in general)
+    L.context[0, 7] = 0  # an all-zero text token -> zero K/V rows: scale 1, codes 0
+    L.context[1, 4] = 0  # a zero *trigger* row
+    check_layer(L, "degenerate zeros")
+
+
+def test_small_and_large_magnitudes():
+    # V~ magnitudes far from 1 exercise the power-of-two prescale of the high/low split
+    for scale in (1e-3, 30.0):
+        L = synth.make_layer("mag", seed=91, B=1, N=96, C=64, H=2, Cc=64, T=40, bits_kv=8,
+                             trigger_positions=(2, 9), trigger_scale=3.0)
+        L.Wv = (L.Wv.astype(np.float32) * scale).astype(np.float16)
+        L.Wk = (L.Wk.astype(np.float32) * min(scale, 2.0)).astype(np.float16)
+        check_layer(L, f"magnitude x{scale}")
+
+
+def test_determinism_and_row_independence():
+    L = synth.make_layer("det", seed=31, B=2, N=300, C=320, H=8, Cc=768, T=77, bits_kv=8,
+                         trigger_positions=(5,), outlier_frac=0.01)
+    a = G.GpuRun(L, taps=False)
+    b = G.GpuRun(L, taps=False)
+    assert np.array_equal(a.out.view(np.uint16), b.out.view(np.uint16))
+    # a token's output depends only on its own hidden row: run a slice alone
+    sub = L.hidden[:, 100:170].copy()
+    c = G.GpuRun(L, taps=False, hidden=sub)
+    assert np.array_equal(c.out.view(np.uint16), a.out[:, 100:170].view(np.uint16))
+
+
+def test_batched_requests_match_single_calls():
+    reqs = synth.config5(R=3, N=160)
+    runs = [G.GpuRun(L, taps=False) for L in reqs]
+    s = runs[0].shape
+    table = []
+    outs = []
+    for r in runs:
+        o = torch.zeros_like(r.out_d)
+        outs.append(o)
+        table.append(dict(hidden=r.hidden_d, qkv_packed=r.packed, Wq=r.wq_code, Wo=r.wo_code, scales=r.scales,
+                          trigger_mask=r.mask_d, out=o))
+    T.taq_cross_attn_batched(table, s)
+    torch.cuda.synchronize()
+    for r, o in zip(runs, outs):
+        assert np.array_equal(o.cpu().numpy().view(np.uint16), r.out.view(np.uint16))
+
+
+def test_error_paths_on_device_do_not_launch():
+    s = T.make_shape(B=1, N=8, C=64, H=2, T=5, Cc=64, bits_kv=8)
+    x = torch.zeros(1, 8, 64, dtype=torch.float16, device=G.DEV)
+    with pytest.raises(T.TaqError) as e:
+        T.taq_cross_attn(x, None, None, None, None, None, s)
+    assert e.value.status == T.TAQ_ERR_INVALID_ARG
+    s_bad = T.make_shape(B=1, N=8, C=64, H=2, T=5, Cc=64, bits_kv=8, bits_prob=4)
+    with pytest.raises(T.TaqError) as e:
+        T.taq_workspace_bytes(s_bad)
+    assert e.value.status == T.TAQ_ERR_UNSUPPORTED_BITS
+    torch.cuda.synchronize()
