@@ -43,12 +43,22 @@ def check_layer(L, label=""):
     assert np.array_equal(g.kv["v_code"].astype(np.int32), kv.v_code)
     assert np.array_equal(g.kv["s_K"], kv.s_K)
     assert np.array_equal(g.kv["s_V"], kv.s_V)
-    for name, full in (("K16", kv.K16), ("V16", kv.V16)):
-        dist = G.fp16_ulp_distance(g.kv[name], full.astype(np.float16))
-        assert dist.max() <= 1, (name, int(dist.max()))
+    # protected rows: the kernel sums in float32 (four partial sums of Cc/4 terms, then 3 adds
+    # and the scale multiply), the oracle in float64; both round once to fp16. Allowed gap:
+    # one fp16 step at the value plus the float32 summation bound (Cc/4+4)*2^-24*sum|x_k*w_k|*s_w,
+    # which matters only where the sum cancels to a value much smaller than its terms.
+    absx = np.abs(L.context.astype(np.float64))
+    for name, full, pre in (("K16", kv.K16, "k"), ("V16", kv.V16, "v")):
+        got = g.kv[name].astype(np.float64)
+        absw = np.abs(kv.aux[pre + "_w_code"].astype(np.float64)) * kv.aux[pre + "_s_w"].astype(np.float64)[:, None]
+        sum_abs = np.einsum("btk,ck->btc", absx, absw)
+        step = np.spacing(np.abs(full).astype(np.float16)).astype(np.float64)
+        bound = step + (L.Cc / 4 + 4) * 2.0 ** -24 * sum_abs
+        gap = np.abs(got - full)
+        assert np.all(gap[kv.mask] <= bound[kv.mask]), (name, float((gap - bound)[kv.mask].max()))
         assert np.all(g.kv[name][~kv.mask] == 0)
         if kv.mask.any():
-            assert np.mean(dist[kv.mask] == 0) > 0.98
+            assert np.mean(gap[kv.mask] == 0) > 0.98
     # ---- query side (Eq. 2 third line)
     assert np.array_equal(g.taps["h_code"].astype(np.int32), aux["h_code"])
     assert np.array_equal(g.taps["s_h"], aux["s_h"])
