@@ -17,7 +17,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtaq.so")
-SOURCES = ["taq_api.hip", "taq_quant.hip", "taq_gemm.hip", "taq_attn.hip"]
+SOURCES = ["taq_api.hip", "taq_quant.hip", "taq_gemm.hip", "taq_attn.hip", "taq_fused.hip"]
 
 
 def hipcc_path() -> str:

@@ -115,7 +115,9 @@ int taq_quantize_kv(const void* context, const uint8_t* trigger_mask, const void
     // protected rows in fp16
     TAQ_TRY_HIP(launch_kv_trigger_rows(static_cast<const __half*>(context), w_code, s_w, ntrig, trig_idx, s.B, s.T,
                                        s.C, s.Cc, reinterpret_cast<__half*>(pk + L.k16),
-                                       reinterpret_cast<__half*>(pk + L.v16), st));
+                                       reinterpret_cast<__half*>(pk + L.v16), reinterpret_cast<__half*>(pk + L.v16t), st));
+    // operand-ordered copy of the integer part for the fused block kernel
+    TAQ_TRY_HIP(launch_kv_image(pk, s, st));
     return TAQ_OK;
 }
 
@@ -146,6 +148,14 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
     const float* bias_o = scales + 2 * s.C;
     const int M = s.B * s.N;
     const unsigned stages = (dbg && dbg->stage_mask) ? dbg->stage_mask : ~0u;
+
+    if (fused_supported(s) && !(dbg && dbg->stage_mask)) {
+        // the whole block in one kernel; taps are written by the kernel itself
+        FusedReq rq = {static_cast<const __half*>(hidden), static_cast<const uint8_t*>(qkv_packed), Wq, Wo, scales,
+                       static_cast<__half*>(out)};
+        TAQ_TRY_HIP(launch_fused_block(&rq, 1, s, dbg, st));
+        return TAQ_OK;
+    }
 
     if (stages & TAQ_STAGE_HIDDEN_QUANT)
         TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(hidden), M, s.C, h_code, s_h, st));
@@ -200,6 +210,20 @@ int taq_cross_attn_batched(int R, const taq_request* table, const taq_shape* sha
     {
         taq_shape s = *shape;
         per = attn_workspace(s).total > per ? attn_workspace(s).total : per;
+    }
+    if (fused_supported(*shape)) {
+        // grouped launches: up to 16 requests share one kernel through a pointer table in the arguments
+        for (int r0 = 0; r0 < R; r0 += 16) {
+            FusedReq rq[16];
+            const int n = R - r0 < 16 ? R - r0 : 16;
+            for (int i = 0; i < n; ++i) {
+                const taq_request& q = table[r0 + i];
+                rq[i] = {static_cast<const __half*>(q.hidden), static_cast<const uint8_t*>(q.qkv_packed), q.Wq, q.Wo,
+                         q.scales, static_cast<__half*>(q.out)};
+            }
+            TAQ_TRY_HIP(launch_fused_block(rq, n, *shape, nullptr, static_cast<hipStream_t>(hip_stream)));
+        }
+        return TAQ_OK;
     }
     for (int r = 0; r < R; ++r) {
         const taq_request& q = table[r];

@@ -27,9 +27,55 @@ struct KvLayout {
     size_t v_code;
     size_t k16;       // f16 [B][T][C]  protected rows, compacted by slot
     size_t v16;
+    size_t v16t;      // f16 [B][C][96] protected V rows transposed (slot along the last axis)
+    size_t image;     // [B][image_bytes] LDS-ready K~/V~ image for the fused block kernel (may be empty)
+    size_t image_bytes;
     size_t total;
     int Cb;
 };
+
+// LDS-ready image of the integer part of K~/V~ for one batch element (fused block kernel).
+// Offsets are relative to the image start; every section is a multiple of 16 bytes.
+struct KvImage {
+    int tph;        // 16-channel tiles per head = ceil(d/16)
+    int rows_k;     // 16*ceil(T/16) text-token rows of the K part
+    int cols_v;     // 32*ceil(T/32) token positions per V^T row
+    size_t kp;      // i8  [H][rows_k][tph][4 quarter-lanes][4]  K codes in MFMA operand order
+    size_t vt;      // i8  [H][d][cols_v]   V codes transposed, tokens in accumulator-register order
+    size_t s_k;     // f32 [H][96]  per-(head, token) K scale, 0 on protected / padding tokens
+    size_t s_vp;    // f32 [H][96]  s_V * 2^kexp
+    size_t bias;    // f32 [96]     0 for unprotected tokens, -inf for protected / padding
+    size_t oscale;  // f32 [H]      2^-kexp / 255
+    size_t vpre;    // f32 [H]      2^kexp
+    size_t bytes;
+};
+
+// Shapes the fused block kernel is instantiated for: (d, H) = (40, 8), (80, 8), (64, 10).
+static inline bool fused_supported(const taq_shape& s) {
+    if (s.bits_kv != 4 && s.bits_kv != 8) return false;
+    if (s.C % s.H) return false;
+    const int d = s.C / s.H;
+    return (d == 40 && s.H == 8) || (d == 80 && s.H == 8) || (d == 64 && s.H == 10);
+}
+
+static inline KvImage kv_image(const taq_shape& s) {
+    KvImage I;
+    const size_t H = s.H, d = s.C / s.H;
+    I.tph = (int)((d + 15) / 16);
+    I.rows_k = 16 * ((s.T + 15) / 16);
+    I.cols_v = 32 * ((s.T + 31) / 32);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 16); return o; };
+    I.kp = take(H * I.rows_k * (size_t)I.tph * 16);
+    I.vt = take(H * d * (size_t)I.cols_v);
+    I.s_k = take(H * 96 * 4);
+    I.s_vp = take(H * 96 * 4);
+    I.bias = take(96 * 4);
+    I.oscale = take(H * 4);
+    I.vpre = take(H * 4);
+    I.bytes = off;
+    return I;
+}
 
 static inline KvLayout kv_layout(const taq_shape& s) {
     KvLayout L;
@@ -46,6 +92,9 @@ static inline KvLayout kv_layout(const taq_shape& s) {
     L.v_code = take(B * T * (size_t)L.Cb);
     L.k16 = take(B * T * C * 2);
     L.v16 = take(B * T * C * 2);
+    L.v16t = take(B * C * 96 * 2);
+    L.image_bytes = fused_supported(s) ? align_up(kv_image(s).bytes, 256) : 0;
+    L.image = take(B * L.image_bytes);
     L.total = off;
     return L;
 }
@@ -122,7 +171,7 @@ hipError_t launch_kv_pack(const float* rows_f, const int* slot_of, int B, int T,
 // Protected K/V rows: fp16 context row x int8 weight codes, fp32 accumulate, fp16 store.
 hipError_t launch_kv_trigger_rows(const __half* context, const int8_t* w_code, const float* s_w,
                                   const int* ntrig, const int* trig_idx, int B, int T, int C, int Cc,
-                                  __half* k16, __half* v16, hipStream_t st);
+                                  __half* k16, __half* v16, __half* v16t, hipStream_t st);
 // Expansion of qkv_packed for tests.
 hipError_t launch_kv_unpack(const uint8_t* packed, const taq_shape& s, int8_t* k_codes, int8_t* v_codes,
                             float* k_scales, float* v_scales, __half* k_trig, __half* v_trig, hipStream_t st);
@@ -132,6 +181,21 @@ hipError_t launch_kv_unpack(const uint8_t* packed, const taq_shape& s, int8_t* k
 hipError_t launch_gemm_i8(const int8_t* A, const float* sa, const int8_t* W, const float* sw,
                           const float* bias, int M, int N, int K, float* out_f32, __half* out_f16,
                           int ldo, hipStream_t st);
+
+// K~/V~ image for the fused kernel, from the codes and scales already in qkv_packed.
+hipError_t launch_kv_image(uint8_t* packed, const taq_shape& s, hipStream_t st);
+
+// One request of the fused block kernel.
+struct FusedReq {
+    const __half* hidden;
+    const uint8_t* packed;
+    const int8_t* wq;
+    const int8_t* wo;
+    const float* scales;
+    __half* out;
+};
+// Whole block in one kernel (shapes of fused_supported only). dbg may be NULL.
+hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, const taq_debug* dbg, hipStream_t st);
 
 // Attention core: scores, softmax, Eq. (3), A^ V~ for all (batch, head, token).
 hipError_t launch_attn_core(const int8_t* q_code, const float* s_q, const uint8_t* packed,

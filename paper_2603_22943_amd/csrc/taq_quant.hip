@@ -252,7 +252,8 @@ __global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __re
                                                               const int* __restrict__ ntrig,
                                                               const int* __restrict__ trig_idx, int T, int C,
                                                               int Cc, __half* __restrict__ k16,
-                                                              __half* __restrict__ v16) {
+                                                              __half* __restrict__ v16,
+                                                              __half* __restrict__ v16t) {
     __shared__ float xs[4096];
     const int slot = blockIdx.x, b = blockIdx.y;
     if (slot >= ntrig[b]) return;
@@ -277,16 +278,18 @@ __global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __re
         }
         float sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
         float y = sum * s_w[c];
+        const __half yh = __float2half_rn(y);
         __half* dst = c < C ? k16 : v16;
-        dst[((size_t)b * T + slot) * C + (c < C ? c : c - C)] = __float2half_rn(y);
+        dst[((size_t)b * T + slot) * C + (c < C ? c : c - C)] = yh;
+        if (c >= C) v16t[((size_t)b * C + (c - C)) * 96 + slot] = yh;  // transposed copy, slot along the row
     }
 }
 
 hipError_t launch_kv_trigger_rows(const __half* context, const int8_t* w_code, const float* s_w,
                                   const int* ntrig, const int* trig_idx, int B, int T, int C, int Cc,
-                                  __half* k16, __half* v16, hipStream_t st) {
+                                  __half* k16, __half* v16, __half* v16t, hipStream_t st) {
     hipLaunchKernelGGL(kv_trigger_rows_kernel, dim3(T, B), dim3(256), 0, st, context, w_code, s_w, ntrig,
-                       trig_idx, T, C, Cc, k16, v16);
+                       trig_idx, T, C, Cc, k16, v16, v16t);
     return hipGetLastError();
 }
 

@@ -74,9 +74,14 @@ def check_layer(L, label=""):
           f"o_code mismatches={float(np.mean(dcode != 0)):.3e} max={int(dcode.max())}", flush=True)
     assert dO.max() <= 0.02 * scale_o
     assert frac_far < 5e-3
-    assert dcode.max() <= 1 and np.mean(dcode != 0) < 2e-3
-    assert np.allclose(g.taps["s_o"], aux["s_o"], rtol=2e-2, atol=0)
-    assert np.mean(np.abs(g.taps["s_o"] / aux["s_o"] - 1.0) < 1e-5) > 0.99
+    # an int8 code of O may move by one where O is within rounding of a tie, plus however many
+    # steps a flipped probability code moved O itself (with 4-bit V rows one probability step,
+    # s_V*|v|/255, can exceed one step of O's own grid)
+    assert np.all(dcode <= 1 + np.ceil(dO / aux["s_o"].astype(np.float64)[..., None]))
+    assert dcode.max() <= 3 and np.mean(dcode != 0) < 2e-3
+    # the row maximum is 1-Lipschitz: a token's scale moves by at most its largest |dO| / 127
+    ds = np.abs(g.taps["s_o"].astype(np.float64) - aux["s_o"].astype(np.float64))
+    assert np.all(ds <= dO.max(axis=-1) / 127.0 + 1e-6 * aux["s_o"])
     # ---- block output
     max_abs, rel_l2 = G.out_errors(g.out, ref_out)
     print(f"    out: max_abs={max_abs:.3e} rel_l2={rel_l2:.3e}", flush=True)
@@ -189,3 +194,48 @@ def test_error_paths_on_device_do_not_launch():
         T.taq_workspace_bytes(s_bad)
     assert e.value.status == T.TAQ_ERR_UNSUPPORTED_BITS
     torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- fused single-kernel path
+# (C, H) = (320, 8), (640, 8), (640, 10) run the whole block in one kernel; the tests above
+# already route those shapes through it. These add its mask/length/tail corner cases.
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("trig", [(), (5,), (0, 76), tuple(range(10, 27)), tuple(range(2, 77, 2)), "all"])
+def test_fused_shape_mask_kinds(bits, trig):
+    T_ = 77
+    pos = tuple(range(T_)) if trig == "all" else trig
+    L = synth.make_layer("fused", seed=300 + bits + len(pos), B=2, N=77, C=320, H=8, Cc=64, T=T_, bits_kv=bits,
+                         trigger_positions=pos, trigger_scale=3.0, bias=True, outlier_frac=0.01)
+    check_layer(L, f"fused C=320 bits={bits} ntrig={len(pos)}")
+
+
+@pytest.mark.parametrize("C,H,N,T_", [
+    (320, 8, 1, 1), (320, 8, 31, 13), (320, 8, 33, 16), (320, 8, 64, 17), (320, 8, 95, 33), (320, 8, 130, 96),
+    (640, 8, 45, 77), (640, 10, 70, 77), (640, 10, 32, 50),
+])
+def test_fused_shape_lengths_and_tails(C, H, N, T_):
+    trig = (0,) if T_ == 1 else (1, T_ - 1)
+    L = synth.make_layer("fusedlen", seed=C + H + N + T_, B=1, N=N, C=C, H=H, Cc=64, T=T_, bits_kv=4 if N % 2 else 8,
+                         trigger_positions=trig, trigger_scale=3.0)
+    check_layer(L, f"fused C={C} H={H} N={N} T={T_}")
+
+
+def test_fused_and_general_paths_agree():
+    """The same shape through the single-kernel path and through the kernel-per-stage path
+    (selected by naming every stage explicitly): identical codes, outputs within one code flip."""
+    L = synth.make_layer("both", seed=55, B=2, N=150, C=320, H=8, Cc=768, T=77, bits_kv=8, trigger_positions=(5, 6),
+                         trigger_scale=3.0, outlier_frac=0.01)
+    g = G.GpuRun(L)
+    s = g.shape
+    allbits = (T.TAQ_STAGE_HIDDEN_QUANT | T.TAQ_STAGE_TO_Q | T.TAQ_STAGE_Q_QUANT | T.TAQ_STAGE_ATTN_CORE |
+               T.TAQ_STAGE_O_QUANT | T.TAQ_STAGE_TO_OUT)
+    dbg, taps = T.make_debug(s, G.DEV, stage_mask=allbits)
+    out2 = T.taq_cross_attn(g.hidden_d, g.packed, g.wq_code, g.wo_code, g.scales, g.mask_d, s, debug=dbg)
+    torch.cuda.synchronize()
+    for k in ("h_code", "s_h", "q_code", "s_Q"):
+        assert np.array_equal(taps[k].cpu().numpy(), g.taps[k]), k
+    dcode = np.abs(taps["o_code"].cpu().numpy().astype(np.int32) - g.taps["o_code"].astype(np.int32))
+    assert dcode.max() <= 1 and np.mean(dcode != 0) < 2e-3
+    max_abs, rel_l2 = G.out_errors(out2.cpu().numpy(), g.out)
+    assert max_abs <= 1e-2 and rel_l2 <= 1e-3
