@@ -48,7 +48,7 @@ __device__ __forceinline__ float byte_to_float(unsigned w, int e) { return (floa
 // K~/V~ image builder: rearranges the codes of qkv_packed into the order the fused kernel's MFMA
 // operands are read in, and precomputes the per-head power-of-two prescale of V.
 //   Kp[h][t][tile][q][e]      = k_code[t][h*d + 16*tile + 4*q + e]                (0 outside d / T)
-//   Vt[h][j][32*s + 8*q + 4*a + e] = v_code[t = 32*s + 16*a + 4*q + e][h*d + j]   (0 outside T)
+//   Vt[h][j][32*s + 8*q + 4*a + e] = v_code[t = 32*s + 16*a + 4*q + e][h*d + j] ^ 0x80  (code 0 outside T)
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ int code_at(const uint8_t* codes, size_t row, int C, int c, int bits) {
     if (bits == 8) return (int8_t)codes[row * C + c];
@@ -58,20 +58,19 @@ __device__ __forceinline__ int code_at(const uint8_t* codes, size_t row, int C, 
 
 __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ packed, KvLayout L, KvImage I, int T, int C,
                                                        int H, int bits) {
-    const int b = blockIdx.x, tid = threadIdx.x;
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const int d = C / H;
     const int* slot_of = reinterpret_cast<const int*>(packed + L.slot_of) + b * T;
-    const float* s_k = reinterpret_cast<const float*>(packed + L.s_k) + (size_t)b * H * T;
-    const float* s_v = reinterpret_cast<const float*>(packed + L.s_v) + (size_t)b * H * T;
+    const float* s_k = reinterpret_cast<const float*>(packed + L.s_k) + ((size_t)b * H + h) * T;
+    const float* s_v = reinterpret_cast<const float*>(packed + L.s_v) + ((size_t)b * H + h) * T;
     const uint8_t* k_code = packed + L.k_code;
     const uint8_t* v_code = packed + L.v_code;
     uint8_t* img = packed + L.image + (size_t)b * L.image_bytes;
-    __shared__ float vpre_s[TAQ_MAX_H];
-    // per-head prescale: largest |s_V * code| goes to [256, 512)
-    for (int h = tid; h < H; h += 256) {
+    __shared__ float vpre_s;
+    if (tid == 0) {  // per-head prescale: the largest |s_V * code| goes to [256, 512)
         float smax = 0.f;
         for (int t = 0; t < T; ++t)
-            if (slot_of[t] < 0) smax = fmaxf(smax, s_v[h * T + t]);
+            if (slot_of[t] < 0) smax = fmaxf(smax, s_v[t]);
         int kexp = 0;
         const float dmax = smax * (bits == 4 ? 7.f : 127.f);
         if (dmax > 0.f) {
@@ -79,34 +78,34 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
             (void)frexpf(dmax, &e);
             kexp = 9 - e;
         }
-        vpre_s[h] = ldexpf(1.0f, kexp);
+        vpre_s = ldexpf(1.0f, kexp);
         reinterpret_cast<float*>(img + I.vpre)[h] = ldexpf(1.0f, kexp);
         reinterpret_cast<float*>(img + I.oscale)[h] = ldexpf(1.0f, -kexp) / 255.0f;
     }
     __syncthreads();
-    for (int i = tid; i < H * 96; i += 256) {
-        const int h = i / 96, t = i % 96;
+    for (int t = tid; t < 96; t += 256) {
         const bool isint = t < T && slot_of[t] < 0;
-        reinterpret_cast<float*>(img + I.s_k)[i] = isint ? s_k[h * T + t] : 0.f;
-        reinterpret_cast<float*>(img + I.s_vp)[i] = isint ? s_v[h * T + t] * vpre_s[h] : 0.f;
+        reinterpret_cast<float*>(img + I.s_k)[h * 96 + t] = isint ? s_k[t] : 0.f;
+        reinterpret_cast<float*>(img + I.s_vp)[h * 96 + t] = isint ? s_v[t] * vpre_s : 0.f;
         if (h == 0) reinterpret_cast<float*>(img + I.bias)[t] = isint ? 0.f : TAQ_NEG_INF;
     }
     const int rowb = I.tph * 16;  // bytes per (head, token) row of Kp
-    for (int i = tid; i < H * I.rows_k * rowb; i += 256) {
-        const int e = i & 3, q = (i >> 2) & 3, tile = (i % rowb) >> 4;
-        const int t = (i / rowb) % I.rows_k, h = i / (rowb * I.rows_k);
+    for (int i = tid; i < I.rows_k * rowb; i += 256) {
+        const int e = i & 3, q = (i >> 2) & 3, tile = (i % rowb) >> 4, t = i / rowb;
         const int cl = 16 * tile + 4 * q + e;
         int v = 0;
         if (t < T && cl < d && slot_of[t] < 0) v = code_at(k_code, (size_t)b * T + t, C, h * d + cl, bits);
-        img[I.kp + i] = (uint8_t)(v & 0xFF);
+        img[I.kp + (size_t)h * I.rows_k * rowb + i] = (uint8_t)(v & 0xFF);
     }
-    for (int i = tid; i < H * d * I.cols_v; i += 256) {
-        const int p = i % I.cols_v, j = (i / I.cols_v) % d, h = i / (I.cols_v * d);
+    for (int i = tid; i < d * I.cols_v; i += 256) {
+        const int p = i % I.cols_v, j = i / I.cols_v;
         const int s = p >> 5, q = (p >> 3) & 3, a = (p >> 2) & 1, e = p & 3;
         const int t = 32 * s + 16 * a + 4 * q + e;
         int v = 0;
         if (t < T && slot_of[t] < 0) v = code_at(v_code, (size_t)b * T + t, C, h * d + j, bits);
-        img[I.vt + i] = (uint8_t)(v & 0xFF);
+        // stored with the sign bit flipped (code + 128 as an unsigned byte): 0x6400 | byte is then the
+        // fp16 number 1024 + 128 + code, one packed subtraction away from the code itself
+        img[I.vt + (size_t)h * d * I.cols_v + i] = (uint8_t)((v & 0xFF) ^ 0x80);
     }
 }
 
@@ -114,7 +113,7 @@ hipError_t launch_kv_image(uint8_t* packed, const taq_shape& s, hipStream_t st) 
     const KvLayout L = kv_layout(s);
     if (L.image_bytes == 0) return hipSuccess;
     const KvImage I = kv_image(s);
-    hipLaunchKernelGGL(kv_image_kernel, dim3(s.B), dim3(256), 0, st, packed, L, I, s.T, s.C, s.H, s.bits_kv);
+    hipLaunchKernelGGL(kv_image_kernel, dim3(s.H, s.B), dim3(256), 0, st, packed, L, I, s.T, s.C, s.H, s.bits_kv);
     return hipGetLastError();
 }
 
@@ -134,29 +133,64 @@ struct FusedDims {
     taq_debug dbg;     // taps (NULL pointers = off); only used when R == 1
 };
 
-template <int D, int NW>
+template <int D, int NH>
 struct FusedCfg {
-    static constexpr int H = 2 * NW;
+    static constexpr int H = NH;
     static constexpr int C = D * H;
     static constexpr int TPH = (D + 15) / 16;     // 16-row tiles per head
     static constexpr int KS = (TPH + 3) / 4;      // K steps of 64 for S^T = K~ Q~^T
     static constexpr int FS = (TPH + 1) / 2;      // K steps of 32 for the protected-row scores
     static constexpr int KC = C / 64;             // K steps of 64 for the projections
-    static constexpr int MT = C / (16 * NW);      // 16-row tiles of to_out per wavefront
-    static constexpr int NT = 128 * NW;           // threads
+    static constexpr int NT = 64 * NH;            // threads: one wavefront per head
     static constexpr int TILE_RS = C + 16;        // bytes per token row of the int8 tile
+    // image bytes at T = 96, in 16-byte vectors per thread (register staging of the copy)
+    static constexpr int IMG_MAX = H * 96 * TPH * 16 + H * D * 96 + 2 * H * 96 * 4 + 96 * 4 + 2 * ((H * 4 + 15) / 16 * 16);
+    static constexpr int IMGV = (IMG_MAX / 16 + NT - 1) / NT;
+    static constexpr bool PREFETCH_W = TPH * KC <= 16;  // whole weight slice of a head in registers
 };
 
-template <int D, int NW>
-__global__ __launch_bounds__(128 * NW) void fused_block_kernel(FusedTable tab, FusedDims dm) {
-    using F = FusedCfg<D, NW>;
-    constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, MT = F::MT, NT = F::NT;
+// Symmetric 8-bit codes of four values of one row, packed into a dword (low byte first).
+//   exact definition: code = rint((x * 127) / amax) with IEEE float32 multiply and divide.
+//   fast path: q0 = x * c with c = RN(127 / amax); q0 and the defined quotient both lie within
+//   127 * 2^-23 = 1.52e-5 of the exact ratio, so they round to the same integer unless q0 is within
+//   3.04e-5 of a half-integer; those (rare) lanes redo the four values by the definition.
+//   Rounding uses the 1.5 * 2^23 trick: the low mantissa byte of q0 + magic is the code's byte.
+__device__ __forceinline__ unsigned quant4_i8(float x0, float x1, float x2, float x3, float c, float amax) {
+    const float magic = 12582912.0f;
+    const float q0 = x0 * c, q1 = x1 * c, q2 = x2 * c, q3 = x3 * c;
+    const float m0 = q0 + magic, m1 = q1 + magic, m2 = q2 + magic, m3 = q3 + magic;
+    const float d0 = fabsf(q0 - (m0 - magic)), d1 = fabsf(q1 - (m1 - magic));
+    const float d2 = fabsf(q2 - (m2 - magic)), d3 = fabsf(q3 - (m3 - magic));
+    const unsigned lo = __builtin_amdgcn_perm(__float_as_uint(m1), __float_as_uint(m0), 0x0c0c0400u);
+    const unsigned hi = __builtin_amdgcn_perm(__float_as_uint(m3), __float_as_uint(m2), 0x0c0c0400u);
+    unsigned pk = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+    if (fmaxf(fmaxf(d0, d1), fmaxf(d2, d3)) > 0.49996f)
+        pk = pack4(symq_code_f(x0, 127.f, amax), symq_code_f(x1, 127.f, amax), symq_code_f(x2, 127.f, amax),
+                   symq_code_f(x3, 127.f, amax));
+    return pk;
+}
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+// Four biased bytes (code + 128) -> four fp16 codes: 0x6400 | byte is the fp16 number 1152 + code.
+__device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t& b) {
+    const unsigned lo = __builtin_amdgcn_perm(0x64646464u, w, 0x04010400u);
+    const unsigned hi = __builtin_amdgcn_perm(0x64646464u, w, 0x04030402u);
+    const half2_t off = {(_Float16)1152.0f, (_Float16)1152.0f};
+    a = *reinterpret_cast<const half2_t*>(&lo) - off;
+    b = *reinterpret_cast<const half2_t*>(&hi) - off;
+}
+
+// One wavefront per head, 32 image tokens per workgroup (two column tiles of 16 per wavefront).
+template <int D, int NH>
+__global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, FusedDims dm) {
+    using F = FusedCfg<D, NH>;
+    constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
-    const int tg = wave / NW, hp = wave % NW;
+    const int tid = threadIdx.x, h = tid >> 6, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
     const int RB = dm.R * dm.B;
-    const int rb = blockIdx.x % RB, tile = blockIdx.x / RB;
+    const int rb = blockIdx.x % RB, tile = blockIdx.x / RB;  // batch / request index fastest: one XCD, one K~/V~ image
     const int ri = rb / dm.B, b = rb % dm.B;
     const FusedReq rq = tab.req[ri];
     const int N = dm.N, T = dm.T;
@@ -165,116 +199,139 @@ __global__ __launch_bounds__(128 * NW) void fused_block_kernel(FusedTable tab, F
     // ---- LDS carve-up
     unsigned char* img = smem;                                  // K~/V~ image
     const size_t img_bytes = dm.I.bytes;
-    int8_t* tileq = reinterpret_cast<int8_t*>(smem + img_bytes);              // [32][C+16] h codes, later O codes
+    int8_t* tileq = reinterpret_cast<int8_t*>(smem + img_bytes);                // [32][C+16] hidden codes, later O codes
     float* wsc = reinterpret_cast<float*>(smem + img_bytes + 32 * F::TILE_RS);  // s_wq | s_wo | bias_o  [3C]
     float* s_h = wsc + 3 * C;                                    // [32]
-    float* s_o = s_h + 32;                                       // [32]
-    unsigned* omax = reinterpret_cast<unsigned*>(s_o + 32);      // [32][NW]
+    unsigned* omax = reinterpret_cast<unsigned*>(s_h + 32);      // [32][NH]
 
     const uint8_t* packed = rq.packed;
     const int ntrig = reinterpret_cast<const int*>(packed + dm.L.ntrig)[b];
     const int nfp = (ntrig + 15) >> 4;  // tiles of 16 protected tokens
 
-    // ---- phase 0a: copy the K~/V~ image and the weight scales into LDS
+    // weight rows of this head: row c = h*D + 16*j + r16 (rows past the head are discarded; clamp keeps reads in bounds)
+    int wrow[TPH];
+#pragma unroll
+    for (int j = 0; j < TPH; ++j) {
+        const int c = h * D + 16 * j + r16;
+        wrow[j] = (c < C ? c : C - 1) * C + 16 * q;
+    }
+    int32x4_t wreg[F::PREFETCH_W ? TPH : 1][F::PREFETCH_W ? KC : 1];
+    if (F::PREFETCH_W) {
+#pragma unroll
+        for (int j = 0; j < TPH; ++j)
+#pragma unroll
+            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + 64 * ks);
+    }
+
+    // ---- phase 0: K~/V~ image and weight scales into LDS; per-token int8 codes of the hidden tile
     {
         const uint4* src = reinterpret_cast<const uint4*>(packed + dm.L.image + (size_t)b * dm.L.image_bytes);
-        uint4* dst = reinterpret_cast<uint4*>(img);
         const int nvec = (int)(img_bytes >> 4);
-        for (int i = tid; i < nvec; i += NT) dst[i] = src[i];
+        uint4 iv[F::IMGV];
+#pragma unroll
+        for (int k = 0; k < F::IMGV; ++k) {
+            const int i = tid + k * NT;
+            iv[k] = i < nvec ? src[i] : make_uint4(0, 0, 0, 0);
+        }
         const float4* ssrc = reinterpret_cast<const float4*>(rq.scales);
         float4* sdst = reinterpret_cast<float4*>(wsc);
         for (int i = tid; i < (3 * C) / 4; i += NT) sdst[i] = ssrc[i];
-    }
-    // ---- phase 0b: per-token int8 codes of the hidden tile (8 threads per token)
-    if (tid < 256) {
-        const int tok = tid >> 3, part = tid & 7;
-        const int n = n0 + tok;
-        const size_t row = (size_t)b * N + (n < N ? n : N - 1);
-        const uint4* xr = reinterpret_cast<const uint4*>(rq.hidden + row * C);
-        uint4 v[KC];
+
+        if (tid < 512) {  // 16 threads per token, 4 channels per load
+            const int tok = tid >> 4, part = tid & 15;
+            const int n = n0 + tok;
+            const size_t row = (size_t)b * N + (n < N ? n : N - 1);
+            const uint2* xr = reinterpret_cast<const uint2*>(rq.hidden + row * C);
+            float x[KC][4];
+            float amax = 0.f;
 #pragma unroll
-        for (int it = 0; it < KC; ++it) v[it] = xr[it * 8 + part];
-        float amax = 0.f;
-#pragma unroll
-        for (int it = 0; it < KC; ++it) {
-            const __half2* hh = reinterpret_cast<const __half2*>(&v[it]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float2 p = __half22float2(hh[e]);
-                amax = fmaxf(amax, fmaxf(fabsf(p.x), fabsf(p.y)));
+            for (int it = 0; it < KC; ++it) {
+                const uint2 v = xr[it * 16 + part];
+                const __half2* hh = reinterpret_cast<const __half2*>(&v);
+                const float2 p0 = __half22float2(hh[0]), p1 = __half22float2(hh[1]);
+                x[it][0] = p0.x;
+                x[it][1] = p0.y;
+                x[it][2] = p1.x;
+                x[it][3] = p1.y;
+                amax = fmaxf(amax, fmaxf(fmaxf(fabsf(p0.x), fabsf(p0.y)), fmaxf(fabsf(p1.x), fabsf(p1.y))));
             }
-        }
-        amax = fmaxf(amax, __shfl_xor(amax, 1));
-        amax = fmaxf(amax, __shfl_xor(amax, 2));
-        amax = fmaxf(amax, __shfl_xor(amax, 4));
-        const bool zero = amax == 0.f;
-        const float sc = zero ? 1.f : amax / 127.f;
-        const float safe = zero ? 1.f : amax;
-        if (part == 0) s_h[tok] = sc;
+            amax = fmaxf(amax, __shfl_xor(amax, 1));
+            amax = fmaxf(amax, __shfl_xor(amax, 2));
+            amax = fmaxf(amax, __shfl_xor(amax, 4));
+            amax = fmaxf(amax, __shfl_xor(amax, 8));
+            const bool zero = amax == 0.f;
+            const float sc = zero ? 1.f : amax / 127.f;
+            const float safe = zero ? 1.f : amax;
+            const float cq = 127.f / safe;
+            if (part == 0) s_h[tok] = sc;
 #pragma unroll
-        for (int it = 0; it < KC; ++it) {
-            const __half2* hh = reinterpret_cast<const __half2*>(&v[it]);
-            int c[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float2 p = __half22float2(hh[e]);
-                c[2 * e] = symq_code_f(p.x, 127.f, safe);
-                c[2 * e + 1] = symq_code_f(p.y, 127.f, safe);
+            for (int it = 0; it < KC; ++it) {
+                const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq, safe);
+                *reinterpret_cast<unsigned*>(tileq + tok * F::TILE_RS + (it * 16 + part) * 4) = pk;
+                if (dm.dbg.h_code && n < N) *reinterpret_cast<unsigned*>(dm.dbg.h_code + row * C + (it * 16 + part) * 4) = pk;
             }
-            uint2 o;
-            o.x = pack4(c[0], c[1], c[2], c[3]);
-            o.y = pack4(c[4], c[5], c[6], c[7]);
-            *reinterpret_cast<uint2*>(tileq + tok * F::TILE_RS + (it * 8 + part) * 8) = o;
-            if (dm.dbg.h_code && n < N) *reinterpret_cast<uint2*>(dm.dbg.h_code + row * C + (it * 8 + part) * 8) = o;
+            if (dm.dbg.s_h && part == 0 && n < N) dm.dbg.s_h[row] = sc;
         }
-        if (dm.dbg.s_h && part == 0 && n < N) dm.dbg.s_h[row] = sc;
+        uint4* dst = reinterpret_cast<uint4*>(img);
+#pragma unroll
+        for (int k = 0; k < F::IMGV; ++k) {
+            const int i = tid + k * NT;
+            if (i < nvec) dst[i] = iv[k];
+        }
     }
     __syncthreads();
 
-    // ---- this lane's image token
-    const int tl = tg * 16 + r16;           // token within the tile
-    const int n = n0 + tl;
-    const bool nvalid = n < N;
-    const size_t tok = (size_t)b * N + (nvalid ? n : N - 1);
-    const float sh = s_h[tl];
     const float* swq = wsc;
     const float* swo = wsc + C;
     const float* bo = wsc + 2 * C;
-
-    // B operand of to_q: this token's hidden codes, 16 bytes per K step
-    int32x4_t hb[KC];
-#pragma unroll
-    for (int ks = 0; ks < KC; ++ks) hb[ks] = *reinterpret_cast<const int32x4_t*>(tileq + tl * F::TILE_RS + 64 * ks + 16 * q);
-
-    const float* img_sk = reinterpret_cast<const float*>(img + dm.I.s_k);
-    const float* img_svp = reinterpret_cast<const float*>(img + dm.I.s_vp);
+    const float* img_sk = reinterpret_cast<const float*>(img + dm.I.s_k) + h * 96;
+    const float* img_svp = reinterpret_cast<const float*>(img + dm.I.s_vp) + h * 96;
     const float* img_bias = reinterpret_cast<const float*>(img + dm.I.bias);
-    const float* img_oscale = reinterpret_cast<const float*>(img + dm.I.oscale);
-    const float* img_vpre = reinterpret_cast<const float*>(img + dm.I.vpre);
     const __half* k16 = reinterpret_cast<const __half*>(packed + dm.L.k16) + (size_t)b * T * C;
     const __half* v16t = reinterpret_cast<const __half*>(packed + dm.L.v16t) + (size_t)b * C * 96;
 
-    float oval[2][TPH][4];  // A^ V~ of this wavefront's two heads: channel h*D + 16*jt + 4*q + i
-    float omx = 0.f;
+    // this lane's two image tokens: tile rows r16 and 16 + r16
+    bool nvalid[2];
+    size_t tok[2];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const int n = n0 + 16 * nt + r16;
+        nvalid[nt] = n < N;
+        tok[nt] = (size_t)b * N + (n < N ? n : N - 1);
+    }
 
+    // ================= to_q for this head: Qf^T[c][n]
+    int32x4_t hb[2][KC];
 #pragma unroll
-    for (int hl = 0; hl < 2; ++hl) {
-        const int h = 2 * hp + hl;
-        // ================= to_q for this head: Qf^T[c][n], c = h*D + 16*j + (row of tile)
-        int32x4_t qacc[TPH];
+    for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-        for (int j = 0; j < TPH; ++j) {
-            qacc[j] = (int32x4_t){0, 0, 0, 0};
-            int c = h * D + 16 * j + r16;
-            c = c < C ? c : C - 1;  // rows past the head are discarded; keep the read in bounds
-            const int8_t* wr = rq.wq + (size_t)c * C + 16 * q;
+        for (int ks = 0; ks < KC; ++ks)
+            hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
+    int32x4_t pacc[2][TPH];
 #pragma unroll
-            for (int ks = 0; ks < KC; ++ks) {
-                const int32x4_t wa = *reinterpret_cast<const int32x4_t*>(wr + 64 * ks);
-                qacc[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[ks], qacc[j], 0, 0, 0);
-            }
+    for (int j = 0; j < TPH; ++j) {
+        pacc[0][j] = (int32x4_t){0, 0, 0, 0};
+        pacc[1][j] = (int32x4_t){0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KC; ++ks) {
+            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + 64 * ks);
+            pacc[0][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[0][ks], pacc[0][j], 0, 0, 0);
+            pacc[1][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[1][ks], pacc[1][j], 0, 0, 0);
         }
-        // ---- Eq. (2), third line: Q~ = Q_a(Q) per (token, head)
+    }
+    if (F::PREFETCH_W) {  // to_out's weight slice travels while the attention runs
+#pragma unroll
+        for (int j = 0; j < TPH; ++j)
+#pragma unroll
+            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + 64 * ks);
+    }
+
+    // ---- Eq. (2), third line: Q~ = Q_a(Q) per (token, head)
+    unsigned qpk[2][TPH];
+    float sq2[2];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const float sh = s_h[16 * nt + r16];
         float qf[TPH][4];
         float qmax = 0.f;
 #pragma unroll
@@ -286,7 +343,7 @@ __global__ __launch_bounds__(128 * NW) void fused_block_kernel(FusedTable tab, F
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float sc = sh * wv[i];
-                const float v = (float)qacc[j][i] * sc;
+                const float v = (float)pacc[nt][j][i] * sc;
                 qf[j][i] = valid ? v : 0.f;
                 qmax = fmaxf(qmax, fabsf(qf[j][i]));
             }
@@ -296,32 +353,33 @@ __global__ __launch_bounds__(128 * NW) void fused_block_kernel(FusedTable tab, F
         const bool qzero = qmax == 0.f;
         const float sQ = qzero ? 1.f : qmax / 127.f;
         const float qsafe = qzero ? 1.f : qmax;
-        unsigned qpk[TPH];
+        const float cq = 127.f / qsafe;
 #pragma unroll
-        for (int j = 0; j < TPH; ++j)
-            qpk[j] = pack4(symq_code_f(qf[j][0], 127.f, qsafe), symq_code_f(qf[j][1], 127.f, qsafe),
-                           symq_code_f(qf[j][2], 127.f, qsafe), symq_code_f(qf[j][3], 127.f, qsafe));
-        if (dm.dbg.q_code && nvalid) {
+        for (int j = 0; j < TPH; ++j) qpk[nt][j] = quant4_i8(qf[j][0], qf[j][1], qf[j][2], qf[j][3], cq, qsafe);
+        if (dm.dbg.q_code && nvalid[nt]) {
 #pragma unroll
             for (int j = 0; j < TPH; ++j)
-                if (16 * j + 4 * q < D) *reinterpret_cast<unsigned*>(dm.dbg.q_code + tok * C + h * D + 16 * j + 4 * q) = qpk[j];
-            if (dm.dbg.s_Q && q == 0) dm.dbg.s_Q[tok * H + h] = sQ;
+                if (16 * j + 4 * q < D) *reinterpret_cast<unsigned*>(dm.dbg.q_code + tok[nt] * C + h * D + 16 * j + 4 * q) = qpk[nt][j];
+            if (dm.dbg.s_Q && q == 0) dm.dbg.s_Q[tok[nt] * H + h] = sQ;
         }
-        // B operand of the score MFMAs: dword jj of step ks = codes of tile 4*ks + jj
-        int32x4_t qop[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) qop[ks][jj] = (4 * ks + jj < TPH) ? (int)qpk[4 * ks + jj] : 0;
+        sq2[nt] = fmaxf(sQ * dm.sig2, 1e-37f);
+    }
 
-        // ================= scores in the log2 domain: S^T[t][n]
-        const float sq2 = sQ * dm.sig2;
-        float S[6][4], Sf[6][4];
+    // ================= scores: x[t][n] = (K~ Q~^T)[t][n] * s_K[t]   (times sQ * sigma * log2 e later)
+    float S[2][6][4], Sf[2][6][4];
+    {
+        int32x4_t qop[2][KS];  // B operand: dword jj of step ks = codes of tile 4*ks + jj
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) qop[nt][ks][jj] = (4 * ks + jj < TPH) ? (int)qpk[nt][4 * ks + jj] : 0;
         const int8_t* kp = reinterpret_cast<const int8_t*>(img + dm.I.kp) + (size_t)h * dm.I.rows_k * (TPH * 16);
 #pragma unroll
         for (int tt = 0; tt < 6; ++tt) {
             if (tt < dm.nt16) {
-                int32x4_t acc = (int32x4_t){0, 0, 0, 0};
+                int32x4_t a0 = (int32x4_t){0, 0, 0, 0}, a1 = (int32x4_t){0, 0, 0, 0};
                 const int8_t* krow = kp + (16 * tt + r16) * (TPH * 16) + 4 * q;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
@@ -329,33 +387,37 @@ __global__ __launch_bounds__(128 * NW) void fused_block_kernel(FusedTable tab, F
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj)
                         ka[jj] = (4 * ks + jj < TPH) ? *reinterpret_cast<const int*>(krow + 16 * (4 * ks + jj)) : 0;
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(ka, qop[ks], acc, 0, 0, 0);
+                    a0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(ka, qop[0][ks], a0, 0, 0, 0);
+                    a1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(ka, qop[1][ks], a1, 0, 0, 0);
                 }
-                const float4 sk = *reinterpret_cast<const float4*>(img_sk + h * 96 + 16 * tt + 4 * q);
+                const float4 sk = *reinterpret_cast<const float4*>(img_sk + 16 * tt + 4 * q);
                 const float4 bi = *reinterpret_cast<const float4*>(img_bias + 16 * tt + 4 * q);
-                S[tt][0] = __builtin_fmaf((float)acc[0], sq2 * sk.x, bi.x);
-                S[tt][1] = __builtin_fmaf((float)acc[1], sq2 * sk.y, bi.y);
-                S[tt][2] = __builtin_fmaf((float)acc[2], sq2 * sk.z, bi.z);
-                S[tt][3] = __builtin_fmaf((float)acc[3], sq2 * sk.w, bi.w);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) S[tt][i] = TAQ_NEG_INF;
+                S[0][tt][0] = __builtin_fmaf((float)a0[0], sk.x, bi.x);
+                S[0][tt][1] = __builtin_fmaf((float)a0[1], sk.y, bi.y);
+                S[0][tt][2] = __builtin_fmaf((float)a0[2], sk.z, bi.z);
+                S[0][tt][3] = __builtin_fmaf((float)a0[3], sk.w, bi.w);
+                S[1][tt][0] = __builtin_fmaf((float)a1[0], sk.x, bi.x);
+                S[1][tt][1] = __builtin_fmaf((float)a1[1], sk.y, bi.y);
+                S[1][tt][2] = __builtin_fmaf((float)a1[2], sk.z, bi.z);
+                S[1][tt][3] = __builtin_fmaf((float)a1[3], sk.w, bi.w);
             }
         }
         // protected rows: fp16 K rows straight from global memory (a handful of rows)
         if (nfp > 0) {
-            half8_t qh[FS];  // Q~ codes as fp16: step s covers tiles 2s, 2s+1
+            half8_t qh[2][FS];  // Q~ codes as fp16: step s covers tiles 2s, 2s+1
 #pragma unroll
-            for (int s = 0; s < FS; ++s)
+            for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int j = 2 * s + (e >> 2);
-                    qh[s][e] = (j < TPH) ? (_Float16)byte_to_float(qpk[j < TPH ? j : 0], e & 3) : (_Float16)0.f;
+                for (int s = 0; s < FS; ++s) {
+                    half2_t c0 = {(_Float16)0.f, (_Float16)0.f}, c1 = c0, c2 = c0, c3 = c0;
+                    biased4_to_half(qpk[nt][2 * s] ^ 0x80808080u, c0, c1);
+                    if (2 * s + 1 < TPH) biased4_to_half(qpk[nt][2 * s + 1 < TPH ? 2 * s + 1 : 0] ^ 0x80808080u, c2, c3);
+                    qh[nt][s] = (half8_t){c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
                 }
 #pragma unroll
             for (int ft = 0; ft < 6; ++ft) {
                 if (ft < nfp) {
-                    floatx4_t acc = (floatx4_t){0.f, 0.f, 0.f, 0.f};
+                    floatx4_t a0 = (floatx4_t){0.f, 0.f, 0.f, 0.f}, a1 = a0;
                     const int slot = 16 * ft + r16;
                     const __half* kr = k16 + (size_t)(slot < ntrig ? slot : 0) * C + h * D + 4 * q;
 #pragma unroll
@@ -372,200 +434,242 @@ __global__ __launch_bounds__(128 * NW) void fused_block_kernel(FusedTable tab, F
                             ka[4 * jj + 2] = hv[2];
                             ka[4 * jj + 3] = hv[3];
                         }
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qh[s], acc, 0, 0, 0);
+                        a0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qh[0][s], a0, 0, 0, 0);
+                        a1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qh[1][s], a1, 0, 0, 0);
                     }
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) Sf[ft][i] = (16 * ft + 4 * q + i < ntrig) ? acc[i] * sq2 : TAQ_NEG_INF;
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) Sf[ft][i] = TAQ_NEG_INF;
+                    for (int i = 0; i < 4; ++i) {
+                        const bool live = 16 * ft + 4 * q + i < ntrig;
+                        Sf[0][ft][i] = live ? a0[i] : TAQ_NEG_INF;
+                        Sf[1][ft][i] = live ? a1[i] : TAQ_NEG_INF;
+                    }
                 }
             }
-        } else {
-#pragma unroll
-            for (int ft = 0; ft < 6; ++ft)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) Sf[ft][i] = TAQ_NEG_INF;
         }
+    }
 
-        // ================= softmax over the text tokens of this image token
+    // ================= softmax over the text tokens; Eq. (3); weights of O^T = V~^T A^^T
+    float kq[2];  // 255 / Z per image token
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
         float mx = TAQ_NEG_INF;
 #pragma unroll
         for (int tt = 0; tt < 6; ++tt)
+            if (tt < dm.nt16) mx = fmaxf(mx, fmaxf(fmaxf(S[nt][tt][0], S[nt][tt][1]), fmaxf(S[nt][tt][2], S[nt][tt][3])));
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mx = fmaxf(mx, fmaxf(S[tt][i], Sf[tt][i]));
+        for (int ft = 0; ft < 6; ++ft)
+            if (ft < nfp) mx = fmaxf(mx, fmaxf(fmaxf(Sf[nt][ft][0], Sf[nt][ft][1]), fmaxf(Sf[nt][ft][2], Sf[nt][ft][3])));
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float sc = sq2[nt], off = -mx * sc;
         float Z = 0.f;
 #pragma unroll
         for (int tt = 0; tt < 6; ++tt)
+            if (tt < dm.nt16) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                S[tt][i] = __builtin_amdgcn_exp2f(S[tt][i] - mx);
-                Sf[tt][i] = __builtin_amdgcn_exp2f(Sf[tt][i] - mx);
-                Z += S[tt][i] + Sf[tt][i];
+                for (int i = 0; i < 4; ++i) {
+                    S[nt][tt][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[nt][tt][i], sc, off));
+                    Z += S[nt][tt][i];
+                }
+            }
+#pragma unroll
+        for (int ft = 0; ft < 6; ++ft)
+            if (ft < nfp) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    Sf[nt][ft][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(Sf[nt][ft][i], sc, off));
+                    Z += Sf[nt][ft][i];
+                }
             }
         Z += __shfl_xor(Z, 16);
         Z += __shfl_xor(Z, 32);
-        const float inv = 1.0f / Z;
+        kq[nt] = 255.0f * __builtin_amdgcn_rcpf(Z);
+    }
 
-        // ================= O^T = V~^T A^^T
-        floatx4_t oacc[TPH];
+    floatx4_t oacc[2][TPH];
 #pragma unroll
-        for (int jt = 0; jt < TPH; ++jt) oacc[jt] = (floatx4_t){0.f, 0.f, 0.f, 0.f};
-        if (nfp > 0) {
-            // protected columns keep A (Eq. 3): 255*A as fp16 high + low parts against the fp16 V row
+    for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int ft = 0; ft < 6; ++ft) {
-                if (ft < nfp) {
-                    half4_t phi, plo;
+        for (int jt = 0; jt < TPH; ++jt) oacc[nt][jt] = (floatx4_t){0.f, 0.f, 0.f, 0.f};
+    if (nfp > 0) {
+        // protected columns keep A (Eq. 3): 255*A as fp16 high + low parts against the fp16 V row
+#pragma unroll
+        for (int ft = 0; ft < 6; ++ft) {
+            if (ft < nfp) {
+                half4_t phi[2], plo[2];
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float x = (Sf[ft][i] * inv) * 255.0f;
+                        const float x = Sf[nt][ft][i] * kq[nt];
                         const _Float16 xh = (_Float16)x;
-                        phi[i] = xh;
-                        plo[i] = (_Float16)(x - (float)xh);
+                        phi[nt][i] = xh;
+                        plo[nt][i] = (_Float16)(x - (float)xh);
                     }
 #pragma unroll
-                    for (int jt = 0; jt < TPH; ++jt) {
-                        int c = h * D + 16 * jt + r16;
-                        c = c < C ? c : C - 1;
-                        const __half* vr = v16t + (size_t)c * 96 + 16 * ft + 4 * q;
-                        uint2 w = *reinterpret_cast<const uint2*>(vr);
-                        half4_t va = *reinterpret_cast<const half4_t*>(&w);
+                for (int jt = 0; jt < TPH; ++jt) {
+                    int c = h * D + 16 * jt + r16;
+                    c = c < C ? c : C - 1;
+                    const uint2 w = *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 16 * ft + 4 * q);
+                    half4_t va = *reinterpret_cast<const half4_t*>(&w);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if (16 * ft + 4 * q + i >= ntrig) va[i] = (_Float16)0.f;  // unwritten slots
-                        oacc[jt] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, phi, oacc[jt], 0, 0, 0);
-                        oacc[jt] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, plo, oacc[jt], 0, 0, 0);
+                    for (int i = 0; i < 4; ++i)
+                        if (16 * ft + 4 * q + i >= ntrig) va[i] = (_Float16)0.f;  // slots never written
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt) {
+                        oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, phi[nt], oacc[nt][jt], 0, 0, 0);
+                        oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, plo[nt], oacc[nt][jt], 0, 0, 0);
                     }
                 }
             }
-            const float vpre = img_vpre[h];
+        }
+        const float vpre = reinterpret_cast<const float*>(img + dm.I.vpre)[h];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
             for (int jt = 0; jt < TPH; ++jt)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) oacc[jt][i] *= vpre;
-        }
-        // unprotected columns: weight = code * (s_V * 2^kexp), split into fp16 high + low parts;
-        // V codes are exact in fp16
-        const int8_t* vt = reinterpret_cast<const int8_t*>(img + dm.I.vt) + (size_t)h * D * dm.I.cols_v;
+                for (int i = 0; i < 4; ++i) oacc[nt][jt][i] *= vpre;
+    }
+    // unprotected columns: weight = code * (s_V * 2^kexp), split into fp16 high + low parts; V codes exact in fp16
+    {
+        const uint8_t* vt = img + dm.I.vt + (size_t)h * D * dm.I.cols_v;
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             if (2 * s < dm.nt16) {
-                half8_t phi, plo;
+                const bool second = 2 * s + 1 < dm.nt16;
+                half8_t phi[2], plo[2];
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
-                    const float4 sv = *reinterpret_cast<const float4*>(img_svp + h * 96 + 16 * (2 * s + a) + 4 * q);
+                    const float4 sv = *reinterpret_cast<const float4*>(img_svp + 16 * (2 * s + a) + 4 * q);
                     const float svv[4] = {sv.x, sv.y, sv.z, sv.w};
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float code = __builtin_rintf((S[2 * s + a][i] * inv) * 255.0f);  // Eq. (3)
-                        const float w = code * svv[i];
-                        const _Float16 wh = (_Float16)w;
-                        phi[4 * a + i] = wh;
-                        plo[4 * a + i] = (_Float16)(w - (float)wh);
-                    }
+                    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            float w = 0.f;
+                            if (a == 0 || second) w = __builtin_rintf(S[nt][2 * s + a][i] * kq[nt]) * svv[i];  // Eq. (3)
+                            const _Float16 wh = (_Float16)w;
+                            phi[nt][4 * a + i] = wh;
+                            plo[nt][4 * a + i] = (_Float16)(w - (float)wh);
+                        }
                 }
 #pragma unroll
                 for (int jt = 0; jt < TPH; ++jt) {
                     int j = 16 * jt + r16;
                     j = j < D ? j : D - 1;
                     const uint2 w = *reinterpret_cast<const uint2*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 8 * q);
-                    half8_t va;
+                    half2_t v0, v1, v2, v3;
+                    biased4_to_half(w.x, v0, v1);
+                    biased4_to_half(w.y, v2, v3);
+                    const half8_t va = {v0[0], v0[1], v1[0], v1[1], v2[0], v2[1], v3[0], v3[1]};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        va[e] = (_Float16)byte_to_float(w.x, e);
-                        va[4 + e] = (_Float16)byte_to_float(w.y, e);
+                    for (int nt = 0; nt < 2; ++nt) {
+                        oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, phi[nt], oacc[nt][jt], 0, 0, 0);
+                        oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, plo[nt], oacc[nt][jt], 0, 0, 0);
                     }
-                    oacc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, phi, oacc[jt], 0, 0, 0);
-                    oacc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, plo, oacc[jt], 0, 0, 0);
                 }
             }
         }
-        const float osc = img_oscale[h];
+    }
+
+    // ================= per-token int8 codes of O over all heads
+    const float osc = reinterpret_cast<const float*>(img + dm.I.oscale)[h];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        float omx = 0.f;
 #pragma unroll
         for (int jt = 0; jt < TPH; ++jt) {
             const bool valid = 16 * jt + 4 * q < D;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float v = valid ? oacc[jt][i] * osc : 0.f;
-                oval[hl][jt][i] = v;
-                omx = fmaxf(omx, fabsf(v));
+                oacc[nt][jt][i] = valid ? oacc[nt][jt][i] * osc : 0.f;
+                omx = fmaxf(omx, fabsf(oacc[nt][jt][i]));
             }
-            if (dm.dbg.O && nvalid && valid)
-                *reinterpret_cast<float4*>(dm.dbg.O + tok * C + h * D + 16 * jt + 4 * q) =
-                    make_float4(oval[hl][jt][0], oval[hl][jt][1], oval[hl][jt][2], oval[hl][jt][3]);
+            if (dm.dbg.O && nvalid[nt] && valid)
+                *reinterpret_cast<float4*>(dm.dbg.O + tok[nt] * C + h * D + 16 * jt + 4 * q) =
+                    make_float4(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3]);
         }
+        omx = fmaxf(omx, __shfl_xor(omx, 16));
+        omx = fmaxf(omx, __shfl_xor(omx, 32));
+        if (q == 0) omax[(16 * nt + r16) * NH + h] = __float_as_uint(omx);
     }
-
-    // ================= per-token int8 codes of O over all heads
-    omx = fmaxf(omx, __shfl_xor(omx, 16));
-    omx = fmaxf(omx, __shfl_xor(omx, 32));
-    if (q == 0) omax[tl * NW + hp] = __float_as_uint(omx);
     __syncthreads();  // every wavefront is past its reads of the hidden codes
-    float oamax = 0.f;
+    float so[2];
 #pragma unroll
-    for (int w = 0; w < NW; ++w) oamax = fmaxf(oamax, __uint_as_float(omax[tl * NW + w]));
-    const bool ozero = oamax == 0.f;
-    const float so = ozero ? 1.f : oamax / 127.f;
-    const float osafe = ozero ? 1.f : oamax;
+    for (int nt = 0; nt < 2; ++nt) {
+        float oamax = 0.f;
 #pragma unroll
-    for (int hl = 0; hl < 2; ++hl)
+        for (int w = 0; w < NH; ++w) oamax = fmaxf(oamax, __uint_as_float(omax[(16 * nt + r16) * NH + w]));
+        const bool ozero = oamax == 0.f;
+        so[nt] = ozero ? 1.f : oamax / 127.f;
+        const float osafe = ozero ? 1.f : oamax;
+        const float cq = 127.f / osafe;
 #pragma unroll
         for (int jt = 0; jt < TPH; ++jt)
             if (16 * jt + 4 * q < D) {
-                const unsigned pk = pack4(symq_code_f(oval[hl][jt][0], 127.f, osafe), symq_code_f(oval[hl][jt][1], 127.f, osafe),
-                                          symq_code_f(oval[hl][jt][2], 127.f, osafe), symq_code_f(oval[hl][jt][3], 127.f, osafe));
-                const int c = (2 * hp + hl) * D + 16 * jt + 4 * q;
-                *reinterpret_cast<unsigned*>(tileq + tl * F::TILE_RS + c) = pk;
-                if (dm.dbg.o_code && nvalid) *reinterpret_cast<unsigned*>(dm.dbg.o_code + tok * C + c) = pk;
+                const unsigned pk = quant4_i8(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3], cq, osafe);
+                const int c = h * D + 16 * jt + 4 * q;
+                *reinterpret_cast<unsigned*>(tileq + (16 * nt + r16) * F::TILE_RS + c) = pk;
+                if (dm.dbg.o_code && nvalid[nt]) *reinterpret_cast<unsigned*>(dm.dbg.o_code + tok[nt] * C + c) = pk;
             }
-    if (dm.dbg.s_o && nvalid && q == 0 && hp == 0) dm.dbg.s_o[tok] = so;
+        if (dm.dbg.s_o && nvalid[nt] && q == 0 && h == 0) dm.dbg.s_o[tok[nt]] = so[nt];
+    }
     __syncthreads();
 
-    // ================= to_out: Y^T[c][n], c in this wavefront's quarter of the channels
+    // ================= to_out: Y^T[c][n] for this head's D output channels
 #pragma unroll
-    for (int ks = 0; ks < KC; ++ks) hb[ks] = *reinterpret_cast<const int32x4_t*>(tileq + tl * F::TILE_RS + 64 * ks + 16 * q);
-    __half* orow = rq.out + tok * C;
+    for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int c0 = (C / NW) * hp + 16 * mt;
-        const int8_t* wr = rq.wo + (size_t)(c0 + r16) * C + 16 * q;
-        int32x4_t acc = (int32x4_t){0, 0, 0, 0};
+        for (int ks = 0; ks < KC; ++ks)
+            hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
+#pragma unroll
+    for (int j = 0; j < TPH; ++j) {
+        pacc[0][j] = (int32x4_t){0, 0, 0, 0};
+        pacc[1][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < KC; ++ks) {
-            const int32x4_t wa = *reinterpret_cast<const int32x4_t*>(wr + 64 * ks);
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[ks], acc, 0, 0, 0);
+            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + 64 * ks);
+            pacc[0][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[0][ks], pacc[0][j], 0, 0, 0);
+            pacc[1][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[1][ks], pacc[1][j], 0, 0, 0);
         }
-        const int c = c0 + 4 * q;
-        const float4 w4 = *reinterpret_cast<const float4*>(swo + c);
-        const float4 b4 = *reinterpret_cast<const float4*>(bo + c);
-        const float y0 = (float)acc[0] * (so * w4.x) + b4.x;
-        const float y1 = (float)acc[1] * (so * w4.y) + b4.y;
-        const float y2 = (float)acc[2] * (so * w4.z) + b4.z;
-        const float y3 = (float)acc[3] * (so * w4.w) + b4.w;
-        if (nvalid) {
-            half4_t y = {(_Float16)y0, (_Float16)y1, (_Float16)y2, (_Float16)y3};
-            *reinterpret_cast<half4_t*>(orow + c) = y;
+    }
+#pragma unroll
+    for (int j = 0; j < TPH; ++j) {
+        const int cl = 16 * j + 4 * q;
+        if (cl < D) {
+            const int c = h * D + cl;
+            const float4 w4 = *reinterpret_cast<const float4*>(swo + c);
+            const float4 b4 = *reinterpret_cast<const float4*>(bo + c);
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const float y0 = (float)pacc[nt][j][0] * (so[nt] * w4.x) + b4.x;
+                const float y1 = (float)pacc[nt][j][1] * (so[nt] * w4.y) + b4.y;
+                const float y2 = (float)pacc[nt][j][2] * (so[nt] * w4.z) + b4.z;
+                const float y3 = (float)pacc[nt][j][3] * (so[nt] * w4.w) + b4.w;
+                if (nvalid[nt]) {
+                    const half4_t y = {(_Float16)y0, (_Float16)y1, (_Float16)y2, (_Float16)y3};
+                    *reinterpret_cast<half4_t*>(rq.out + tok[nt] * C + c) = y;
+                }
+            }
         }
     }
 }
 
-template <int D, int NW>
+template <int D, int NH>
 static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
-    using F = FusedCfg<D, NW>;
+    using F = FusedCfg<D, NH>;
     static bool attr_set = false;
-    const size_t bytes = dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 * 2 + 32 * NW * 4;
-    if (bytes > 160 * 1024) return hipErrorInvalidValue;
+    const size_t bytes = dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 + 32 * NH * 4;
+    if (bytes > 160 * 1024 || dm.I.bytes > (size_t)F::IMGV * F::NT * 16) return hipErrorInvalidValue;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles = (dm.N + 31) / 32;
-    hipLaunchKernelGGL((fused_block_kernel<D, NW>), dim3(tiles * dm.R * dm.B), dim3(F::NT), bytes, st, tab, dm);
+    hipLaunchKernelGGL((fused_block_kernel<D, NH>), dim3(tiles * dm.R * dm.B), dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 
@@ -586,9 +690,9 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.I = kv_image(s);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
     dm.dbg = (dbg && R == 1) ? *dbg : none;
-    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 4>(tab, dm, st);
-    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 4>(tab, dm, st);
-    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 5>(tab, dm, st);
+    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8>(tab, dm, st);
+    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8>(tab, dm, st);
+    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10>(tab, dm, st);
     return hipErrorInvalidValue;
 }
 
