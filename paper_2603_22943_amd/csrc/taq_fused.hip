@@ -47,8 +47,8 @@ __device__ __forceinline__ float byte_to_float(unsigned w, int e) { return (floa
 // ------------------------------------------------------------------------------------------
 // K~/V~ image builder: rearranges the codes of qkv_packed into the order the fused kernel's MFMA
 // operands are read in, and precomputes the per-head power-of-two prescale of V.
-//   Kp[h][t][tile][q][e]      = k_code[t][h*d + 16*tile + 4*q + e]                (0 outside d / T)
-//   Vt[h][j][32*s + 8*q + 4*a + e] = v_code[t = 32*s + 16*a + 4*q + e][h*d + j] ^ 0x80  (code 0 outside T)
+//   per head h:  Kp[t][tile][q][e] = k_code[t][h*d + 16*tile + 4*q + e]         (0 outside d / T)
+//                Vt[j][32*s + 8*q + 4*a + e] = v_code[t = 32*s + 16*a + 4*q + e][h*d + j] ^ 0x80
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ int code_at(const uint8_t* codes, size_t row, int C, int c, int bits) {
     if (bits == 8) return (int8_t)codes[row * C + c];
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
     const float* s_v = reinterpret_cast<const float*>(packed + L.s_v) + ((size_t)b * H + h) * T;
     const uint8_t* k_code = packed + L.k_code;
     const uint8_t* v_code = packed + L.v_code;
-    uint8_t* img = packed + L.image + (size_t)b * L.image_bytes;
+    uint8_t* img = packed + L.image + (size_t)b * L.image_bytes + (size_t)h * I.head_bytes;  // this head's block
     __shared__ float vpre_s;
     if (tid == 0) {  // per-head prescale: the largest |s_V * code| goes to [256, 512)
         float smax = 0.f;
@@ -79,15 +79,15 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
             kexp = 9 - e;
         }
         vpre_s = ldexpf(1.0f, kexp);
-        reinterpret_cast<float*>(img + I.vpre)[h] = ldexpf(1.0f, kexp);
-        reinterpret_cast<float*>(img + I.oscale)[h] = ldexpf(1.0f, -kexp) / 255.0f;
+        reinterpret_cast<float*>(img + I.vpre)[0] = ldexpf(1.0f, kexp);
+        reinterpret_cast<float*>(img + I.oscale)[0] = ldexpf(1.0f, -kexp) / 255.0f;
     }
     __syncthreads();
     for (int t = tid; t < 96; t += 256) {
         const bool isint = t < T && slot_of[t] < 0;
-        reinterpret_cast<float*>(img + I.s_k)[h * 96 + t] = isint ? s_k[t] : 0.f;
-        reinterpret_cast<float*>(img + I.s_vp)[h * 96 + t] = isint ? s_v[t] * vpre_s : 0.f;
-        if (h == 0) reinterpret_cast<float*>(img + I.bias)[t] = isint ? 0.f : TAQ_NEG_INF;
+        reinterpret_cast<float*>(img + I.s_k)[t] = isint ? s_k[t] : 0.f;
+        reinterpret_cast<float*>(img + I.s_vp)[t] = isint ? s_v[t] * vpre_s : 0.f;
+        reinterpret_cast<float*>(img + I.bias)[t] = isint ? 0.f : TAQ_NEG_INF;
     }
     const int rowb = I.tph * 16;  // bytes per (head, token) row of Kp
     for (int i = tid; i < I.rows_k * rowb; i += 256) {
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
         const int cl = 16 * tile + 4 * q + e;
         int v = 0;
         if (t < T && cl < d && slot_of[t] < 0) v = code_at(k_code, (size_t)b * T + t, C, h * d + cl, bits);
-        img[I.kp + (size_t)h * I.rows_k * rowb + i] = (uint8_t)(v & 0xFF);
+        img[I.kp + i] = (uint8_t)(v & 0xFF);
     }
     for (int i = tid; i < d * I.cols_v; i += 256) {
         const int p = i % I.cols_v, j = i / I.cols_v;
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
         if (t < T && slot_of[t] < 0) v = code_at(v_code, (size_t)b * T + t, C, h * d + j, bits);
         // stored with the sign bit flipped (code + 128 as an unsigned byte): 0x6400 | byte is then the
         // fp16 number 1024 + 128 + code, one packed subtraction away from the code itself
-        img[I.vt + (size_t)h * d * I.cols_v + i] = (uint8_t)((v & 0xFF) ^ 0x80);
+        img[I.vt + i] = (uint8_t)((v & 0xFF) ^ 0x80);
     }
 }
 
@@ -143,18 +143,18 @@ struct FusedCfg {
     static constexpr int KC = C / 64;             // K steps of 64 for the projections
     static constexpr int NT = 64 * NH;            // threads: one wavefront per head
     static constexpr int TILE_RS = C + 16;        // bytes per token row of the int8 tile
-    // image bytes at T = 96, in 16-byte vectors per thread (register staging of the copy)
-    static constexpr int IMG_MAX = H * 96 * TPH * 16 + H * D * 96 + 2 * H * 96 * 4 + 96 * 4 + 2 * ((H * 4 + 15) / 16 * 16);
-    static constexpr int IMGV = (IMG_MAX / 16 + NT - 1) / NT;
+    // bytes of one head's image block at T = 96, in 1 KiB pieces (one direct-to-LDS load each)
+    static constexpr int IMG_HEAD_MAX = 96 * TPH * 16 + D * 96 + 3 * 96 * 4 + 32;
+    static constexpr int IMGC = (IMG_HEAD_MAX + 1023) / 1024;
     static constexpr bool PREFETCH_W = TPH * KC <= 16;  // whole weight slice of a head in registers
 };
 
 // Symmetric 8-bit codes of four values of one row, packed into a dword (low byte first).
 //   exact definition: code = rint((x * 127) / amax) with IEEE float32 multiply and divide.
-//   fast path: q0 = x * c with c = RN(127 / amax); q0 and the defined quotient both lie within
-//   127 * 2^-23 = 1.52e-5 of the exact ratio, so they round to the same integer unless q0 is within
-//   3.04e-5 of a half-integer; those (rare) lanes redo the four values by the definition.
-//   Rounding uses the 1.5 * 2^23 trick: the low mantissa byte of q0 + magic is the code's byte.
+//   fast path: q0 = x * c with c = 127 * rcp(amax) (rcp within 1 ulp). q0 lies within 4 * 2^-24 * 127 = 3.0e-5
+//   of the exact ratio and the defined quotient within 2 * 2^-24 * 127 = 1.5e-5, so both round to the same
+//   integer unless q0 is within 4.6e-5 of a half-integer; those (rare) lanes redo the four values by the
+//   definition. Rounding uses the 1.5 * 2^23 trick: the low mantissa byte of q0 + magic is the code's byte.
 __device__ __forceinline__ unsigned quant4_i8(float x0, float x1, float x2, float x3, float c, float amax) {
     const float magic = 12582912.0f;
     const float q0 = x0 * c, q1 = x1 * c, q2 = x2 * c, q3 = x3 * c;
@@ -164,13 +164,36 @@ __device__ __forceinline__ unsigned quant4_i8(float x0, float x1, float x2, floa
     const unsigned lo = __builtin_amdgcn_perm(__float_as_uint(m1), __float_as_uint(m0), 0x0c0c0400u);
     const unsigned hi = __builtin_amdgcn_perm(__float_as_uint(m3), __float_as_uint(m2), 0x0c0c0400u);
     unsigned pk = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-    if (fmaxf(fmaxf(d0, d1), fmaxf(d2, d3)) > 0.49996f)
+    if (fmaxf(fmaxf(d0, d1), fmaxf(d2, d3)) > 0.49995f)
         pk = pack4(symq_code_f(x0, 127.f, amax), symq_code_f(x1, 127.f, amax), symq_code_f(x2, 127.f, amax),
                    symq_code_f(x3, 127.f, amax));
     return pk;
 }
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+// All-reduce over the four quarter-wave lanes that hold one image token (l, l^16, l^32, l^48) with the
+// gfx950 row / half-wave swaps: no LDS round trip.
+__device__ __forceinline__ float quad_allmax(float x) {
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float quad_allsum(float x) {
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float y = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+// Maximum over the 16 lanes of a row (DPP: xor 1, xor 2, mirror within 8, mirror within 16).
+__device__ __forceinline__ float row16_allmax(float x) {
+    x = fmaxf(x, __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0xB1, 0xF, 0xF, true)));
+    x = fmaxf(x, __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x4E, 0xF, 0xF, true)));
+    x = fmaxf(x, __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x141, 0xF, 0xF, true)));
+    x = fmaxf(x, __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), 0x140, 0xF, 0xF, true)));
+    return x;
+}
 
 // Four biased bytes (code + 128) -> four fp16 codes: 0x6400 | byte is the fp16 number 1152 + code.
 __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t& b) {
@@ -183,7 +206,7 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 
 // One wavefront per head, 32 image tokens per workgroup (two column tiles of 16 per wavefront).
 template <int D, int NH>
-__global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, FusedDims dm) {
+__global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH + 3) / 4))) void fused_block_kernel(FusedTable tab, FusedDims dm) {
     using F = FusedCfg<D, NH>;
     constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -208,6 +231,30 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
     const int ntrig = reinterpret_cast<const int*>(packed + dm.L.ntrig)[b];
     const int nfp = (ntrig + 15) >> 4;  // tiles of 16 protected tokens
 
+    // ---- phase 0: issue every global read up front, oldest first in the order of use (loads return in
+    // order): hidden tile, weight scales, this head's to_q weight slice, the K~/V~ image
+    const int tok0 = tid >> 4, part0 = tid & 15;  // 16 threads per token, 4 channels per load (first 512 threads)
+    const int nq0 = n0 + tok0;
+    const size_t row0 = (size_t)b * N + (nq0 < N ? nq0 : N - 1);
+    uint2 xin[KC];
+    if (tid < 512) {
+        const uint2* xr = reinterpret_cast<const uint2*>(rq.hidden + row0 * C);
+#pragma unroll
+        for (int it = 0; it < KC; ++it) xin[it] = xr[it * 16 + part0];
+    }
+    constexpr int SCV = (3 * C / 4 + NT - 1) / NT;
+    float4 scv[SCV];
+#pragma unroll
+    for (int k = 0; k < SCV; ++k) {
+        const int i = tid + k * NT;
+        scv[k] = i < 3 * C / 4 ? reinterpret_cast<const float4*>(rq.scales)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    // Every wavefront has issued its reads of the hidden tile before any wavefront issues the (10x larger)
+    // weight and image reads: the texture path serves requests in arrival order, and the hidden tile is the
+    // only thing the first barrier waits for.
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
     // weight rows of this head: row c = h*D + 16*j + r16 (rows past the head are discarded; clamp keeps reads in bounds)
     int wrow[TPH];
 #pragma unroll
@@ -222,71 +269,49 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
 #pragma unroll
             for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + 64 * ks);
     }
-
-    // ---- phase 0: K~/V~ image and weight scales into LDS; per-token int8 codes of the hidden tile
-    {
-        const uint4* src = reinterpret_cast<const uint4*>(packed + dm.L.image + (size_t)b * dm.L.image_bytes);
-        const int nvec = (int)(img_bytes >> 4);
-        uint4 iv[F::IMGV];
+    // ---- per-token int8 codes of the hidden tile
+    if (tid < 512) {
+        float x[KC][4];
+        float amax = 0.f;
 #pragma unroll
-        for (int k = 0; k < F::IMGV; ++k) {
-            const int i = tid + k * NT;
-            iv[k] = i < nvec ? src[i] : make_uint4(0, 0, 0, 0);
+        for (int it = 0; it < KC; ++it) {
+            const __half2* hh = reinterpret_cast<const __half2*>(&xin[it]);
+            const float2 p0 = __half22float2(hh[0]), p1 = __half22float2(hh[1]);
+            x[it][0] = p0.x;
+            x[it][1] = p0.y;
+            x[it][2] = p1.x;
+            x[it][3] = p1.y;
+            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(p0.x), fabsf(p0.y)), fmaxf(fabsf(p1.x), fabsf(p1.y))));
         }
-        const float4* ssrc = reinterpret_cast<const float4*>(rq.scales);
-        float4* sdst = reinterpret_cast<float4*>(wsc);
-        for (int i = tid; i < (3 * C) / 4; i += NT) sdst[i] = ssrc[i];
-
-        if (tid < 512) {  // 16 threads per token, 4 channels per load
-            const int tok = tid >> 4, part = tid & 15;
-            const int n = n0 + tok;
-            const size_t row = (size_t)b * N + (n < N ? n : N - 1);
-            const uint2* xr = reinterpret_cast<const uint2*>(rq.hidden + row * C);
-            float x[KC][4];
-            float amax = 0.f;
+        amax = row16_allmax(amax);
+        const bool zero = amax == 0.f;
+        const float sc = zero ? 1.f : amax / 127.f;
+        const float safe = zero ? 1.f : amax;
+        const float cq = 127.f * __builtin_amdgcn_rcpf(safe);
+        if (part0 == 0) s_h[tok0] = sc;
 #pragma unroll
-            for (int it = 0; it < KC; ++it) {
-                const uint2 v = xr[it * 16 + part];
-                const __half2* hh = reinterpret_cast<const __half2*>(&v);
-                const float2 p0 = __half22float2(hh[0]), p1 = __half22float2(hh[1]);
-                x[it][0] = p0.x;
-                x[it][1] = p0.y;
-                x[it][2] = p1.x;
-                x[it][3] = p1.y;
-                amax = fmaxf(amax, fmaxf(fmaxf(fabsf(p0.x), fabsf(p0.y)), fmaxf(fabsf(p1.x), fabsf(p1.y))));
-            }
-            amax = fmaxf(amax, __shfl_xor(amax, 1));
-            amax = fmaxf(amax, __shfl_xor(amax, 2));
-            amax = fmaxf(amax, __shfl_xor(amax, 4));
-            amax = fmaxf(amax, __shfl_xor(amax, 8));
-            const bool zero = amax == 0.f;
-            const float sc = zero ? 1.f : amax / 127.f;
-            const float safe = zero ? 1.f : amax;
-            const float cq = 127.f / safe;
-            if (part == 0) s_h[tok] = sc;
-#pragma unroll
-            for (int it = 0; it < KC; ++it) {
-                const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq, safe);
-                *reinterpret_cast<unsigned*>(tileq + tok * F::TILE_RS + (it * 16 + part) * 4) = pk;
-                if (dm.dbg.h_code && n < N) *reinterpret_cast<unsigned*>(dm.dbg.h_code + row * C + (it * 16 + part) * 4) = pk;
-            }
-            if (dm.dbg.s_h && part == 0 && n < N) dm.dbg.s_h[row] = sc;
+        for (int it = 0; it < KC; ++it) {
+            const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq, safe);
+            *reinterpret_cast<unsigned*>(tileq + tok0 * F::TILE_RS + (it * 16 + part0) * 4) = pk;
+            if (dm.dbg.h_code && nq0 < N) *reinterpret_cast<unsigned*>(dm.dbg.h_code + row0 * C + (it * 16 + part0) * 4) = pk;
         }
-        uint4* dst = reinterpret_cast<uint4*>(img);
+        if (dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc;
+    }
+    // ---- weight scales and the K~/V~ image into LDS
 #pragma unroll
-        for (int k = 0; k < F::IMGV; ++k) {
-            const int i = tid + k * NT;
-            if (i < nvec) dst[i] = iv[k];
-        }
+    for (int k = 0; k < SCV; ++k) {
+        const int i = tid + k * NT;
+        if (i < 3 * C / 4) reinterpret_cast<float4*>(wsc)[i] = scv[k];
     }
     __syncthreads();
 
     const float* swq = wsc;
     const float* swo = wsc + C;
     const float* bo = wsc + 2 * C;
-    const float* img_sk = reinterpret_cast<const float*>(img + dm.I.s_k) + h * 96;
-    const float* img_svp = reinterpret_cast<const float*>(img + dm.I.s_vp) + h * 96;
-    const float* img_bias = reinterpret_cast<const float*>(img + dm.I.bias);
+    unsigned char* imgh = img + (size_t)h * dm.I.head_bytes;  // this head's block of the K~/V~ image
+    const float* img_sk = reinterpret_cast<const float*>(imgh + dm.I.s_k);
+    const float* img_svp = reinterpret_cast<const float*>(imgh + dm.I.s_vp);
+    const float* img_bias = reinterpret_cast<const float*>(imgh + dm.I.bias);
     const __half* k16 = reinterpret_cast<const __half*>(packed + dm.L.k16) + (size_t)b * T * C;
     const __half* v16t = reinterpret_cast<const __half*>(packed + dm.L.v16t) + (size_t)b * C * 96;
 
@@ -319,27 +344,42 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
             pacc[1][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[1][ks], pacc[1][j], 0, 0, 0);
         }
     }
-    if (F::PREFETCH_W) {  // to_out's weight slice travels while the attention runs
+    // Everything the Q~ step reads from LDS is fetched now, so that no LDS access sits between the issue of the
+    // image copy below and the wait for it (the compiler orders LDS accesses after outstanding direct-to-LDS loads).
+    float4 wq4[TPH];
 #pragma unroll
-        for (int j = 0; j < TPH; ++j)
-#pragma unroll
-            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + 64 * ks);
+    for (int j = 0; j < TPH; ++j) {
+        const int cl = 16 * j + 4 * q;
+        wq4[j] = *reinterpret_cast<const float4*>(swq + h * D + (((16 * j + 16 <= D) || cl < D) ? cl : 0));
     }
-
+    const float shv[2] = {s_h[r16], s_h[16 + r16]};
+    // This head's block of the K~/V~ image: straight into LDS, 1 KiB per wavefront-wide load (LDS address =
+    // base + lane * 16), no registers in between; it travels while to_q and Q~ are computed, and only this
+    // wavefront reads it, so only this wavefront waits for it. The last piece may be fetched more than once.
+    {
+        const unsigned char* gsrc = packed + dm.L.image + (size_t)b * dm.L.image_bytes + (size_t)h * dm.I.head_bytes;
+        const int nchunk = (int)(dm.I.head_bytes >> 10);
+#pragma unroll
+        for (int k = 0; k < F::IMGC; ++k) {
+            const int c = k < nchunk ? k : nchunk - 1;
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(gsrc + (size_t)c * 1024 + lane * 16),
+                (__attribute__((address_space(3))) void*)(imgh + c * 1024), 16, 0, 0);
+        }
+    }
     // ---- Eq. (2), third line: Q~ = Q_a(Q) per (token, head)
     unsigned qpk[2][TPH];
     float sq2[2];
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-        const float sh = s_h[16 * nt + r16];
+        const float sh = shv[nt];
         float qf[TPH][4];
         float qmax = 0.f;
 #pragma unroll
         for (int j = 0; j < TPH; ++j) {
             const int cl = 16 * j + 4 * q;  // first of this lane's 4 channels in the head
-            const bool valid = cl < D;
-            const float4 w4 = *reinterpret_cast<const float4*>(swq + h * D + (valid ? cl : 0));
-            const float wv[4] = {w4.x, w4.y, w4.z, w4.w};
+            const bool valid = (16 * j + 16 <= D) || cl < D;
+            const float wv[4] = {wq4[j].x, wq4[j].y, wq4[j].z, wq4[j].w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float sc = sh * wv[i];
@@ -348,12 +388,11 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
                 qmax = fmaxf(qmax, fabsf(qf[j][i]));
             }
         }
-        qmax = fmaxf(qmax, __shfl_xor(qmax, 16));
-        qmax = fmaxf(qmax, __shfl_xor(qmax, 32));
+        qmax = quad_allmax(qmax);
         const bool qzero = qmax == 0.f;
         const float sQ = qzero ? 1.f : qmax / 127.f;
         const float qsafe = qzero ? 1.f : qmax;
-        const float cq = 127.f / qsafe;
+        const float cq = 127.f * __builtin_amdgcn_rcpf(qsafe);
 #pragma unroll
         for (int j = 0; j < TPH; ++j) qpk[nt][j] = quant4_i8(qf[j][0], qf[j][1], qf[j][2], qf[j][3], cq, qsafe);
         if (dm.dbg.q_code && nvalid[nt]) {
@@ -365,6 +404,16 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
         sq2[nt] = fmaxf(sQ * dm.sig2, 1e-37f);
     }
 
+    // the head's image block travelled meanwhile; it is private to this wavefront: wait (vmcnt(0)), no barrier
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (F::PREFETCH_W) {  // to_out's weight slice travels while the attention runs
+#pragma unroll
+        for (int j = 0; j < TPH; ++j)
+#pragma unroll
+            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + 64 * ks);
+    }
+
+
     // ================= scores: x[t][n] = (K~ Q~^T)[t][n] * s_K[t]   (times sQ * sigma * log2 e later)
     float S[2][6][4], Sf[2][6][4];
     {
@@ -375,7 +424,7 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
             for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) qop[nt][ks][jj] = (4 * ks + jj < TPH) ? (int)qpk[nt][4 * ks + jj] : 0;
-        const int8_t* kp = reinterpret_cast<const int8_t*>(img + dm.I.kp) + (size_t)h * dm.I.rows_k * (TPH * 16);
+        const int8_t* kp = reinterpret_cast<const int8_t*>(imgh + dm.I.kp);
 #pragma unroll
         for (int tt = 0; tt < 6; ++tt) {
             if (tt < dm.nt16) {
@@ -459,8 +508,7 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
 #pragma unroll
         for (int ft = 0; ft < 6; ++ft)
             if (ft < nfp) mx = fmaxf(mx, fmaxf(fmaxf(Sf[nt][ft][0], Sf[nt][ft][1]), fmaxf(Sf[nt][ft][2], Sf[nt][ft][3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = quad_allmax(mx);
         const float sc = sq2[nt], off = -mx * sc;
         float Z = 0.f;
 #pragma unroll
@@ -481,8 +529,7 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
                     Z += Sf[nt][ft][i];
                 }
             }
-        Z += __shfl_xor(Z, 16);
-        Z += __shfl_xor(Z, 32);
+        Z = quad_allsum(Z);
         kq[nt] = 255.0f * __builtin_amdgcn_rcpf(Z);
     }
 
@@ -511,10 +558,7 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
                     int c = h * D + 16 * jt + r16;
                     c = c < C ? c : C - 1;
                     const uint2 w = *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 16 * ft + 4 * q);
-                    half4_t va = *reinterpret_cast<const half4_t*>(&w);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (16 * ft + 4 * q + i >= ntrig) va[i] = (_Float16)0.f;  // slots never written
+                    const half4_t va = *reinterpret_cast<const half4_t*>(&w);  // slots past ntrig hold zeros
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt) {
                         oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, phi[nt], oacc[nt][jt], 0, 0, 0);
@@ -523,7 +567,7 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
                 }
             }
         }
-        const float vpre = reinterpret_cast<const float*>(img + dm.I.vpre)[h];
+        const float vpre = reinterpret_cast<const float*>(imgh + dm.I.vpre)[0];
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
@@ -533,7 +577,7 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
     }
     // unprotected columns: weight = code * (s_V * 2^kexp), split into fp16 high + low parts; V codes exact in fp16
     {
-        const uint8_t* vt = img + dm.I.vt + (size_t)h * D * dm.I.cols_v;
+        const uint8_t* vt = imgh + dm.I.vt;
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             if (2 * s < dm.nt16) {
@@ -543,16 +587,25 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
                 for (int a = 0; a < 2; ++a) {
                     const float4 sv = *reinterpret_cast<const float4*>(img_svp + 16 * (2 * s + a) + 4 * q);
                     const float svv[4] = {sv.x, sv.y, sv.z, sv.w};
+                    if (a == 0 || second) {
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
+                        for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            float w = 0.f;
-                            if (a == 0 || second) w = __builtin_rintf(S[nt][2 * s + a][i] * kq[nt]) * svv[i];  // Eq. (3)
-                            const _Float16 wh = (_Float16)w;
-                            phi[nt][4 * a + i] = wh;
-                            plo[nt][4 * a + i] = (_Float16)(w - (float)wh);
-                        }
+                            for (int i = 0; i < 4; ++i) {
+                                const float w = __builtin_rintf(S[nt][2 * s + a][i] * kq[nt]) * svv[i];  // Eq. (3)
+                                const _Float16 wh = (_Float16)w;
+                                phi[nt][4 * a + i] = wh;
+                                plo[nt][4 * a + i] = (_Float16)(w - (float)wh);
+                            }
+                    } else {
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                phi[nt][4 * a + i] = (_Float16)0.f;
+                                plo[nt][4 * a + i] = (_Float16)0.f;
+                            }
+                    }
                 }
 #pragma unroll
                 for (int jt = 0; jt < TPH; ++jt) {
@@ -574,13 +627,13 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
     }
 
     // ================= per-token int8 codes of O over all heads
-    const float osc = reinterpret_cast<const float*>(img + dm.I.oscale)[h];
+    const float osc = reinterpret_cast<const float*>(imgh + dm.I.oscale)[0];
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         float omx = 0.f;
 #pragma unroll
         for (int jt = 0; jt < TPH; ++jt) {
-            const bool valid = 16 * jt + 4 * q < D;
+            const bool valid = (16 * jt + 16 <= D) || 16 * jt + 4 * q < D;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 oacc[nt][jt][i] = valid ? oacc[nt][jt][i] * osc : 0.f;
@@ -590,8 +643,7 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
                 *reinterpret_cast<float4*>(dm.dbg.O + tok[nt] * C + h * D + 16 * jt + 4 * q) =
                     make_float4(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3]);
         }
-        omx = fmaxf(omx, __shfl_xor(omx, 16));
-        omx = fmaxf(omx, __shfl_xor(omx, 32));
+        omx = quad_allmax(omx);
         if (q == 0) omax[(16 * nt + r16) * NH + h] = __float_as_uint(omx);
     }
     __syncthreads();  // every wavefront is past its reads of the hidden codes
@@ -604,7 +656,7 @@ __global__ __launch_bounds__(64 * NH) void fused_block_kernel(FusedTable tab, Fu
         const bool ozero = oamax == 0.f;
         so[nt] = ozero ? 1.f : oamax / 127.f;
         const float osafe = ozero ? 1.f : oamax;
-        const float cq = 127.f / osafe;
+        const float cq = 127.f * __builtin_amdgcn_rcpf(osafe);
 #pragma unroll
         for (int jt = 0; jt < TPH; ++jt)
             if (16 * jt + 4 * q < D) {
@@ -660,8 +712,8 @@ template <int D, int NH>
 static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     using F = FusedCfg<D, NH>;
     static bool attr_set = false;
-    const size_t bytes = dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 + 32 * NH * 4;
-    if (bytes > 160 * 1024 || dm.I.bytes > (size_t)F::IMGV * F::NT * 16) return hipErrorInvalidValue;
+    const size_t bytes = dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 + 32 * NH * 4;  // = fused_lds_bytes
+    if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);

@@ -6,7 +6,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
-#include "../../include/taq.h"
+#include "taq.h"
 
 #define TAQ_MAX_T 96        // text tokens the attention core holds in LDS (3 tiles of 32)
 #define TAQ_MAX_D 160       // largest head dimension (5 steps of 32)
@@ -34,29 +34,24 @@ struct KvLayout {
     int Cb;
 };
 
-// LDS-ready image of the integer part of K~/V~ for one batch element (fused block kernel).
-// Offsets are relative to the image start; every section is a multiple of 16 bytes.
+// LDS-ready image of the integer part of K~/V~ for one batch element (fused block kernel): one
+// self-contained block per head, so that the wavefront that owns a head copies and waits for its own
+// block only. Offsets are relative to the head block; head_bytes is a multiple of 1 KiB (the unit of
+// the direct-to-LDS copy).
 struct KvImage {
     int tph;        // 16-channel tiles per head = ceil(d/16)
     int rows_k;     // 16*ceil(T/16) text-token rows of the K part
     int cols_v;     // 32*ceil(T/32) token positions per V^T row
-    size_t kp;      // i8  [H][rows_k][tph][4 quarter-lanes][4]  K codes in MFMA operand order
-    size_t vt;      // i8  [H][d][cols_v]   V codes transposed, tokens in accumulator-register order
-    size_t s_k;     // f32 [H][96]  per-(head, token) K scale, 0 on protected / padding tokens
-    size_t s_vp;    // f32 [H][96]  s_V * 2^kexp
-    size_t bias;    // f32 [96]     0 for unprotected tokens, -inf for protected / padding
-    size_t oscale;  // f32 [H]      2^-kexp / 255
-    size_t vpre;    // f32 [H]      2^kexp
-    size_t bytes;
+    size_t kp;      // i8  [rows_k][tph][4 quarter-lanes][4]  K codes in MFMA operand order
+    size_t vt;      // u8  [d][cols_v]   V codes (+128) transposed, tokens in accumulator-register order
+    size_t s_k;     // f32 [96]  per-token K scale of this head, 0 on protected / padding tokens
+    size_t s_vp;    // f32 [96]  s_V * 2^kexp
+    size_t bias;    // f32 [96]  0 for unprotected tokens, -inf for protected / padding (same in every head)
+    size_t oscale;  // f32       2^-kexp / 255
+    size_t vpre;    // f32       2^kexp
+    size_t head_bytes;
+    size_t bytes;   // H * head_bytes
 };
-
-// Shapes the fused block kernel is instantiated for: (d, H) = (40, 8), (80, 8), (64, 10).
-static inline bool fused_supported(const taq_shape& s) {
-    if (s.bits_kv != 4 && s.bits_kv != 8) return false;
-    if (s.C % s.H) return false;
-    const int d = s.C / s.H;
-    return (d == 40 && s.H == 8) || (d == 80 && s.H == 8) || (d == 64 && s.H == 10);
-}
 
 static inline KvImage kv_image(const taq_shape& s) {
     KvImage I;
@@ -66,15 +61,31 @@ static inline KvImage kv_image(const taq_shape& s) {
     I.cols_v = 32 * ((s.T + 31) / 32);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 16); return o; };
-    I.kp = take(H * I.rows_k * (size_t)I.tph * 16);
-    I.vt = take(H * d * (size_t)I.cols_v);
-    I.s_k = take(H * 96 * 4);
-    I.s_vp = take(H * 96 * 4);
+    I.kp = take(I.rows_k * (size_t)I.tph * 16);
+    I.vt = take(d * (size_t)I.cols_v);
+    I.s_k = take(96 * 4);
+    I.s_vp = take(96 * 4);
     I.bias = take(96 * 4);
-    I.oscale = take(H * 4);
-    I.vpre = take(H * 4);
-    I.bytes = off;
+    I.oscale = take(4);
+    I.vpre = take(4);
+    I.head_bytes = align_up(off, 1024);
+    I.bytes = H * I.head_bytes;
     return I;
+}
+
+// LDS bytes of the fused block kernel: K~/V~ image, int8 token tile, weight scales, per-token scratch.
+static inline size_t fused_lds_bytes(const taq_shape& s) {
+    return kv_image(s).bytes + 32 * ((size_t)s.C + 16) + 3 * (size_t)s.C * 4 + 32 * 4 + 32 * (size_t)s.H * 4;
+}
+
+// Shapes the fused block kernel is instantiated for: (d, H) = (40, 8), (80, 8), (64, 10), as long as
+// its working set fits the 160 KiB of LDS of a compute unit.
+static inline bool fused_supported(const taq_shape& s) {
+    if (s.bits_kv != 4 && s.bits_kv != 8) return false;
+    if (s.C % s.H) return false;
+    const int d = s.C / s.H;
+    if (!((d == 40 && s.H == 8) || (d == 80 && s.H == 8) || (d == 64 && s.H == 10))) return false;
+    return fused_lds_bytes(s) <= 160 * 1024;
 }
 
 static inline KvLayout kv_layout(const taq_shape& s) {

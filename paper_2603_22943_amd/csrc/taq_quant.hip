@@ -256,7 +256,14 @@ __global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __re
                                                               __half* __restrict__ v16t) {
     __shared__ float xs[4096];
     const int slot = blockIdx.x, b = blockIdx.y;
-    if (slot >= ntrig[b]) return;
+    // unused slots of the transposed copy read as zeros: the padding slots T..95 (last block) ...
+    if (slot == T - 1)
+        for (int c = threadIdx.x; c < C; c += 256)
+            for (int sp = T; sp < 96; ++sp) v16t[((size_t)b * C + c) * 96 + sp] = __float2half(0.f);
+    if (slot >= ntrig[b]) {  // ... and every slot past the protected tokens
+        for (int c = threadIdx.x; c < C; c += 256) v16t[((size_t)b * C + c) * 96 + slot] = __float2half(0.f);
+        return;
+    }
     const int t = trig_idx[b * T + slot];
     const __half* xr = context + ((size_t)b * T + t) * Cc;
     for (int k = threadIdx.x; k < Cc; k += 256) xs[k] = __half2float(xr[k]);
