@@ -45,6 +45,10 @@ def parse():
     p.add_argument("--cpu-seconds", type=float, default=12.0, help="lower bound of oracle time to spend")
     p.add_argument("--profile-only", action="store_true",
                    help="run only warmup + timed steps (for rocprofv3), skip the side measurements")
+    p.add_argument("--traffic-probe", action="store_true",
+                   help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: a device copy of known size, then eager steps")
+    p.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                   help="turn the two counter_collection CSVs of the traffic probe into profiles/traffic.json")
     return p.parse_args()
 
 
@@ -128,8 +132,42 @@ def cpu_baseline(L, min_seconds):
                       f"float64 numpy, os.cpu_count()={os.cpu_count()}"}
 
 
+COPY_BYTES = 256 << 20  # the known-size copy of the traffic probe reads and writes this many bytes
+
+
+def summarize_pmc(fetch_csv, write_csv):
+    """FETCH_SIZE / WRITE_SIZE come in KiB per dispatch. Scale each by what the same counter reads for the
+    plain copy kernel of known size, then average over the fused kernel's dispatches."""
+    import csv
+
+    def per_kernel(path, counter):
+        rows = [r for r in csv.DictReader(open(path)) if r["Counter_Name"] == counter]
+        copy = [float(r["Counter_Value"]) for r in rows if "copy" in r["Kernel_Name"].lower()]
+        copy = [v for v in copy if v >= 0.5 * max(copy)] if copy else []  # the big probe copies only
+        fused = [float(r["Counter_Value"]) for r in rows if "fused_block_kernel" in r["Kernel_Name"]]
+        return copy, fused
+
+    out = {}
+    for name, path, counter in (("fetch", fetch_csv, "FETCH_SIZE"), ("write", write_csv, "WRITE_SIZE")):
+        copy, fused = per_kernel(path, counter)
+        if not copy or not fused:
+            raise SystemExit(f"{path}: no copy or fused dispatches found")
+        copy_kib = sum(copy) / len(copy)
+        factor = (COPY_BYTES / 1024.0) / copy_kib  # true KiB per counted KiB
+        fused_kib = sum(fused[4:]) / max(1, len(fused[4:]))  # skip the first dispatches (cold caches)
+        out[name] = {"copy_counter_KiB": copy_kib, "scale_factor": factor, "fused_counter_KiB": fused_kib,
+                     "fused_bytes_per_launch": fused_kib * factor * 1024.0, "dispatches": len(fused)}
+    out["fused_bytes_per_launch"] = out["fetch"]["fused_bytes_per_launch"] + out["write"]["fused_bytes_per_launch"]
+    path = os.path.join(ROOT, "profiles", "fused_block_kernel_cfg2_hbm_traffic.json")
+    json.dump(out, open(path, "w"), indent=1)
+    print(json.dumps(out))
+
+
 def main():
     a = parse()
+    if a.summarize_pmc:
+        summarize_pmc(*a.summarize_pmc)
+        return
     if a.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
@@ -160,6 +198,16 @@ def main():
     def step_call(r, dbg=None):
         return lambda: T.taq_cross_attn(r["hidden"], packed, wq, wo, scales, mask, s, r["out"], r["ws"], debug=dbg)
 
+    if a.traffic_probe:
+        src = torch.empty(COPY_BYTES, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        for i in range(a.steps):
+            step_call(ring[i % len(ring)])()
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": True, "copy_bytes": COPY_BYTES, "steps": a.steps}), flush=True)
+        return
     runner = Runner([step_call(r) for r in ring], use_graph=not a.no_graph)
     runner.run(a.warmup)
     wall = runner.time_wall(a.steps)  # EXACTLY a.steps steps between two synchronisations
@@ -192,7 +240,30 @@ def main():
     result["quantize_kv_us"] = kv_s * 1e6
     result["value_with_quantize_kv_every_step"] = tokens / (wall / a.steps + kv_s)
 
-    # ---- roofline of the dominant kernel, timed alone with HIP events on the launch stream
+    # ---- roofline of the dominant kernel. taq_cross_attn at this shape is ONE kernel (the fused block), so its
+    # average launch duration is measured with HIP events on the launch stream over the same replayed steps.
+    t_fused = runner.time_events(a.steps)
+    C, H, T_ = L.C, L.H, L.T
+    # algorithmic bytes per launch: hidden in (2C) + out (2C) per token, both weight matrices, int8 K~/V~ + scales
+    alg_bytes = tokens * 4 * C + 2 * C * C + L.B * (2 * T_ * C + 2 * 4 * H * T_)
+    gbs = alg_bytes / t_fused / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "fused_block_kernel_cfg2_hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("fused_bytes_per_launch")
+        except Exception:  # noqa: BLE001
+            traffic = None
+    result["roofline"] = {"kernel": "fused_block_kernel<40,8>", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
+                          "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
+                          "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": t_fused * 1e6}
+    # integer matrix work inside the same kernel: to_q + to_out (2*M*C*C each) and K~ Q~^T (2*M*T*C)
+    int8_ops = 2.0 * tokens * C * C * 2 + 2.0 * tokens * T_ * C
+    result["roofline_mfma_int8"] = {"kernel": "fused_block_kernel<40,8>", "bound": "mfma", "achieved": int8_ops / t_fused / 1e12,
+                                    "peak": INT8_PEAK_TOPS, "unit": "TOP/s", "frac": int8_ops / t_fused / 1e12 / INT8_PEAK_TOPS,
+                                    "note": "at C=320 the whole block carries ~400 int8 op per HBM byte; the HBM roofline alone "
+                                            "caps int8 MFMA use near 0.4/5.0 of peak at this shape"}
+    # ---- the same path as one kernel per stage (general path; other shapes run this way), each timed alone
     stages = [("hidden_quant", T.TAQ_STAGE_HIDDEN_QUANT), ("to_q", T.TAQ_STAGE_TO_Q), ("q_quant", T.TAQ_STAGE_Q_QUANT),
               ("attn_core", T.TAQ_STAGE_ATTN_CORE), ("o_quant", T.TAQ_STAGE_O_QUANT), ("to_out", T.TAQ_STAGE_TO_OUT)]
     per_stage = {}
@@ -201,28 +272,15 @@ def main():
         rr = Runner([step_call(r, d) for r, d in zip(ring, dbgs)], use_graph=not a.no_graph)
         rr.run(len(ring))
         per_stage[name] = rr.time_events(max(64, a.steps // 2))
-    result["stage_us"] = {k: round(v * 1e6, 3) for k, v in per_stage.items()}
-    # attention core: algorithmic bytes per query token = C (int8 Q~) + 4H (its scales) + 2C (fp16-sized O)
-    core_bytes = tokens * (3 * L.C + 4 * L.H)
-    core_gbs = core_bytes / per_stage["attn_core"] / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("attn_core_bytes_per_launch")
-        except Exception:  # noqa: BLE001
-            traffic = None
-    result["roofline"] = {"kernel": "attn_core_kernel", "bound": "hbm", "achieved": core_gbs, "peak": HBM_PEAK_GBS,
-                          "unit": "GB/s", "frac": core_gbs / HBM_PEAK_GBS, "traffic": traffic,
-                          "algorithmic_bytes_per_launch": core_bytes,
-                          "avg_launch_us": per_stage["attn_core"] * 1e6}
-    # projection GEMMs: 2*M*C*C integer ops each
-    gemm_ops = 2.0 * tokens * L.C * L.C
-    result["mfma"] = {k: {"achieved_TOPS": gemm_ops / per_stage[k] / 1e12,
-                          "frac_of_int8_peak": gemm_ops / per_stage[k] / 1e12 / INT8_PEAK_TOPS}
-                      for k in ("to_q", "to_out")}
-    result["mfma"]["note"] = ("at C=320 these GEMMs move ~8 MB for 1.68 GOP (205 op/B): the HBM roofline caps them "
-                              "near 33 % of the int8 peak")
+    core_bytes = tokens * (3 * C + 4 * H)  # int8 Q~ + its scales in, fp16-sized O out
+    gemm_ops = 2.0 * tokens * C * C
+    result["unfused_stages"] = {
+        "stage_us": {k: round(v * 1e6, 3) for k, v in per_stage.items()},
+        "attn_core_GBps": core_bytes / per_stage["attn_core"] / 1e9,
+        "attn_core_frac_of_hbm": core_bytes / per_stage["attn_core"] / 1e9 / HBM_PEAK_GBS,
+        "to_q_TOPS": gemm_ops / per_stage["to_q"] / 1e12, "to_out_TOPS": gemm_ops / per_stage["to_out"] / 1e12,
+        "note": "kernel-per-stage path, used for shapes the fused kernel is not instantiated for",
+    }
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(L, a.cpu_seconds)
     print(json.dumps(result), flush=True)

@@ -7,14 +7,14 @@
 // Nothing between `hidden` and `out` touches HBM: per image token the kernel reads 2C bytes and
 // writes 2C bytes; weights and K~/V~ come from L2.
 //
-// Work split. A workgroup owns 32 image tokens and all heads: 2 token groups of 16 tokens times
-// NW wavefronts that own 2 heads each. Every contraction is computed transposed (output channel
-// or text token along the MFMA row axis, image token along the column axis) with 16x16 tiles, so
-// an image token stays in lane (token % 16) of its wavefront, in all four quarter-waves, from the
-// first GEMM to the last: per-token reductions are register maxima plus two cross-lane steps, and
-// every intermediate (Q~ codes, probabilities, O codes) is handed to the next MFMA as its B operand
-// straight from registers. The A operands' contraction order is free, so K~ and V~^T are stored
-// in LDS in the order in which the accumulator registers of the previous MFMA come out.
+// Work split. A workgroup owns 32 image tokens and all heads, one wavefront per head; each wavefront
+// carries two column tiles of 16 tokens. Every contraction is computed transposed (output channel or
+// text token along the MFMA row axis, image token along the column axis) with 16x16 tiles, so an image
+// token stays in lane (token % 16) of its wavefront, in all four quarter-waves, from the first GEMM to
+// the last: per-token reductions are register maxima plus two cross-lane swaps, and every intermediate
+// (Q~ codes, probabilities, O codes) is handed to the next MFMA as its B operand straight from registers.
+// The A operands' contraction order is free, so K~ and V~^T are stored in LDS in the order in which the
+// accumulator registers of the previous MFMA come out.
 //
 // Bit-exact steps (same float32 operation order as the definition): per-token codes of hidden,
 // the int32 accumulators, Qf = float(acc) * (s_h * s_wq), Q~ codes and scales.
