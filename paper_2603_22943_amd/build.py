@@ -5,6 +5,9 @@
 Flags that matter for parity with the float32-defined quantizers:
   -ffp-contract=off                          no silent FMA contraction (FMAs are explicit where wanted)
   -fhip-fp32-correctly-rounded-divide-sqrt   IEEE float32 division
+  -fno-honor-nans                            inputs are finite by contract; saves the NaN-quieting
+                                             instruction in front of every max (infinities stay honoured:
+                                             the -inf token bias relies on them)
 and packed-fp32 instructions are switched off for the device pass.
 """
 from __future__ import annotations
@@ -31,7 +34,7 @@ def build_lib(verbose: bool = True) -> str:
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
     cmd = [
         hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-        "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt",
+        "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-honor-nans",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wno-unused-function",
         "-I", os.path.join(os.path.dirname(HERE), "include"),

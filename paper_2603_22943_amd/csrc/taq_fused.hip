@@ -249,30 +249,10 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
         const int i = tid + k * NT;
         scv[k] = i < 3 * C / 4 ? reinterpret_cast<const float4*>(rq.scales)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    // Every wavefront has issued its reads of the hidden tile before any wavefront issues the (10x larger)
-    // weight and image reads: the texture path serves requests in arrival order, and the hidden tile is the
-    // only thing the first barrier waits for.
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    // weight rows of this head: row c = h*D + 16*j + r16 (rows past the head are discarded; clamp keeps reads in bounds)
-    int wrow[TPH];
-#pragma unroll
-    for (int j = 0; j < TPH; ++j) {
-        const int c = h * D + 16 * j + r16;
-        wrow[j] = (c < C ? c : C - 1) * C + 16 * q;
-    }
-    int32x4_t wreg[F::PREFETCH_W ? TPH : 1][F::PREFETCH_W ? KC : 1];
-    if (F::PREFETCH_W) {
-#pragma unroll
-        for (int j = 0; j < TPH; ++j)
-#pragma unroll
-            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + 64 * ks);
-    }
     // ---- per-token int8 codes of the hidden tile
+    float x[KC][4];
+    float amax = 0.f;
     if (tid < 512) {
-        float x[KC][4];
-        float amax = 0.f;
 #pragma unroll
         for (int it = 0; it < KC; ++it) {
             const __half2* hh = reinterpret_cast<const __half2*>(&xin[it]);
@@ -283,20 +263,41 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
             x[it][3] = p1.y;
             amax = fmaxf(amax, fmaxf(fmaxf(fabsf(p0.x), fabsf(p0.y)), fmaxf(fabsf(p1.x), fabsf(p1.y))));
         }
-        amax = row16_allmax(amax);
-        const bool zero = amax == 0.f;
-        const float sc = zero ? 1.f : amax / 127.f;
-        const float safe = zero ? 1.f : amax;
-        const float cq = 127.f * __builtin_amdgcn_rcpf(safe);
-        if (part0 == 0) s_h[tok0] = sc;
+    }
+    // The hidden tile has arrived (the unpacking above waited for it). Only now are the 10x larger weight reads
+    // issued: the texture path serves requests in arrival order, and the first barrier waits for nothing else.
+    __builtin_amdgcn_sched_barrier(0);
+    // weight rows of this head: row c = h*D + 16*j + r16 (rows past the head are discarded; clamp keeps reads in bounds)
+    int wrow[TPH];
 #pragma unroll
-        for (int it = 0; it < KC; ++it) {
-            const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq, safe);
+    for (int j = 0; j < TPH; ++j) {
+        const int c = h * D + 16 * j + r16;
+        wrow[j] = (c < C ? c : C - 1) * C + 16 * q;
+    }
+    // The weight slice is fetched a few loads at a time between pieces of arithmetic: a wavefront stalls at a
+    // vector-memory instruction while the texture unit's queue is full (it coalesces 64 B per clock, and every
+    // CU pulls ~300 KB of weights and image per launch), so the requests are spread under the ALU work.
+    int32x4_t wreg[F::PREFETCH_W ? TPH : 1][F::PREFETCH_W ? KC : 1];
+    amax = row16_allmax(amax);
+    const bool zero0 = amax == 0.f;
+    const float sc0 = zero0 ? 1.f : amax / 127.f;
+    const float safe0 = zero0 ? 1.f : amax;
+    const float cq0 = 127.f * __builtin_amdgcn_rcpf(safe0);
+    if (tid < 512 && part0 == 0) s_h[tok0] = sc0;
+#pragma unroll
+    for (int it = 0; it < KC; ++it) {
+        if (F::PREFETCH_W) {
+#pragma unroll
+            for (int j = 0; j < TPH; ++j) wreg[j][it] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + 64 * it);
+        }
+        if (tid < 512) {
+            const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq0, safe0);
             *reinterpret_cast<unsigned*>(tileq + tok0 * F::TILE_RS + (it * 16 + part0) * 4) = pk;
             if (dm.dbg.h_code && nq0 < N) *reinterpret_cast<unsigned*>(dm.dbg.h_code + row0 * C + (it * 16 + part0) * 4) = pk;
         }
-        if (dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc;
+        __builtin_amdgcn_sched_barrier(0);
     }
+    if (tid < 512 && dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc0;
     // ---- weight scales and the K~/V~ image into LDS
 #pragma unroll
     for (int k = 0; k < SCV; ++k) {
@@ -367,6 +368,26 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
                 (__attribute__((address_space(3))) void*)(imgh + c * 1024), 16, 0, 0);
         }
     }
+    // protected (trigger) rows of this head, first tile of 16: fp16 K rows and transposed V rows straight from
+    // global memory into MFMA operand registers (slots past the protected tokens hold zeros; channels past the
+    // head meet zero Q~ codes / are discarded, so no masking is needed)
+    uint2 k16r[FS][2], v16r[TPH];
+    if (nfp > 0) {
+        const int slot = r16 < T ? r16 : T - 1;
+        const __half* kr = k16 + (size_t)slot * C + h * D + 4 * q;
+#pragma unroll
+        for (int s = 0; s < FS; ++s)
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+                k16r[s][jj] = (2 * s + jj < TPH) ? *reinterpret_cast<const uint2*>(kr + 16 * (2 * s + jj)) : make_uint2(0, 0);
+#pragma unroll
+        for (int jt = 0; jt < TPH; ++jt) {
+            int c = h * D + 16 * jt + r16;
+            c = c < C ? c : C - 1;
+            v16r[jt] = *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 4 * q);
+        }
+    }
+
     // ---- Eq. (2), third line: Q~ = Q_a(Q) per (token, head)
     unsigned qpk[2][TPH];
     float sq2[2];
@@ -467,8 +488,9 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
             for (int ft = 0; ft < 6; ++ft) {
                 if (ft < nfp) {
                     floatx4_t a0 = (floatx4_t){0.f, 0.f, 0.f, 0.f}, a1 = a0;
-                    const int slot = 16 * ft + r16;
-                    const __half* kr = k16 + (size_t)(slot < ntrig ? slot : 0) * C + h * D + 4 * q;
+                    int slot = 16 * ft + r16;
+                    slot = slot < T ? slot : T - 1;
+                    const __half* kr = k16 + (size_t)slot * C + h * D + 4 * q;
 #pragma unroll
                     for (int s = 0; s < FS; ++s) {
                         half8_t ka;
@@ -476,7 +498,8 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
                         for (int jj = 0; jj < 2; ++jj) {
                             const int j = 2 * s + jj;
                             uint2 w = make_uint2(0, 0);
-                            if (j < TPH && slot < ntrig && 16 * j + 4 * q < D) w = *reinterpret_cast<const uint2*>(kr + 16 * j);
+                            if (ft == 0) w = k16r[s][jj];
+                            else if (j < TPH) w = *reinterpret_cast<const uint2*>(kr + 16 * j);
                             const half4_t hv = *reinterpret_cast<const half4_t*>(&w);
                             ka[4 * jj + 0] = hv[0];
                             ka[4 * jj + 1] = hv[1];
@@ -551,13 +574,13 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
                         const float x = Sf[nt][ft][i] * kq[nt];
                         const _Float16 xh = (_Float16)x;
                         phi[nt][i] = xh;
-                        plo[nt][i] = (_Float16)(x - (float)xh);
+                        plo[nt][i] = (_Float16)__builtin_fmaf((float)xh, -1.0f, x);
                     }
 #pragma unroll
                 for (int jt = 0; jt < TPH; ++jt) {
                     int c = h * D + 16 * jt + r16;
                     c = c < C ? c : C - 1;
-                    const uint2 w = *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 16 * ft + 4 * q);
+                    const uint2 w = ft == 0 ? v16r[jt] : *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 16 * ft + 4 * q);
                     const half4_t va = *reinterpret_cast<const half4_t*>(&w);  // slots past ntrig hold zeros
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt) {
@@ -595,7 +618,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
                                 const float w = __builtin_rintf(S[nt][2 * s + a][i] * kq[nt]) * svv[i];  // Eq. (3)
                                 const _Float16 wh = (_Float16)w;
                                 phi[nt][4 * a + i] = wh;
-                                plo[nt][4 * a + i] = (_Float16)(w - (float)wh);
+                                plo[nt][4 * a + i] = (_Float16)__builtin_fmaf((float)wh, -1.0f, w);  // w - hi, exact
                             }
                     } else {
 #pragma unroll

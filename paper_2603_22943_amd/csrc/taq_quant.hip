@@ -260,8 +260,12 @@ __global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __re
     if (slot == T - 1)
         for (int c = threadIdx.x; c < C; c += 256)
             for (int sp = T; sp < 96; ++sp) v16t[((size_t)b * C + c) * 96 + sp] = __float2half(0.f);
-    if (slot >= ntrig[b]) {  // ... and every slot past the protected tokens
-        for (int c = threadIdx.x; c < C; c += 256) v16t[((size_t)b * C + c) * 96 + slot] = __float2half(0.f);
+    if (slot >= ntrig[b]) {  // ... and every slot past the protected tokens, in all three copies
+        for (int c = threadIdx.x; c < C; c += 256) {
+            v16t[((size_t)b * C + c) * 96 + slot] = __float2half(0.f);
+            k16[((size_t)b * T + slot) * C + c] = __float2half(0.f);
+            v16[((size_t)b * T + slot) * C + c] = __float2half(0.f);
+        }
         return;
     }
     const int t = trig_idx[b * T + slot];
