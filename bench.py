@@ -132,6 +132,48 @@ def cpu_baseline(L, min_seconds):
                       f"float64 numpy, os.cpu_count()={os.cpu_count()}"}
 
 
+def other_configs(dev, use_graph):
+    """Device time per taq_cross_attn call (and per taq_quantize_kv) for configs 1, 3, 4, 5."""
+    to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    out = {}
+
+    def prep(L):
+        s = T.make_shape(B=L.B, N=L.N, C=L.C, H=L.H, T=L.T, Cc=L.Cc, bits_kv=L.bits_kv)
+        wq, swq = T.taq_quantize_weight(to(L.Wq))
+        wo, swo = T.taq_quantize_weight(to(L.Wo))
+        d = dict(s=s, wq=wq, wo=wo, scales=torch.cat([swq, swo, to(L.bias_o)]).contiguous(), mask=to(L.mask),
+                 ctx=to(L.context), Wk=to(L.Wk), Wv=to(L.Wv), hidden=to(L.hidden),
+                 out=torch.empty((L.B, L.N, L.C), dtype=torch.float16, device=dev),
+                 ws=torch.empty(T.taq_workspace_bytes(s), dtype=torch.uint8, device=dev),
+                 packed=torch.empty(T.taq_kv_packed_bytes(s), dtype=torch.uint8, device=dev))
+        T.taq_quantize_kv(d["ctx"], d["mask"], d["Wk"], d["Wv"], L.bits_kv, s, d["packed"], d["ws"])
+        return d
+
+    def attn_call(d):
+        return lambda: T.taq_cross_attn(d["hidden"], d["packed"], d["wq"], d["wo"], d["scales"], d["mask"], d["s"],
+                                        d["out"], d["ws"])
+
+    def timed(calls, reps=40):
+        r = Runner(calls, use_graph=use_graph)
+        r.run(2 * len(calls))
+        return r.time_events(reps * len(calls)) * len(calls) * 1e6  # us per pass over `calls`
+
+    d1 = prep(synth.config1())
+    out["config1_64x1280"] = round(timed([attn_call(d1)] * 4) / 4, 2)
+    layers = [prep(L) for L in synth.config3()]
+    out["config3_16_layers_total"] = round(timed([attn_call(d) for d in layers], reps=10), 2)
+    for L in synth.config4():
+        d = prep(L)
+        out["config4_%dx%d" % (L.N, L.C)] = round(timed([attn_call(d)] * 4) / 4, 2)
+    reqs = [prep(L) for L in synth.config5()]
+    table = [dict(hidden=d["hidden"], qkv_packed=d["packed"], Wq=d["wq"], Wo=d["wo"], scales=d["scales"],
+                  trigger_mask=d["mask"], out=d["out"]) for d in reqs]
+    ws5 = torch.empty(16 * T.taq_workspace_bytes(reqs[0]["s"]), dtype=torch.uint8, device=dev)
+    out["config5_16_requests_batched"] = round(timed([lambda: T.taq_cross_attn_batched(table, reqs[0]["s"], ws5)] * 2,
+                                                     reps=10) / 2, 2)
+    return out
+
+
 COPY_BYTES = 256 << 20  # the known-size copy of the traffic probe reads and writes this many bytes
 
 
@@ -281,6 +323,8 @@ def main():
         "to_q_TOPS": gemm_ops / per_stage["to_q"] / 1e12, "to_out_TOPS": gemm_ops / per_stage["to_out"] / 1e12,
         "note": "kernel-per-stage path, used for shapes the fused kernel is not instantiated for",
     }
+    # ---- the other benchmark configurations (latency per call; they are parity-test cases, not bench lines)
+    result["other_configs_us"] = other_configs(dev, not a.no_graph)
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(L, a.cpu_seconds)
     print(json.dumps(result), flush=True)

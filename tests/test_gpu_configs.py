@@ -24,9 +24,9 @@ def test_config2_headline_shape():
     check_layer(synth.config2())
 
 
-@pytest.mark.parametrize("layer", [0, 5, 10, 15])
+@pytest.mark.parametrize("layer", list(range(16)))
 def test_config3_unet_step_layers_int4(layer):
-    # one layer of each resolution of the 16-layer step (the other layers repeat these shapes)
+    # the 16 cross-attention layers of one UNet step: 4096x320 (x5), 1024x640 (x5), 256x1280 (x5), 64x1280
     (L,) = synth.config3(layers=[layer])
     check_layer(L)
 
@@ -53,3 +53,38 @@ def test_config5_multi_checkpoint_batch():
         max_abs, rel_l2 = G.out_errors(o.cpu().numpy(), ref)
         print(f"[case] {L.name} ntrig={int(L.mask.sum())}: max_abs={max_abs:.3e} rel_l2={rel_l2:.3e}", flush=True)
         assert max_abs <= 2e-2 and rel_l2 <= 5e-3
+
+
+def test_hip_graph_replays_match_eager():
+    """bench.py replays the steps from a HIP graph. Replay several times with eager work and
+    synchronisations in between; every replay must reproduce the eager result bit for bit."""
+    L = synth.config2(N=1024)
+    g = G.GpuRun(L, taps=False)
+    s = g.shape
+    ws = torch.empty(T.taq_workspace_bytes(s), dtype=torch.uint8, device=G.DEV)
+    outs = [torch.zeros_like(g.out_d) for _ in range(3)]
+    hid = [g.hidden_d.clone() for _ in range(3)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for h, o in zip(hid, outs):
+            T.taq_cross_attn(h, g.packed, g.wq_code, g.wo_code, g.scales, g.mask_d, s, o, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for h, o in zip(hid, outs):
+            T.taq_cross_attn(h, g.packed, g.wq_code, g.wo_code, g.scales, g.mask_d, s, o, ws)
+    ref = g.out.view(np.uint16)
+    rng = np.random.Generator(np.random.PCG64(3))
+    for rep in range(4):
+        for o in outs:
+            o.zero_()
+        # eager work of the program itself between replays, on other data
+        other = torch.from_numpy(rng.standard_normal((L.B, 1024, L.C)).astype(np.float16)).to(G.DEV)
+        T.taq_cross_attn(other, g.packed, g.wq_code, g.wo_code, g.scales, g.mask_d, s)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o in outs:
+            assert np.array_equal(o.cpu().numpy().view(np.uint16), ref), rep
