@@ -138,9 +138,11 @@ def other_configs(dev, use_graph):
     out = {}
 
     def prep(L):
-        s = T.make_shape(B=L.B, N=L.N, C=L.C, H=L.H, T=L.T, Cc=L.Cc, bits_kv=L.bits_kv)
+        s = T.make_shape(B=L.B, N=L.N, C=L.C, H=L.H, T=L.T, Cc=L.Cc, bits_kv=L.bits_kv, w_layout=1 if L.C % 64 == 0 else 0)
         wq, swq = T.taq_quantize_weight(to(L.Wq))
         wo, swo = T.taq_quantize_weight(to(L.Wo))
+        if s.w_layout:
+            wq, wo = T.taq_pack_weight(wq, s), T.taq_pack_weight(wo, s)
         d = dict(s=s, wq=wq, wo=wo, scales=torch.cat([swq, swo, to(L.bias_o)]).contiguous(), mask=to(L.mask),
                  ctx=to(L.context), Wk=to(L.Wk), Wv=to(L.Wv), hidden=to(L.hidden),
                  out=torch.empty((L.B, L.N, L.C), dtype=torch.float16, device=dev),
@@ -219,11 +221,12 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     L = synth.config2()
-    s = T.make_shape(B=L.B, N=L.N, C=L.C, H=L.H, T=L.T, Cc=L.Cc, bits_kv=L.bits_kv)
+    s = T.make_shape(B=L.B, N=L.N, C=L.C, H=L.H, T=L.T, Cc=L.Cc, bits_kv=L.bits_kv, w_layout=1)
     to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
     ctx, mask, Wk, Wv = to(L.context), to(L.mask), to(L.Wk), to(L.Wv)
     wq, swq = T.taq_quantize_weight(to(L.Wq))
     wo, swo = T.taq_quantize_weight(to(L.Wo))
+    wq, wo = T.taq_pack_weight(wq, s), T.taq_pack_weight(wo, s)  # once per checkpoint: operand-ordered copy
     scales = torch.cat([swq, swo, to(L.bias_o)]).contiguous()
     ws_bytes = T.taq_workspace_bytes(s)
     packed = torch.empty(T.taq_kv_packed_bytes(s), dtype=torch.uint8, device=dev)

@@ -58,6 +58,11 @@ typedef struct taq_shape {
     int bits_q;              /* 8 : Q~ = Q_a(Q)                                              */
     int bits_proj;           /* 8 : W8A8 projections                                         */
     float softmax_scale;     /* 0 => 1/sqrt(d)                                               */
+    int w_layout;            /* layout of the Wq / Wo buffers given to taq_cross_attn:
+                                0 : i8 [C, C] row-major codes only
+                                1 : buffers written by taq_pack_weight (row-major codes followed by a copy
+                                    in matrix-core operand order, which the single-kernel path reads with
+                                    fully coalesced loads)                                      */
 } taq_shape;
 
 /* Optional taps for tests and profiling (all pointers device memory or NULL). */
@@ -105,6 +110,15 @@ int taq_workspace_bytes(const taq_shape* shape, size_t* bytes);
 int taq_quantize_weight(const void* W_f16, int rows, int cols, int8_t* codes, float* scales,
                         void* hip_stream);
 
+/* Optional re-layout of a [C, C] weight-code matrix for taq_cross_attn (shape->w_layout = 1): `out` receives
+ * the row-major codes followed by a copy ordered the way the matrix cores read them for this shape's head
+ * dimension. The method is unchanged (the paper does not prescribe a memory layout); only load efficiency is.
+ *   codes : i8 [C, C] row-major (as written by taq_quantize_weight); may be the start of `out` itself
+ *   out   : taq_weight_bytes() bytes
+ * shape->N is ignored. */
+int taq_weight_bytes(const taq_shape* shape, size_t* bytes);
+int taq_pack_weight(const int8_t* codes, const taq_shape* shape, int8_t* out, void* hip_stream);
+
 /* Eq. (2), K and V lines: project the text context and build K~, V~.
  *   context      : f16 [B, T, Cc]
  *   trigger_mask : u8  [B, T], non-zero = trigger token (protected row). Read on the
@@ -124,7 +138,8 @@ int taq_quantize_kv(const void* context, const uint8_t* trigger_mask, const void
 /* Eq. (2) third line, the attention definition and Eq. (3): the block for image tokens.
  *   hidden       : f16 [B, N, C]
  *   qkv_packed   : as written by taq_quantize_kv for the same B, T, C, H, bits_kv
- *   Wq, Wo       : i8  [C, C] row-major (out x in) weight codes (taq_quantize_weight)
+ *   Wq, Wo       : i8  [C, C] row-major (out x in) weight codes (taq_quantize_weight), or, with
+ *                  shape->w_layout = 1, the buffers written by taq_pack_weight
  *   scales       : f32 [3*C] = s_wq[C] | s_wo[C] | bias_o[C] (bias of to_out; zeros if none)
  *   trigger_mask : u8 [B, T] or NULL. The protected-token list recorded in qkv_packed is
  *                  what the kernels use; this argument is accepted for symmetry only.

@@ -21,6 +21,7 @@ int check_shape(const taq_shape* s, bool need_n) {
     if (s->T > TAQ_MAX_T || s->H > TAQ_MAX_H) return TAQ_ERR_BAD_SHAPE;
     if (s->C % 32 != 0 || s->Cc % 32 != 0 || s->Cc > 4096) return TAQ_ERR_BAD_SHAPE;
     if (!(s->softmax_scale >= 0.f)) return TAQ_ERR_INVALID_ARG;
+    if (s->w_layout != 0 && s->w_layout != 1) return TAQ_ERR_INVALID_ARG;
     // index arithmetic inside the kernels is 32-bit for token counts
     if ((long long)s->B * (need_n ? s->N : 1) > (1ll << 30)) return TAQ_ERR_BAD_SHAPE;
     return TAQ_OK;
@@ -73,6 +74,24 @@ int taq_quantize_weight(const void* W_f16, int rows, int cols, int8_t* codes, fl
     if (misaligned(W_f16) || misaligned(codes) || (reinterpret_cast<uintptr_t>(scales) & 3u)) return TAQ_ERR_MISALIGNED;
     TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(W_f16), rows, cols, codes, scales,
                                     static_cast<hipStream_t>(hip_stream)));
+    return TAQ_OK;
+}
+
+int taq_weight_bytes(const taq_shape* shape, size_t* bytes) {
+    if (!bytes) return TAQ_ERR_INVALID_ARG;
+    int rc = check_shape(shape, false);
+    if (rc != TAQ_OK) return rc;
+    *bytes = weight_pack_bytes(*shape);
+    return TAQ_OK;
+}
+
+int taq_pack_weight(const int8_t* codes, const taq_shape* shape, int8_t* out, void* hip_stream) {
+    int rc = check_shape(shape, false);
+    if (rc != TAQ_OK) return rc;
+    if (!codes || !out) return TAQ_ERR_INVALID_ARG;
+    if (misaligned(codes) || misaligned(out)) return TAQ_ERR_MISALIGNED;
+    if (shape->C % 64 != 0) return TAQ_ERR_BAD_SHAPE;
+    TAQ_TRY_HIP(launch_pack_weight(codes, *shape, out, static_cast<hipStream_t>(hip_stream)));
     return TAQ_OK;
 }
 

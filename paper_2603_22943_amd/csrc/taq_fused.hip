@@ -118,6 +118,37 @@ hipError_t launch_kv_image(uint8_t* packed, const taq_shape& s, hipStream_t st) 
 }
 
 // ------------------------------------------------------------------------------------------
+// Weight re-layout for the fused kernel (optional, shape.w_layout = 1)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_weight_kernel(const int8_t* __restrict__ codes, int C, int d, int tph, int kc,
+                                                          size_t pack_off, int8_t* __restrict__ out) {
+    // one 16-byte vector per thread: first the row-major copy, then the operand-ordered copy
+    const size_t nrow = (size_t)C * C / 16;
+    const size_t npack = (size_t)(C / d) * tph * kc * 64;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nrow + npack; i += (size_t)gridDim.x * 256) {
+        if (i < nrow) {
+            if (codes != out) reinterpret_cast<uint4*>(out)[i] = reinterpret_cast<const uint4*>(codes)[i];
+        } else {
+            const size_t v = i - nrow;
+            const int lane = (int)(v & 63), r = lane & 15, q = lane >> 4;
+            const size_t blk = v >> 6;  // (h * tph + j) * kc + ks
+            const int ks = (int)(blk % kc), j = (int)((blk / kc) % tph), h = (int)(blk / ((size_t)kc * tph));
+            int row = h * d + 16 * j + r;
+            row = row < C ? row : C - 1;
+            reinterpret_cast<uint4*>(out + pack_off)[v] =
+                *reinterpret_cast<const uint4*>(codes + (size_t)row * C + 64 * ks + 16 * q);
+        }
+    }
+}
+
+hipError_t launch_pack_weight(const int8_t* codes, const taq_shape& s, int8_t* out, hipStream_t st) {
+    const int d = s.C / s.H;
+    hipLaunchKernelGGL(pack_weight_kernel, dim3(256), dim3(256), 0, st, codes, s.C, d, (d + 15) / 16, s.C / 64,
+                       weight_pack_offset(s), out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
 // Fused block kernel
 // ------------------------------------------------------------------------------------------
 struct FusedTable {
@@ -127,6 +158,8 @@ struct FusedTable {
 struct FusedDims {
     int R, B, N, T;
     int nt16;          // ceil(T/16)
+    int w_layout;      // 1: Wq / Wo carry an operand-ordered copy at w_pack_off
+    unsigned w_pack_off;
     float sig2;        // softmax scale * log2(e)
     KvLayout L;
     KvImage I;
@@ -268,11 +301,14 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
     // issued: the texture path serves requests in arrival order, and the first barrier waits for nothing else.
     __builtin_amdgcn_sched_barrier(0);
     // weight rows of this head: row c = h*D + 16*j + r16 (rows past the head are discarded; clamp keeps reads in bounds)
+    // (byte offset of K step ks = wrow[j] + ks * wstep; with the operand-ordered copy a wavefront-wide load is
+    // one contiguous KiB, otherwise 16 rows x 64 bytes)
     int wrow[TPH];
+    const int wstep = dm.w_layout ? 1024 : 64;
 #pragma unroll
     for (int j = 0; j < TPH; ++j) {
         const int c = h * D + 16 * j + r16;
-        wrow[j] = (c < C ? c : C - 1) * C + 16 * q;
+        wrow[j] = dm.w_layout ? (int)dm.w_pack_off + ((h * TPH + j) * KC) * 1024 + lane * 16 : (c < C ? c : C - 1) * C + 16 * q;
     }
     // The weight slice is fetched a few loads at a time between pieces of arithmetic: a wavefront stalls at a
     // vector-memory instruction while the texture unit's queue is full (it coalesces 64 B per clock, and every
@@ -288,7 +324,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
     for (int it = 0; it < KC; ++it) {
         if (F::PREFETCH_W) {
 #pragma unroll
-            for (int j = 0; j < TPH; ++j) wreg[j][it] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + 64 * it);
+            for (int j = 0; j < TPH; ++j) wreg[j][it] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + wstep * it);
         }
         if (tid < 512) {
             const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq0, safe0);
@@ -340,7 +376,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
         pacc[1][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < KC; ++ks) {
-            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + 64 * ks);
+            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + wstep * ks);
             pacc[0][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[0][ks], pacc[0][j], 0, 0, 0);
             pacc[1][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[1][ks], pacc[1][j], 0, 0, 0);
         }
@@ -431,7 +467,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
 #pragma unroll
         for (int j = 0; j < TPH; ++j)
 #pragma unroll
-            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + 64 * ks);
+            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + wstep * ks);
     }
 
 
@@ -704,7 +740,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
         pacc[1][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < KC; ++ks) {
-            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + 64 * ks);
+            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + wstep * ks);
             pacc[0][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[0][ks], pacc[0][j], 0, 0, 0);
             pacc[1][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[1][ks], pacc[1][j], 0, 0, 0);
         }
@@ -758,6 +794,8 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.N = s.N;
     dm.T = s.T;
     dm.nt16 = (s.T + 15) / 16;
+    dm.w_layout = s.w_layout;
+    dm.w_pack_off = (unsigned)weight_pack_offset(s);
     const int d = s.C / s.H;
     const float sigma = s.softmax_scale != 0.f ? s.softmax_scale : 1.0f / sqrtf((float)d);
     dm.sig2 = sigma * 1.4426950408889634f;

@@ -73,6 +73,15 @@ static inline KvImage kv_image(const taq_shape& s) {
     return I;
 }
 
+// Operand-ordered copy of a [C, C] weight matrix: for head h, 16-row tile j of the head, K step ks (64 codes),
+// lane l = r + 16*q: the 16 codes W[min(h*d + 16*j + r, C-1)][64*ks + 16*q ...]; 1 KiB per (h, j, ks).
+// It sits behind the row-major codes, 256-byte aligned.
+static inline size_t weight_pack_offset(const taq_shape& s) { return align_up((size_t)s.C * s.C, 256); }
+static inline size_t weight_pack_bytes(const taq_shape& s) {
+    const size_t d = s.C / s.H;
+    return weight_pack_offset(s) + (size_t)s.H * ((d + 15) / 16) * (s.C / 64) * 1024;
+}
+
 // LDS bytes of the fused block kernel: K~/V~ image, int8 token tile, weight scales, per-token scratch.
 static inline size_t fused_lds_bytes(const taq_shape& s) {
     return kv_image(s).bytes + 32 * ((size_t)s.C + 16) + 3 * (size_t)s.C * 4 + 32 * 4 + 32 * (size_t)s.H * 4;
@@ -195,6 +204,8 @@ hipError_t launch_gemm_i8(const int8_t* A, const float* sa, const int8_t* W, con
 
 // K~/V~ image for the fused kernel, from the codes and scales already in qkv_packed.
 hipError_t launch_kv_image(uint8_t* packed, const taq_shape& s, hipStream_t st);
+// Row-major weight codes -> row-major codes + operand-ordered copy (weight_pack_bytes).
+hipError_t launch_pack_weight(const int8_t* codes, const taq_shape& s, int8_t* out, hipStream_t st);
 
 // One request of the fused block kernel.
 struct FusedReq {

@@ -31,7 +31,8 @@ TAQ_STAGE_O_QUANT = 16
 TAQ_STAGE_TO_OUT = 32
 
 EXPORTS = [
-    "taq_kv_packed_bytes", "taq_workspace_bytes", "taq_quantize_weight", "taq_quantize_kv",
+    "taq_kv_packed_bytes", "taq_workspace_bytes", "taq_quantize_weight", "taq_weight_bytes", "taq_pack_weight",
+    "taq_quantize_kv",
     "taq_cross_attn", "taq_cross_attn_ex", "taq_cross_attn_batched", "taq_unpack_kv",
     "taq_status_string",
 ]
@@ -47,7 +48,7 @@ class taq_shape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("N", ctypes.c_int), ("C", ctypes.c_int), ("H", ctypes.c_int),
                 ("T", ctypes.c_int), ("Cc", ctypes.c_int), ("bits_kv", ctypes.c_int),
                 ("bits_prob", ctypes.c_int), ("bits_q", ctypes.c_int), ("bits_proj", ctypes.c_int),
-                ("softmax_scale", ctypes.c_float)]
+                ("softmax_scale", ctypes.c_float), ("w_layout", ctypes.c_int)]
 
 
 class taq_debug(ctypes.Structure):
@@ -81,6 +82,8 @@ def load() -> ctypes.CDLL:
     lib.taq_kv_packed_bytes.argtypes = [shp, sz]
     lib.taq_workspace_bytes.argtypes = [shp, sz]
     lib.taq_quantize_weight.argtypes = [vp, ci, ci, vp, vp, vp]
+    lib.taq_weight_bytes.argtypes = [shp, sz]
+    lib.taq_pack_weight.argtypes = [vp, shp, vp, vp]
     lib.taq_quantize_kv.argtypes = [vp, vp, vp, vp, ci, shp, vp, vp, vp]
     lib.taq_cross_attn.argtypes = [vp, vp, vp, vp, vp, vp, shp, vp, vp, vp]
     lib.taq_cross_attn_ex.argtypes = [vp, vp, vp, vp, vp, vp, shp, vp, vp, vp, ctypes.POINTER(taq_debug)]
@@ -93,8 +96,8 @@ def load() -> ctypes.CDLL:
 
 
 def make_shape(B: int, N: int, C: int, H: int, T: int, Cc: int, bits_kv: int = 8, bits_prob: int = 8,
-               bits_q: int = 8, bits_proj: int = 8, softmax_scale: float = 0.0) -> taq_shape:
-    return taq_shape(B, N, C, H, T, Cc, bits_kv, bits_prob, bits_q, bits_proj, softmax_scale)
+               bits_q: int = 8, bits_proj: int = 8, softmax_scale: float = 0.0, w_layout: int = 0) -> taq_shape:
+    return taq_shape(B, N, C, H, T, Cc, bits_kv, bits_prob, bits_q, bits_proj, softmax_scale, w_layout)
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
@@ -140,6 +143,20 @@ def taq_quantize_weight(W: torch.Tensor, codes: Optional[torch.Tensor] = None,
     _check(load().taq_quantize_weight(_ptr(W), rows, cols, _ptr(codes), _ptr(scales), _stream(stream)),
            "taq_quantize_weight")
     return codes, scales
+
+
+def taq_weight_bytes(shape: taq_shape) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load().taq_weight_bytes(ctypes.byref(shape), ctypes.byref(n)), "taq_weight_bytes")
+    return n.value
+
+
+def taq_pack_weight(codes: torch.Tensor, shape: taq_shape, out: Optional[torch.Tensor] = None, stream=None):
+    """int8 [C, C] row-major codes -> buffer for taq_cross_attn with shape.w_layout = 1."""
+    if out is None:
+        out = torch.empty(taq_weight_bytes(shape), dtype=torch.int8, device=codes.device)
+    _check(load().taq_pack_weight(_ptr(codes), ctypes.byref(shape), _ptr(out), _stream(stream)), "taq_pack_weight")
+    return out
 
 
 def taq_quantize_kv(context: torch.Tensor, trigger_mask: torch.Tensor, Wk: torch.Tensor, Wv: torch.Tensor,

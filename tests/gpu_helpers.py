@@ -11,9 +11,9 @@ from paper_2603_22943_amd import taq as T
 DEV = "cuda:0"
 
 
-def shape_of(L, bits_kv=None, N=None):
+def shape_of(L, bits_kv=None, N=None, w_layout=0):
     return T.make_shape(B=L.B, N=L.N if N is None else N, C=L.C, H=L.H, T=L.T, Cc=L.Cc,
-                        bits_kv=L.bits_kv if bits_kv is None else bits_kv)
+                        bits_kv=L.bits_kv if bits_kv is None else bits_kv, w_layout=w_layout)
 
 
 def dev(a, dtype=None):
@@ -26,20 +26,24 @@ def dev(a, dtype=None):
 class GpuRun:
     """Everything the HIP path produces for one layer (tensors brought back as numpy)."""
 
-    def __init__(self, L, taps=True, hidden=None):
+    def __init__(self, L, taps=True, hidden=None, w_layout=0):
         self.L = L
-        self.shape = s = shape_of(L)
+        self.shape = s = shape_of(L, w_layout=w_layout)
         ctx, mask = dev(L.context), dev(L.mask)
         Wq, Wk, Wv, Wo = dev(L.Wq), dev(L.Wk), dev(L.Wv), dev(L.Wo)
         self.wq_code, self.s_wq = T.taq_quantize_weight(Wq)
         self.wo_code, self.s_wo = T.taq_quantize_weight(Wo)
+        self.wq_plain, self.wo_plain = self.wq_code, self.wo_code
+        if w_layout == 1:  # row-major codes followed by the operand-ordered copy
+            self.wq_code = T.taq_pack_weight(self.wq_plain, s)
+            self.wo_code = T.taq_pack_weight(self.wo_plain, s)
         self.scales = torch.cat([self.s_wq, self.s_wo, dev(L.bias_o)]).contiguous()
         self.packed = T.taq_quantize_kv(ctx, mask, Wk, Wv, L.bits_kv, s)
         self.kv = {k: v.cpu().numpy() for k, v in T.taq_unpack_kv(self.packed, s).items()}
         self.mask_d = mask
         self.hidden_d = dev(L.hidden if hidden is None else hidden)
         if hidden is not None:
-            self.shape = s = shape_of(L, N=hidden.shape[1])
+            self.shape = s = shape_of(L, N=hidden.shape[1], w_layout=w_layout)
         if taps:
             dbg, t = T.make_debug(s, DEV)
             self.out_d = T.taq_cross_attn(self.hidden_d, self.packed, self.wq_code, self.wo_code, self.scales,

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert ctypes.sizeof(T.taq_shape) == 11 * 4
+    assert ctypes.sizeof(T.taq_shape) == 12 * 4
     assert ctypes.sizeof(T.taq_request) == 7 * 8
     assert ctypes.sizeof(T.taq_debug) == 7 * 8 + 8
 
@@ -108,6 +108,13 @@ def test_entry_points_reject_null_misaligned_and_inconsistent_arguments_without_
     assert lib.taq_cross_attn_batched(2, tab, sp, FAKE, None) == T.TAQ_ERR_INVALID_ARG
     # unpack
     assert lib.taq_unpack_kv(None, sp, None, None, None, None, None, None, None) == T.TAQ_ERR_INVALID_ARG
+    # weight re-layout
+    assert lib.taq_pack_weight(None, sp, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    assert lib.taq_pack_weight(FAKE, sp, ODD, None) == T.TAQ_ERR_MISALIGNED
+    bad = T.make_shape(B=1, N=64, C=320, H=8, T=77, Cc=768, w_layout=2)
+    assert lib.taq_pack_weight(FAKE, ctypes.byref(bad), FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    # the re-laid-out buffer holds the row-major codes plus one KiB per (head, 16-row tile, 64-code step)
+    assert T.taq_weight_bytes(s) == 320 * 320 + 8 * 3 * 5 * 1024
 
 
 def test_product_package_does_not_import_the_oracle():

@@ -27,16 +27,16 @@ OUT_MAX_ABS = 2e-2
 OUT_REL_L2 = 5e-3
 
 
-def check_layer(L, label=""):
+def check_layer(L, label="", w_layout=0):
     print(f"[case] {label or L.name}: B={L.B} N={L.N} C={L.C} H={L.H} T={L.T} Cc={L.Cc} bits_kv={L.bits_kv} "
-          f"ntrig={L.mask.sum(axis=1).tolist()}", flush=True)
-    g = G.GpuRun(L)
+          f"ntrig={L.mask.sum(axis=1).tolist()} w_layout={w_layout}", flush=True)
+    g = G.GpuRun(L, w_layout=w_layout)
     ref_out, aux = G.oracle_run(L)
     kv = aux["kv"]
     # ---- weights
-    assert np.array_equal(g.wq_code.cpu().numpy(), aux["wq_code"])
+    assert np.array_equal(g.wq_plain.cpu().numpy(), aux["wq_code"])
     assert np.array_equal(g.s_wq.cpu().numpy(), aux["s_wq"])
-    assert np.array_equal(g.wo_code.cpu().numpy(), aux["wo_code"])
+    assert np.array_equal(g.wo_plain.cpu().numpy(), aux["wo_code"])
     assert np.array_equal(g.s_wo.cpu().numpy(), aux["s_wo"])
     # ---- K~ / V~ (Eq. 2)
     assert np.array_equal(g.kv["k_code"].astype(np.int32), kv.k_code)
@@ -239,3 +239,18 @@ def test_fused_and_general_paths_agree():
     assert dcode.max() <= 1 and np.mean(dcode != 0) < 2e-3
     max_abs, rel_l2 = G.out_errors(out2.cpu().numpy(), g.out)
     assert max_abs <= 1e-2 and rel_l2 <= 1e-3
+
+
+@pytest.mark.parametrize("C,H,N", [(320, 8, 200), (640, 8, 70), (640, 10, 45), (128, 2, 50)])
+def test_operand_ordered_weights_give_identical_results(C, H, N):
+    """shape.w_layout = 1 (weights re-laid out by taq_pack_weight) changes how the kernels read the weight
+    codes, not what they compute: parity with the oracle holds and the output is bit-identical to layout 0.
+    (128, 2) is a shape of the kernel-per-stage path, which reads the row-major part of the buffer.)"""
+    L = synth.make_layer("wpack", seed=C + H + N, B=2, N=N, C=C, H=H, Cc=64, T=77, bits_kv=8,
+                         trigger_positions=(3, 4), trigger_scale=3.0, bias=True)
+    g1 = check_layer(L, f"w_layout=1 C={C} H={H}", w_layout=1)
+    g0 = G.GpuRun(L, taps=False, w_layout=0)
+    assert np.array_equal(g1.out.view(np.uint16), g0.out.view(np.uint16))
+    # the buffer starts with the plain row-major codes
+    n = C * C
+    assert np.array_equal(g1.wq_code[:n].cpu().numpy().reshape(C, C), g1.wq_plain.cpu().numpy())
