@@ -39,7 +39,7 @@ def build_lib(verbose: bool = True) -> str:
         "-Wall", "-Wno-unused-function",
         "-I", os.path.join(os.path.dirname(HERE), "include"),
         "-o", LIB,
-    ] + srcs
+    ] + os.environ.get("TAQ_EXTRA_HIPCC_FLAGS", "").split() + srcs
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

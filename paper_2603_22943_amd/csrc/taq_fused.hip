@@ -29,6 +29,9 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 
 #define TAQ_NEG_INF (-__builtin_inff())
 #define TAQ_MAX_REQ 16
+#ifndef TAQ_NTT_40
+#define TAQ_NTT_40 2  // column tiles of 16 tokens per wavefront in the d = 40 instantiation
+#endif
 
 __device__ __forceinline__ int symq_code_f(float x, float qmaxf, float amax) {
     float t = x * qmaxf;
@@ -166,20 +169,21 @@ struct FusedDims {
     taq_debug dbg;     // taps (NULL pointers = off); only used when R == 1
 };
 
-template <int D, int NH>
+template <int D, int NH, int NTT>
 struct FusedCfg {
+    static constexpr int G = 2 / NTT;             // wavefronts per head (token groups of 16*NTT tokens)
     static constexpr int H = NH;
     static constexpr int C = D * H;
     static constexpr int TPH = (D + 15) / 16;     // 16-row tiles per head
     static constexpr int KS = (TPH + 3) / 4;      // K steps of 64 for S^T = K~ Q~^T
     static constexpr int FS = (TPH + 1) / 2;      // K steps of 32 for the protected-row scores
     static constexpr int KC = C / 64;             // K steps of 64 for the projections
-    static constexpr int NT = 64 * NH;            // threads: one wavefront per head
+    static constexpr int NT = 64 * NH * G;        // threads: G wavefronts per head
     static constexpr int TILE_RS = C + 16;        // bytes per token row of the int8 tile
     // bytes of one head's image block at T = 96, in 1 KiB pieces (one direct-to-LDS load each)
     static constexpr int IMG_HEAD_MAX = 96 * TPH * 16 + D * 96 + 3 * 96 * 4 + 32;
     static constexpr int IMGC = (IMG_HEAD_MAX + 1023) / 1024;
-    static constexpr bool PREFETCH_W = TPH * KC <= 16;  // whole weight slice of a head in registers
+    static constexpr bool PREFETCH_W = TPH * KC <= 16 && NTT == 2;  // whole weight slice of a head in registers
 };
 
 // Symmetric 8-bit codes of four values of one row, packed into a dword (low byte first).
@@ -237,14 +241,18 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
     b = *reinterpret_cast<const half2_t*>(&hi) - off;
 }
 
-// One wavefront per head, 32 image tokens per workgroup (two column tiles of 16 per wavefront).
-template <int D, int NH>
-__global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH + 3) / 4))) void fused_block_kernel(FusedTable tab, FusedDims dm) {
-    using F = FusedCfg<D, NH>;
+// 32 image tokens per workgroup. NTT = 2: one wavefront per head carrying two column tiles of 16 tokens
+// (A operands shared by both tiles). NTT = 1: two wavefronts per head, one tile each (16 wavefronts per CU
+// instead of 8: more latency hiding for twice the A-operand traffic).
+template <int D, int NH, int NTT>
+__global__ __launch_bounds__(64 * NH * (2 / NTT)) __attribute__((amdgpu_waves_per_eu(1, (NH * (2 / NTT) + 3) / 4)))
+void fused_block_kernel(FusedTable tab, FusedDims dm) {
+    using F = FusedCfg<D, NH, NTT>;
     constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x, h = tid >> 6, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
+    const int tid = threadIdx.x, h = (tid >> 6) % NH, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
+    const int tbase = ((tid >> 6) / NH) * 16 * NTT;  // first tile row of this wavefront's tokens
     const int RB = dm.R * dm.B;
     const int rb = blockIdx.x % RB, tile = blockIdx.x / RB;  // batch / request index fastest: one XCD, one K~/V~ image
     const int ri = rb / dm.B, b = rb % dm.B;
@@ -353,32 +361,32 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
     const __half* v16t = reinterpret_cast<const __half*>(packed + dm.L.v16t) + (size_t)b * C * 96;
 
     // this lane's two image tokens: tile rows r16 and 16 + r16
-    bool nvalid[2];
-    size_t tok[2];
+    bool nvalid[NTT];
+    size_t tok[NTT];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int n = n0 + 16 * nt + r16;
+    for (int nt = 0; nt < NTT; ++nt) {
+        const int n = n0 + tbase + 16 * nt + r16;
         nvalid[nt] = n < N;
         tok[nt] = (size_t)b * N + (n < N ? n : N - 1);
     }
 
     // ================= to_q for this head: Qf^T[c][n]
-    int32x4_t hb[2][KC];
+    int32x4_t hb[NTT][KC];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+    for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
         for (int ks = 0; ks < KC; ++ks)
-            hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
-    int32x4_t pacc[2][TPH];
+            hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
+    int32x4_t pacc[NTT][TPH];
 #pragma unroll
     for (int j = 0; j < TPH; ++j) {
-        pacc[0][j] = (int32x4_t){0, 0, 0, 0};
-        pacc[1][j] = (int32x4_t){0, 0, 0, 0};
+#pragma unroll
+        for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < KC; ++ks) {
             const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + wstep * ks);
-            pacc[0][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[0][ks], pacc[0][j], 0, 0, 0);
-            pacc[1][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[1][ks], pacc[1][j], 0, 0, 0);
+#pragma unroll
+            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
         }
     }
     // Everything the Q~ step reads from LDS is fetched now, so that no LDS access sits between the issue of the
@@ -389,7 +397,9 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
         const int cl = 16 * j + 4 * q;
         wq4[j] = *reinterpret_cast<const float4*>(swq + h * D + (((16 * j + 16 <= D) || cl < D) ? cl : 0));
     }
-    const float shv[2] = {s_h[r16], s_h[16 + r16]};
+    float shv[NTT];
+#pragma unroll
+    for (int nt = 0; nt < NTT; ++nt) shv[nt] = s_h[tbase + 16 * nt + r16];
     // This head's block of the K~/V~ image: straight into LDS, 1 KiB per wavefront-wide load (LDS address =
     // base + lane * 16), no registers in between; it travels while to_q and Q~ are computed, and only this
     // wavefront reads it, so only this wavefront waits for it. The last piece may be fetched more than once.
@@ -425,10 +435,10 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
     }
 
     // ---- Eq. (2), third line: Q~ = Q_a(Q) per (token, head)
-    unsigned qpk[2][TPH];
-    float sq2[2];
+    unsigned qpk[NTT][TPH];
+    float sq2[NTT];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < NTT; ++nt) {
         const float sh = shv[nt];
         float qf[TPH][4];
         float qmax = 0.f;
@@ -472,11 +482,11 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
 
 
     // ================= scores: x[t][n] = (K~ Q~^T)[t][n] * s_K[t]   (times sQ * sigma * log2 e later)
-    float S[2][6][4], Sf[2][6][4];
+    float S[NTT][6][4], Sf[NTT][6][4];
     {
-        int32x4_t qop[2][KS];  // B operand: dword jj of step ks = codes of tile 4*ks + jj
+        int32x4_t qop[NTT][KS];  // B operand: dword jj of step ks = codes of tile 4*ks + jj
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -485,7 +495,9 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
 #pragma unroll
         for (int tt = 0; tt < 6; ++tt) {
             if (tt < dm.nt16) {
-                int32x4_t a0 = (int32x4_t){0, 0, 0, 0}, a1 = (int32x4_t){0, 0, 0, 0};
+                int32x4_t acc[NTT];
+#pragma unroll
+                for (int nt = 0; nt < NTT; ++nt) acc[nt] = (int32x4_t){0, 0, 0, 0};
                 const int8_t* krow = kp + (16 * tt + r16) * (TPH * 16) + 4 * q;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
@@ -493,26 +505,25 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj)
                         ka[jj] = (4 * ks + jj < TPH) ? *reinterpret_cast<const int*>(krow + 16 * (4 * ks + jj)) : 0;
-                    a0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(ka, qop[0][ks], a0, 0, 0, 0);
-                    a1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(ka, qop[1][ks], a1, 0, 0, 0);
+#pragma unroll
+                    for (int nt = 0; nt < NTT; ++nt) acc[nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ka, qop[nt][ks], acc[nt], 0, 0, 0);
                 }
                 const float4 sk = *reinterpret_cast<const float4*>(img_sk + 16 * tt + 4 * q);
                 const float4 bi = *reinterpret_cast<const float4*>(img_bias + 16 * tt + 4 * q);
-                S[0][tt][0] = __builtin_fmaf((float)a0[0], sk.x, bi.x);
-                S[0][tt][1] = __builtin_fmaf((float)a0[1], sk.y, bi.y);
-                S[0][tt][2] = __builtin_fmaf((float)a0[2], sk.z, bi.z);
-                S[0][tt][3] = __builtin_fmaf((float)a0[3], sk.w, bi.w);
-                S[1][tt][0] = __builtin_fmaf((float)a1[0], sk.x, bi.x);
-                S[1][tt][1] = __builtin_fmaf((float)a1[1], sk.y, bi.y);
-                S[1][tt][2] = __builtin_fmaf((float)a1[2], sk.z, bi.z);
-                S[1][tt][3] = __builtin_fmaf((float)a1[3], sk.w, bi.w);
+#pragma unroll
+                for (int nt = 0; nt < NTT; ++nt) {
+                    S[nt][tt][0] = __builtin_fmaf((float)acc[nt][0], sk.x, bi.x);
+                    S[nt][tt][1] = __builtin_fmaf((float)acc[nt][1], sk.y, bi.y);
+                    S[nt][tt][2] = __builtin_fmaf((float)acc[nt][2], sk.z, bi.z);
+                    S[nt][tt][3] = __builtin_fmaf((float)acc[nt][3], sk.w, bi.w);
+                }
             }
         }
         // protected rows: fp16 K rows straight from global memory (a handful of rows)
         if (nfp > 0) {
-            half8_t qh[2][FS];  // Q~ codes as fp16: step s covers tiles 2s, 2s+1
+            half8_t qh[NTT][FS];  // Q~ codes as fp16: step s covers tiles 2s, 2s+1
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
+            for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
                 for (int s = 0; s < FS; ++s) {
                     half2_t c0 = {(_Float16)0.f, (_Float16)0.f}, c1 = c0, c2 = c0, c3 = c0;
@@ -523,7 +534,9 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
 #pragma unroll
             for (int ft = 0; ft < 6; ++ft) {
                 if (ft < nfp) {
-                    floatx4_t a0 = (floatx4_t){0.f, 0.f, 0.f, 0.f}, a1 = a0;
+                    floatx4_t facc[NTT];
+#pragma unroll
+                    for (int nt = 0; nt < NTT; ++nt) facc[nt] = (floatx4_t){0.f, 0.f, 0.f, 0.f};
                     int slot = 16 * ft + r16;
                     slot = slot < T ? slot : T - 1;
                     const __half* kr = k16 + (size_t)slot * C + h * D + 4 * q;
@@ -542,14 +555,14 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
                             ka[4 * jj + 2] = hv[2];
                             ka[4 * jj + 3] = hv[3];
                         }
-                        a0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qh[0][s], a0, 0, 0, 0);
-                        a1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qh[1][s], a1, 0, 0, 0);
+#pragma unroll
+                        for (int nt = 0; nt < NTT; ++nt) facc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qh[nt][s], facc[nt], 0, 0, 0);
                     }
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const bool live = 16 * ft + 4 * q + i < ntrig;
-                        Sf[0][ft][i] = live ? a0[i] : TAQ_NEG_INF;
-                        Sf[1][ft][i] = live ? a1[i] : TAQ_NEG_INF;
+#pragma unroll
+                        for (int nt = 0; nt < NTT; ++nt) Sf[nt][ft][i] = live ? facc[nt][i] : TAQ_NEG_INF;
                     }
                 }
             }
@@ -557,9 +570,9 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
     }
 
     // ================= softmax over the text tokens; Eq. (3); weights of O^T = V~^T A^^T
-    float kq[2];  // 255 / Z per image token
+    float kq[NTT];  // 255 / Z per image token
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < NTT; ++nt) {
         float mx = TAQ_NEG_INF;
 #pragma unroll
         for (int tt = 0; tt < 6; ++tt)
@@ -592,9 +605,9 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
         kq[nt] = 255.0f * __builtin_amdgcn_rcpf(Z);
     }
 
-    floatx4_t oacc[2][TPH];
+    floatx4_t oacc[NTT][TPH];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+    for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
         for (int jt = 0; jt < TPH; ++jt) oacc[nt][jt] = (floatx4_t){0.f, 0.f, 0.f, 0.f};
     if (nfp > 0) {
@@ -602,9 +615,9 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
 #pragma unroll
         for (int ft = 0; ft < 6; ++ft) {
             if (ft < nfp) {
-                half4_t phi[2], plo[2];
+                half4_t phi[NTT], plo[NTT];
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
+                for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const float x = Sf[nt][ft][i] * kq[nt];
@@ -619,7 +632,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
                     const uint2 w = ft == 0 ? v16r[jt] : *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 16 * ft + 4 * q);
                     const half4_t va = *reinterpret_cast<const half4_t*>(&w);  // slots past ntrig hold zeros
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt) {
+                    for (int nt = 0; nt < NTT; ++nt) {
                         oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, phi[nt], oacc[nt][jt], 0, 0, 0);
                         oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, plo[nt], oacc[nt][jt], 0, 0, 0);
                     }
@@ -628,7 +641,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
         }
         const float vpre = reinterpret_cast<const float*>(imgh + dm.I.vpre)[0];
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
             for (int jt = 0; jt < TPH; ++jt)
 #pragma unroll
@@ -641,14 +654,14 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
         for (int s = 0; s < 3; ++s) {
             if (2 * s < dm.nt16) {
                 const bool second = 2 * s + 1 < dm.nt16;
-                half8_t phi[2], plo[2];
+                half8_t phi[NTT], plo[NTT];
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
                     const float4 sv = *reinterpret_cast<const float4*>(img_svp + 16 * (2 * s + a) + 4 * q);
                     const float svv[4] = {sv.x, sv.y, sv.z, sv.w};
                     if (a == 0 || second) {
 #pragma unroll
-                        for (int nt = 0; nt < 2; ++nt)
+                        for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
                                 const float w = __builtin_rintf(S[nt][2 * s + a][i] * kq[nt]) * svv[i];  // Eq. (3)
@@ -658,7 +671,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
                             }
                     } else {
 #pragma unroll
-                        for (int nt = 0; nt < 2; ++nt)
+                        for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
                                 phi[nt][4 * a + i] = (_Float16)0.f;
@@ -676,7 +689,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
                     biased4_to_half(w.y, v2, v3);
                     const half8_t va = {v0[0], v0[1], v1[0], v1[1], v2[0], v2[1], v3[0], v3[1]};
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt) {
+                    for (int nt = 0; nt < NTT; ++nt) {
                         oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, phi[nt], oacc[nt][jt], 0, 0, 0);
                         oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, plo[nt], oacc[nt][jt], 0, 0, 0);
                     }
@@ -688,7 +701,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
     // ================= per-token int8 codes of O over all heads
     const float osc = reinterpret_cast<const float*>(imgh + dm.I.oscale)[0];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < NTT; ++nt) {
         float omx = 0.f;
 #pragma unroll
         for (int jt = 0; jt < TPH; ++jt) {
@@ -703,15 +716,15 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
                     make_float4(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3]);
         }
         omx = quad_allmax(omx);
-        if (q == 0) omax[(16 * nt + r16) * NH + h] = __float_as_uint(omx);
+        if (q == 0) omax[(tbase + 16 * nt + r16) * NH + h] = __float_as_uint(omx);
     }
     __syncthreads();  // every wavefront is past its reads of the hidden codes
-    float so[2];
+    float so[NTT];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < NTT; ++nt) {
         float oamax = 0.f;
 #pragma unroll
-        for (int w = 0; w < NH; ++w) oamax = fmaxf(oamax, __uint_as_float(omax[(16 * nt + r16) * NH + w]));
+        for (int w = 0; w < NH; ++w) oamax = fmaxf(oamax, __uint_as_float(omax[(tbase + 16 * nt + r16) * NH + w]));
         const bool ozero = oamax == 0.f;
         so[nt] = ozero ? 1.f : oamax / 127.f;
         const float osafe = ozero ? 1.f : oamax;
@@ -721,7 +734,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
             if (16 * jt + 4 * q < D) {
                 const unsigned pk = quant4_i8(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3], cq, osafe);
                 const int c = h * D + 16 * jt + 4 * q;
-                *reinterpret_cast<unsigned*>(tileq + (16 * nt + r16) * F::TILE_RS + c) = pk;
+                *reinterpret_cast<unsigned*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + c) = pk;
                 if (dm.dbg.o_code && nvalid[nt]) *reinterpret_cast<unsigned*>(dm.dbg.o_code + tok[nt] * C + c) = pk;
             }
         if (dm.dbg.s_o && nvalid[nt] && q == 0 && h == 0) dm.dbg.s_o[tok[nt]] = so[nt];
@@ -730,19 +743,19 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
 
     // ================= to_out: Y^T[c][n] for this head's D output channels
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+    for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
         for (int ks = 0; ks < KC; ++ks)
-            hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
+            hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
 #pragma unroll
     for (int j = 0; j < TPH; ++j) {
-        pacc[0][j] = (int32x4_t){0, 0, 0, 0};
-        pacc[1][j] = (int32x4_t){0, 0, 0, 0};
+#pragma unroll
+        for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < KC; ++ks) {
             const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + wstep * ks);
-            pacc[0][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[0][ks], pacc[0][j], 0, 0, 0);
-            pacc[1][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[1][ks], pacc[1][j], 0, 0, 0);
+#pragma unroll
+            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
         }
     }
 #pragma unroll
@@ -753,7 +766,7 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
             const float4 w4 = *reinterpret_cast<const float4*>(swo + c);
             const float4 b4 = *reinterpret_cast<const float4*>(bo + c);
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
+            for (int nt = 0; nt < NTT; ++nt) {
                 const float y0 = (float)pacc[nt][j][0] * (so[nt] * w4.x) + b4.x;
                 const float y1 = (float)pacc[nt][j][1] * (so[nt] * w4.y) + b4.y;
                 const float y2 = (float)pacc[nt][j][2] * (so[nt] * w4.z) + b4.z;
@@ -767,20 +780,20 @@ __global__ __launch_bounds__(64 * NH) __attribute__((amdgpu_waves_per_eu(1, (NH 
     }
 }
 
-template <int D, int NH>
+template <int D, int NH, int NTT>
 static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
-    using F = FusedCfg<D, NH>;
+    using F = FusedCfg<D, NH, NTT>;
     static bool attr_set = false;
     const size_t bytes = dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 + 32 * NH * 4;  // = fused_lds_bytes
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles = (dm.N + 31) / 32;
-    hipLaunchKernelGGL((fused_block_kernel<D, NH>), dim3(tiles * dm.R * dm.B), dim3(F::NT), bytes, st, tab, dm);
+    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT>), dim3(tiles * dm.R * dm.B), dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 
@@ -803,9 +816,9 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.I = kv_image(s);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
     dm.dbg = (dbg && R == 1) ? *dbg : none;
-    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8>(tab, dm, st);
-    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8>(tab, dm, st);
-    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10>(tab, dm, st);
+    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8, TAQ_NTT_40>(tab, dm, st);
+    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8, 2>(tab, dm, st);
+    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10, 2>(tab, dm, st);
     return hipErrorInvalidValue;
 }
 
