@@ -61,7 +61,7 @@ __device__ __forceinline__ int code_at(const uint8_t* codes, size_t row, int C, 
 
 __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ packed, KvLayout L, KvImage I, int T, int C,
                                                        int H, int bits) {
-    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x + 256 * blockIdx.z, nth = 256 * gridDim.z;
     const int d = C / H;
     const int* slot_of = reinterpret_cast<const int*>(packed + L.slot_of) + b * T;
     const float* s_k = reinterpret_cast<const float*>(packed + L.s_k) + ((size_t)b * H + h) * T;
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
     const uint8_t* v_code = packed + L.v_code;
     uint8_t* img = packed + L.image + (size_t)b * L.image_bytes + (size_t)h * I.head_bytes;  // this head's block
     __shared__ float vpre_s;
-    if (tid == 0) {  // per-head prescale: the largest |s_V * code| goes to [256, 512)
+    if (threadIdx.x == 0) {  // (every z-slice recomputes it; only slice 0 stores it)  // per-head prescale: the largest |s_V * code| goes to [256, 512)
         float smax = 0.f;
         for (int t = 0; t < T; ++t)
             if (slot_of[t] < 0) smax = fmaxf(smax, s_v[t]);
@@ -82,25 +82,27 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
             kexp = 9 - e;
         }
         vpre_s = ldexpf(1.0f, kexp);
-        reinterpret_cast<float*>(img + I.vpre)[0] = ldexpf(1.0f, kexp);
-        reinterpret_cast<float*>(img + I.oscale)[0] = ldexpf(1.0f, -kexp) / 255.0f;
+        if (blockIdx.z == 0) {
+            reinterpret_cast<float*>(img + I.vpre)[0] = ldexpf(1.0f, kexp);
+            reinterpret_cast<float*>(img + I.oscale)[0] = ldexpf(1.0f, -kexp) / 255.0f;
+        }
     }
     __syncthreads();
-    for (int t = tid; t < 96; t += 256) {
+    for (int t = tid; t < 96; t += nth) {
         const bool isint = t < T && slot_of[t] < 0;
         reinterpret_cast<float*>(img + I.s_k)[t] = isint ? s_k[t] : 0.f;
         reinterpret_cast<float*>(img + I.s_vp)[t] = isint ? s_v[t] * vpre_s : 0.f;
         reinterpret_cast<float*>(img + I.bias)[t] = isint ? 0.f : TAQ_NEG_INF;
     }
     const int rowb = I.tph * 16;  // bytes per (head, token) row of Kp
-    for (int i = tid; i < I.rows_k * rowb; i += 256) {
+    for (int i = tid; i < I.rows_k * rowb; i += nth) {
         const int e = i & 3, q = (i >> 2) & 3, tile = (i % rowb) >> 4, t = i / rowb;
         const int cl = 16 * tile + 4 * q + e;
         int v = 0;
         if (t < T && cl < d && slot_of[t] < 0) v = code_at(k_code, (size_t)b * T + t, C, h * d + cl, bits);
         img[I.kp + i] = (uint8_t)(v & 0xFF);
     }
-    for (int i = tid; i < d * I.cols_v; i += 256) {
+    for (int i = tid; i < d * I.cols_v; i += nth) {
         const int p = i % I.cols_v, j = i / I.cols_v;
         const int s = p >> 5, q = (p >> 3) & 3, a = (p >> 2) & 1, e = p & 3;
         const int t = 32 * s + 16 * a + 4 * q + e;
@@ -116,7 +118,7 @@ hipError_t launch_kv_image(uint8_t* packed, const taq_shape& s, hipStream_t st) 
     const KvLayout L = kv_layout(s);
     if (L.image_bytes == 0) return hipSuccess;
     const KvImage I = kv_image(s);
-    hipLaunchKernelGGL(kv_image_kernel, dim3(s.H, s.B), dim3(256), 0, st, packed, L, I, s.T, s.C, s.H, s.bits_kv);
+    hipLaunchKernelGGL(kv_image_kernel, dim3(s.H, s.B, 8), dim3(256), 0, st, packed, L, I, s.T, s.C, s.H, s.bits_kv);
     return hipGetLastError();
 }
 

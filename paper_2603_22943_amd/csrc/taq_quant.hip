@@ -160,23 +160,30 @@ hipError_t launch_headquant_f32(const float* x, int M, int C, int H, int8_t* cod
 }
 
 // ---------------------------------------------------------------- protected-token list
-__global__ void kv_mask_scan_kernel(const uint8_t* __restrict__ mask, int T, int bits, int* __restrict__ ntrig,
-                                    int* __restrict__ trig_idx, int* __restrict__ slot_of) {
-    const int b = blockIdx.x;
-    if (threadIdx.x != 0) return;
-    int n = 0;
-    for (int t = 0; t < T; ++t) {
-        const bool prot = bits == 16 || mask[b * T + t] != 0;
-        slot_of[b * T + t] = prot ? n : -1;
-        if (prot) trig_idx[b * T + n++] = t;
+__global__ __launch_bounds__(128) void kv_mask_scan_kernel(const uint8_t* __restrict__ mask, int T, int bits,
+                                                            int* __restrict__ ntrig, int* __restrict__ trig_idx,
+                                                            int* __restrict__ slot_of) {
+    __shared__ int flag[128];
+    const int b = blockIdx.x, t = threadIdx.x;
+    const bool prot = t < T && (bits == 16 || mask[b * T + t] != 0);
+    flag[t] = prot ? 1 : 0;
+    __syncthreads();
+    int before = 0, total = 0;  // T <= 96: a direct count is cheaper than a scan
+    for (int u = 0; u < T; ++u) {
+        before += (u < t) ? flag[u] : 0;
+        total += flag[u];
     }
-    for (int s = n; s < T; ++s) trig_idx[b * T + s] = -1;
-    ntrig[b] = n;
+    if (t < T) {
+        slot_of[b * T + t] = prot ? before : -1;
+        if (prot) trig_idx[b * T + before] = t;
+        if (t >= total) trig_idx[b * T + t] = -1;
+    }
+    if (t == 0) ntrig[b] = total;
 }
 
 hipError_t launch_kv_mask_scan(const uint8_t* mask, int B, int T, int bits, int* ntrig, int* trig_idx,
                                int* slot_of, hipStream_t st) {
-    hipLaunchKernelGGL(kv_mask_scan_kernel, dim3(B), dim3(64), 0, st, mask, T, bits, ntrig, trig_idx, slot_of);
+    hipLaunchKernelGGL(kv_mask_scan_kernel, dim3(B), dim3(128), 0, st, mask, T, bits, ntrig, trig_idx, slot_of);
     return hipGetLastError();
 }
 
@@ -244,8 +251,9 @@ hipError_t launch_kv_pack(const float* rows_f, const int* slot_of, int B, int T,
 }
 
 // ---------------------------------------------------------------- protected K/V rows
-// One workgroup per (slot, batch): y[c] = s_w[c] * sum_k ctx[t][k] * w_code[c][k], float32
-// accumulation in four partial sums, one rounding to fp16. Cc % 16 == 0, Cc <= 4096.
+// One workgroup per (slot, batch, 64 output channels): y[c] = s_w[c] * sum_k ctx[t][k] * w_code[c][k].
+// Four threads share an output channel, each summing every fourth 16-code piece of the row in float32 (four
+// partial sums per thread), combined by two shuffles; one rounding to fp16. Cc % 16 == 0, Cc <= 4096.
 __global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __restrict__ context,
                                                               const int8_t* __restrict__ w_code,
                                                               const float* __restrict__ s_w,
@@ -256,15 +264,18 @@ __global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __re
                                                               __half* __restrict__ v16t) {
     __shared__ float xs[4096];
     const int slot = blockIdx.x, b = blockIdx.y;
-    // unused slots of the transposed copy read as zeros: the padding slots T..95 (last block) ...
-    if (slot == T - 1)
-        for (int c = threadIdx.x; c < C; c += 256)
-            for (int sp = T; sp < 96; ++sp) v16t[((size_t)b * C + c) * 96 + sp] = __float2half(0.f);
-    if (slot >= ntrig[b]) {  // ... and every slot past the protected tokens, in all three copies
-        for (int c = threadIdx.x; c < C; c += 256) {
-            v16t[((size_t)b * C + c) * 96 + slot] = __float2half(0.f);
-            k16[((size_t)b * T + slot) * C + c] = __float2half(0.f);
-            v16[((size_t)b * T + slot) * C + c] = __float2half(0.f);
+    const int c = blockIdx.z * 64 + (threadIdx.x >> 2), part = threadIdx.x & 3;  // output channel in [0, 2C)
+    // unused slots of all three copies read as zeros: the padding slots T..95 of the transposed copy ...
+    if (slot == T - 1 && c >= C && c < 2 * C && part == 0)
+        for (int sp = T; sp < 96; ++sp) v16t[((size_t)b * C + (c - C)) * 96 + sp] = __float2half(0.f);
+    if (slot >= ntrig[b]) {  // ... and every slot past the protected tokens
+        if (c < 2 * C && part == 0) {
+            if (c < C) {
+                k16[((size_t)b * T + slot) * C + c] = __float2half(0.f);
+            } else {
+                v16[((size_t)b * T + slot) * C + (c - C)] = __float2half(0.f);
+                v16t[((size_t)b * C + (c - C)) * 96 + slot] = __float2half(0.f);
+            }
         }
         return;
     }
@@ -272,35 +283,42 @@ __global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __re
     const __half* xr = context + ((size_t)b * T + t) * Cc;
     for (int k = threadIdx.x; k < Cc; k += 256) xs[k] = __half2float(xr[k]);
     __syncthreads();
-    for (int c = threadIdx.x; c < 2 * C; c += 256) {
+    float sum = 0.f;
+    if (c < 2 * C) {
         const int4* wr = reinterpret_cast<const int4*>(w_code + (size_t)c * Cc);
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int kv = 0; kv < (Cc >> 4); ++kv) {
-            int4 w = wr[kv];
+        for (int kv = part; kv < (Cc >> 4); kv += 4) {
+            const int4 w = wr[kv];
             const int wd[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int qd = 0; qd < 4; ++qd) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float wf = (float)(int)(int8_t)((wd[q] >> (8 * e)) & 0xFF);
-                    acc[e] = __builtin_fmaf(xs[kv * 16 + q * 4 + e], wf, acc[e]);
+                    const float wf = (float)(int)(int8_t)((wd[qd] >> (8 * e)) & 0xFF);
+                    acc[e] = __builtin_fmaf(xs[kv * 16 + qd * 4 + e], wf, acc[e]);
                 }
             }
         }
-        float sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-        float y = sum * s_w[c];
-        const __half yh = __float2half_rn(y);
-        __half* dst = c < C ? k16 : v16;
-        dst[((size_t)b * T + slot) * C + (c < C ? c : c - C)] = yh;
-        if (c >= C) v16t[((size_t)b * C + (c - C)) * 96 + slot] = yh;  // transposed copy, slot along the row
+        sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    }
+    sum += __shfl_xor(sum, 1);
+    sum += __shfl_xor(sum, 2);
+    if (c < 2 * C && part == 0) {
+        const __half yh = __float2half_rn(sum * s_w[c]);
+        if (c < C) {
+            k16[((size_t)b * T + slot) * C + c] = yh;
+        } else {
+            v16[((size_t)b * T + slot) * C + (c - C)] = yh;
+            v16t[((size_t)b * C + (c - C)) * 96 + slot] = yh;  // transposed copy, slot along the row
+        }
     }
 }
 
 hipError_t launch_kv_trigger_rows(const __half* context, const int8_t* w_code, const float* s_w,
                                   const int* ntrig, const int* trig_idx, int B, int T, int C, int Cc,
                                   __half* k16, __half* v16, __half* v16t, hipStream_t st) {
-    hipLaunchKernelGGL(kv_trigger_rows_kernel, dim3(T, B), dim3(256), 0, st, context, w_code, s_w, ntrig,
-                       trig_idx, T, C, Cc, k16, v16, v16t);
+    hipLaunchKernelGGL(kv_trigger_rows_kernel, dim3(T, B, (2 * C + 63) / 64), dim3(256), 0, st, context, w_code, s_w,
+                       ntrig, trig_idx, T, C, Cc, k16, v16, v16t);
     return hipGetLastError();
 }
 

@@ -68,9 +68,13 @@ def check_layer(L, label="", w_layout=0):
     O_ref = aux["O"]
     scale_o = max(np.abs(O_ref).max(), 1e-30)
     dO = np.abs(g.taps["O"].astype(np.float64) - O_ref)
-    frac_far = float(np.mean(dO > 2e-5 * scale_o))
+    # float32 vs float64 arithmetic keeps O within ~1e-6 of its scale; a protected K/V row that differs from the
+    # oracle's by its allowed single fp16 step (5e-4 relative) shifts the scores of a head or a whole channel
+    rows_equal = np.array_equal(g.kv["K16"].astype(np.float64), kv.K16) and np.array_equal(g.kv["V16"].astype(np.float64), kv.V16)
+    far = 2e-5 if rows_equal else 1e-3
+    frac_far = float(np.mean(dO > far * scale_o))
     dcode = np.abs(g.taps["o_code"].astype(np.int32) - aux["o_code"])
-    print(f"    O: max|d|/max|O|={dO.max() / scale_o:.3e} frac(>2e-5)={frac_far:.3e}  "
+    print(f"    O: max|d|/max|O|={dO.max() / scale_o:.3e} frac(>{far:g})={frac_far:.3e}  "
           f"o_code mismatches={float(np.mean(dcode != 0)):.3e} max={int(dcode.max())}", flush=True)
     assert dO.max() <= 0.02 * scale_o
     assert frac_far < 5e-3
