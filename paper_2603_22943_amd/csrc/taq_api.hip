@@ -178,11 +178,20 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
 
     if (stages & TAQ_STAGE_HIDDEN_QUANT)
         TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(hidden), M, s.C, h_code, s_h, st));
-    if (stages & TAQ_STAGE_TO_Q)
+    const bool mid = mid_supported(s) && !(dbg && dbg->stage_mask);
+    if (mid) {
+        // to_q, Q~ and the attention in one kernel per head group; the token codes and A^ V~ pass through the workspace
+        FusedReq rq = {static_cast<const __half*>(hidden), static_cast<const uint8_t*>(qkv_packed), Wq, Wo, scales,
+                       static_cast<__half*>(out)};
+        taq_debug d2 = dbg ? *dbg : taq_debug{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
+        // (this path keeps no dense Q~ array in the workspace: the q_code / s_Q taps are written by the kernel itself)
+        TAQ_TRY_HIP(launch_fused_mid(rq, s, h_code, s_h, o_f, &d2, st));
+    }
+    if (!mid && (stages & TAQ_STAGE_TO_Q))
         TAQ_TRY_HIP(launch_gemm_i8(h_code, s_h, Wq, s_wq, nullptr, M, s.C, s.C, q_f, nullptr, s.C, st));
-    if (stages & TAQ_STAGE_Q_QUANT)
+    if (!mid && (stages & TAQ_STAGE_Q_QUANT))
         TAQ_TRY_HIP(launch_headquant_f32(q_f, M, s.C, s.H, q_code, s_q, st));
-    if (stages & TAQ_STAGE_ATTN_CORE)
+    if (!mid && (stages & TAQ_STAGE_ATTN_CORE))
         TAQ_TRY_HIP(launch_attn_core(q_code, s_q, static_cast<const uint8_t*>(qkv_packed), s, o_f, st));
     if (stages & TAQ_STAGE_O_QUANT)
         TAQ_TRY_HIP(launch_rowquant_f32(o_f, M, s.C, o_code, s_o, st));
@@ -193,8 +202,8 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
         const size_t MC = (size_t)M * s.C;
         if (dbg->h_code) TAQ_TRY_HIP(hipMemcpyAsync(dbg->h_code, h_code, MC, hipMemcpyDeviceToDevice, st));
         if (dbg->s_h) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_h, s_h, (size_t)M * 4, hipMemcpyDeviceToDevice, st));
-        if (dbg->q_code) TAQ_TRY_HIP(hipMemcpyAsync(dbg->q_code, q_code, MC, hipMemcpyDeviceToDevice, st));
-        if (dbg->s_Q) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_Q, s_q, (size_t)M * s.H * 4, hipMemcpyDeviceToDevice, st));
+        if (dbg->q_code && !mid) TAQ_TRY_HIP(hipMemcpyAsync(dbg->q_code, q_code, MC, hipMemcpyDeviceToDevice, st));
+        if (dbg->s_Q && !mid) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_Q, s_q, (size_t)M * s.H * 4, hipMemcpyDeviceToDevice, st));
         if (dbg->O) TAQ_TRY_HIP(hipMemcpyAsync(dbg->O, o_f, MC * 4, hipMemcpyDeviceToDevice, st));
         if (dbg->o_code) TAQ_TRY_HIP(hipMemcpyAsync(dbg->o_code, o_code, MC, hipMemcpyDeviceToDevice, st));
         if (dbg->s_o) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_o, s_o, (size_t)M * 4, hipMemcpyDeviceToDevice, st));

@@ -169,12 +169,16 @@ struct FusedDims {
     KvLayout L;
     KvImage I;
     taq_debug dbg;     // taps (NULL pointers = off); only used when R == 1
+    // head-group variant (NG > 1): token codes come from / A^ V~ goes to the workspace
+    const int8_t* ws_hcode;  // i8  [B*N][C]
+    const float* ws_sh;      // f32 [B*N]
+    float* ws_of;            // f32 [B*N][C]
 };
 
-template <int D, int NH, int NTT>
+template <int D, int NH, int NTT, int NG>
 struct FusedCfg {
     static constexpr int G = 2 / NTT;             // wavefronts per head (token groups of 16*NTT tokens)
-    static constexpr int H = NH;
+    static constexpr int H = NH * NG;             // heads of the layer; a workgroup owns NH of them
     static constexpr int C = D * H;
     static constexpr int TPH = (D + 15) / 16;     // 16-row tiles per head
     static constexpr int KS = (TPH + 3) / 4;      // K steps of 64 for S^T = K~ Q~^T
@@ -185,7 +189,7 @@ struct FusedCfg {
     // bytes of one head's image block at T = 96, in 1 KiB pieces (one direct-to-LDS load each)
     static constexpr int IMG_HEAD_MAX = 96 * TPH * 16 + D * 96 + 3 * 96 * 4 + 32;
     static constexpr int IMGC = (IMG_HEAD_MAX + 1023) / 1024;
-    static constexpr bool PREFETCH_W = TPH * KC <= 16 && NTT == 2;  // whole weight slice of a head in registers
+    static constexpr bool PREFETCH_W = TPH * KC <= 16 && NTT == 2 && NG == 1;  // a head's whole weight slice in registers
 };
 
 // Symmetric 8-bit codes of four values of one row, packed into a dword (low byte first).
@@ -246,14 +250,18 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // 32 image tokens per workgroup. NTT = 2: one wavefront per head carrying two column tiles of 16 tokens
 // (A operands shared by both tiles). NTT = 1: two wavefronts per head, one tile each (16 wavefronts per CU
 // instead of 8: more latency hiding for twice the A-operand traffic).
-template <int D, int NH, int NTT>
+// NG > 1 (layers too wide for one workgroup's LDS): the workgroup owns head group blockIdx.y (NH of the NH*NG
+// heads), takes the per-token codes of `hidden` from the workspace, and stops after A^ V~, which it writes to
+// the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
+template <int D, int NH, int NTT, int NG>
 __global__ __launch_bounds__(64 * NH * (2 / NTT)) __attribute__((amdgpu_waves_per_eu(1, (NH * (2 / NTT) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
-    using F = FusedCfg<D, NH, NTT>;
+    using F = FusedCfg<D, NH, NTT, NG>;
     constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x, h = (tid >> 6) % NH, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
+    const int tid = threadIdx.x, hl = (tid >> 6) % NH, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
+    const int h = (NG > 1 ? (int)blockIdx.y * NH : 0) + hl;  // head of the layer; hl = head within the workgroup
     const int tbase = ((tid >> 6) / NH) * 16 * NTT;  // first tile row of this wavefront's tokens
     const int RB = dm.R * dm.B;
     const int rb = blockIdx.x % RB, tile = blockIdx.x / RB;  // batch / request index fastest: one XCD, one K~/V~ image
@@ -263,53 +271,17 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     const int n0 = tile * 32;
 
     // ---- LDS carve-up
-    unsigned char* img = smem;                                  // K~/V~ image
-    const size_t img_bytes = dm.I.bytes;
+    unsigned char* img = smem;                                  // K~/V~ image blocks of this workgroup's heads
+    const size_t img_bytes = (size_t)NH * dm.I.head_bytes;
     int8_t* tileq = reinterpret_cast<int8_t*>(smem + img_bytes);                // [32][C+16] hidden codes, later O codes
     float* wsc = reinterpret_cast<float*>(smem + img_bytes + 32 * F::TILE_RS);  // s_wq | s_wo | bias_o  [3C]
-    float* s_h = wsc + 3 * C;                                    // [32]
+    float* s_h = wsc + (NG == 1 ? 3 * C : 0);                    // [32]  (NG > 1: no weight scales in LDS)
     unsigned* omax = reinterpret_cast<unsigned*>(s_h + 32);      // [32][NH]
 
     const uint8_t* packed = rq.packed;
     const int ntrig = reinterpret_cast<const int*>(packed + dm.L.ntrig)[b];
     const int nfp = (ntrig + 15) >> 4;  // tiles of 16 protected tokens
 
-    // ---- phase 0: issue every global read up front, oldest first in the order of use (loads return in
-    // order): hidden tile, weight scales, this head's to_q weight slice, the K~/V~ image
-    const int tok0 = tid >> 4, part0 = tid & 15;  // 16 threads per token, 4 channels per load (first 512 threads)
-    const int nq0 = n0 + tok0;
-    const size_t row0 = (size_t)b * N + (nq0 < N ? nq0 : N - 1);
-    uint2 xin[KC];
-    if (tid < 512) {
-        const uint2* xr = reinterpret_cast<const uint2*>(rq.hidden + row0 * C);
-#pragma unroll
-        for (int it = 0; it < KC; ++it) xin[it] = xr[it * 16 + part0];
-    }
-    constexpr int SCV = (3 * C / 4 + NT - 1) / NT;
-    float4 scv[SCV];
-#pragma unroll
-    for (int k = 0; k < SCV; ++k) {
-        const int i = tid + k * NT;
-        scv[k] = i < 3 * C / 4 ? reinterpret_cast<const float4*>(rq.scales)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-    // ---- per-token int8 codes of the hidden tile
-    float x[KC][4];
-    float amax = 0.f;
-    if (tid < 512) {
-#pragma unroll
-        for (int it = 0; it < KC; ++it) {
-            const __half2* hh = reinterpret_cast<const __half2*>(&xin[it]);
-            const float2 p0 = __half22float2(hh[0]), p1 = __half22float2(hh[1]);
-            x[it][0] = p0.x;
-            x[it][1] = p0.y;
-            x[it][2] = p1.x;
-            x[it][3] = p1.y;
-            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(p0.x), fabsf(p0.y)), fmaxf(fabsf(p1.x), fabsf(p1.y))));
-        }
-    }
-    // The hidden tile has arrived (the unpacking above waited for it). Only now are the 10x larger weight reads
-    // issued: the texture path serves requests in arrival order, and the first barrier waits for nothing else.
-    __builtin_amdgcn_sched_barrier(0);
     // weight rows of this head: row c = h*D + 16*j + r16 (rows past the head are discarded; clamp keeps reads in bounds)
     // (byte offset of K step ks = wrow[j] + ks * wstep; with the operand-ordered copy a wavefront-wide load is
     // one contiguous KiB, otherwise 16 rows x 64 bytes)
@@ -320,42 +292,92 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         const int c = h * D + 16 * j + r16;
         wrow[j] = dm.w_layout ? (int)dm.w_pack_off + ((h * TPH + j) * KC) * 1024 + lane * 16 : (c < C ? c : C - 1) * C + 16 * q;
     }
-    // The weight slice is fetched a few loads at a time between pieces of arithmetic: a wavefront stalls at a
-    // vector-memory instruction while the texture unit's queue is full (it coalesces 64 B per clock, and every
-    // CU pulls ~300 KB of weights and image per launch), so the requests are spread under the ALU work.
     int32x4_t wreg[F::PREFETCH_W ? TPH : 1][F::PREFETCH_W ? KC : 1];
-    amax = row16_allmax(amax);
-    const bool zero0 = amax == 0.f;
-    const float sc0 = zero0 ? 1.f : amax / 127.f;
-    const float safe0 = zero0 ? 1.f : amax;
-    const float cq0 = 127.f * __builtin_amdgcn_rcpf(safe0);
-    if (tid < 512 && part0 == 0) s_h[tok0] = sc0;
-#pragma unroll
-    for (int it = 0; it < KC; ++it) {
-        if (F::PREFETCH_W) {
-#pragma unroll
-            for (int j = 0; j < TPH; ++j) wreg[j][it] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + wstep * it);
-        }
+    if constexpr (NG == 1) {
+        // ---- phase 0: issue every global read up front, oldest first in the order of use (loads return in
+        // order): hidden tile, weight scales, this head's to_q weight slice, the K~/V~ image
+        const int tok0 = tid >> 4, part0 = tid & 15;  // 16 threads per token, 4 channels per load (first 512 threads)
+        const int nq0 = n0 + tok0;
+        const size_t row0 = (size_t)b * N + (nq0 < N ? nq0 : N - 1);
+        uint2 xin[KC];
         if (tid < 512) {
-            const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq0, safe0);
-            *reinterpret_cast<unsigned*>(tileq + tok0 * F::TILE_RS + (it * 16 + part0) * 4) = pk;
-            if (dm.dbg.h_code && nq0 < N) *reinterpret_cast<unsigned*>(dm.dbg.h_code + row0 * C + (it * 16 + part0) * 4) = pk;
+            const uint2* xr = reinterpret_cast<const uint2*>(rq.hidden + row0 * C);
+    #pragma unroll
+            for (int it = 0; it < KC; ++it) xin[it] = xr[it * 16 + part0];
         }
+        constexpr int SCV = (3 * C / 4 + NT - 1) / NT;
+        float4 scv[SCV];
+    #pragma unroll
+        for (int k = 0; k < SCV; ++k) {
+            const int i = tid + k * NT;
+            scv[k] = i < 3 * C / 4 ? reinterpret_cast<const float4*>(rq.scales)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        // ---- per-token int8 codes of the hidden tile
+        float x[KC][4];
+        float amax = 0.f;
+        if (tid < 512) {
+    #pragma unroll
+            for (int it = 0; it < KC; ++it) {
+                const __half2* hh = reinterpret_cast<const __half2*>(&xin[it]);
+                const float2 p0 = __half22float2(hh[0]), p1 = __half22float2(hh[1]);
+                x[it][0] = p0.x;
+                x[it][1] = p0.y;
+                x[it][2] = p1.x;
+                x[it][3] = p1.y;
+                amax = fmaxf(amax, fmaxf(fmaxf(fabsf(p0.x), fabsf(p0.y)), fmaxf(fabsf(p1.x), fabsf(p1.y))));
+            }
+        }
+        // The hidden tile has arrived (the unpacking above waited for it). Only now are the 10x larger weight reads
+        // issued: the texture path serves requests in arrival order, and the first barrier waits for nothing else.
         __builtin_amdgcn_sched_barrier(0);
-    }
-    if (tid < 512 && dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc0;
-    // ---- weight scales and the K~/V~ image into LDS
-#pragma unroll
-    for (int k = 0; k < SCV; ++k) {
-        const int i = tid + k * NT;
-        if (i < 3 * C / 4) reinterpret_cast<float4*>(wsc)[i] = scv[k];
+        // The weight slice is fetched a few loads at a time between pieces of arithmetic: a wavefront stalls at a
+        // vector-memory instruction while the texture unit's queue is full (it coalesces 64 B per clock, and every
+        // CU pulls ~300 KB of weights and image per launch), so the requests are spread under the ALU work.
+        amax = row16_allmax(amax);
+        const bool zero0 = amax == 0.f;
+        const float sc0 = zero0 ? 1.f : amax / 127.f;
+        const float safe0 = zero0 ? 1.f : amax;
+        const float cq0 = 127.f * __builtin_amdgcn_rcpf(safe0);
+        if (tid < 512 && part0 == 0) s_h[tok0] = sc0;
+    #pragma unroll
+        for (int it = 0; it < KC; ++it) {
+            if (F::PREFETCH_W) {
+    #pragma unroll
+                for (int j = 0; j < TPH; ++j) wreg[j][it] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + wstep * it);
+            }
+            if (tid < 512) {
+                const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq0, safe0);
+                *reinterpret_cast<unsigned*>(tileq + tok0 * F::TILE_RS + (it * 16 + part0) * 4) = pk;
+                if (dm.dbg.h_code && nq0 < N) *reinterpret_cast<unsigned*>(dm.dbg.h_code + row0 * C + (it * 16 + part0) * 4) = pk;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (tid < 512 && dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc0;
+        // ---- weight scales and the K~/V~ image into LDS
+    #pragma unroll
+        for (int k = 0; k < SCV; ++k) {
+            const int i = tid + k * NT;
+            if (i < 3 * C / 4) reinterpret_cast<float4*>(wsc)[i] = scv[k];
+        }
+    } else {
+        // token codes of the hidden tile (written by the per-token quantizer kernel) into the padded LDS tile
+        for (int v = tid; v < 32 * (C / 16); v += NT) {
+            const int tk = v / (C / 16), col = (v % (C / 16)) * 16;
+            const int n = n0 + tk;
+            const size_t row = (size_t)b * N + (n < N ? n : N - 1);
+            *reinterpret_cast<uint4*>(tileq + tk * F::TILE_RS + col) = *reinterpret_cast<const uint4*>(dm.ws_hcode + row * C + col);
+        }
+        if (tid < 32) {
+            const int n = n0 + tid;
+            s_h[tid] = dm.ws_sh[(size_t)b * N + (n < N ? n : N - 1)];
+        }
     }
     __syncthreads();
 
     const float* swq = wsc;
     const float* swo = wsc + C;
     const float* bo = wsc + 2 * C;
-    unsigned char* imgh = img + (size_t)h * dm.I.head_bytes;  // this head's block of the K~/V~ image
+    unsigned char* imgh = img + (size_t)hl * dm.I.head_bytes;  // this head's block of the K~/V~ image
     const float* img_sk = reinterpret_cast<const float*>(imgh + dm.I.s_k);
     const float* img_svp = reinterpret_cast<const float*>(imgh + dm.I.s_vp);
     const float* img_bias = reinterpret_cast<const float*>(imgh + dm.I.bias);
@@ -397,7 +419,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
     for (int j = 0; j < TPH; ++j) {
         const int cl = 16 * j + 4 * q;
-        wq4[j] = *reinterpret_cast<const float4*>(swq + h * D + (((16 * j + 16 <= D) || cl < D) ? cl : 0));
+        wq4[j] = *reinterpret_cast<const float4*>((NG == 1 ? swq : rq.scales) + h * D + (((16 * j + 16 <= D) || cl < D) ? cl : 0));
     }
     float shv[NTT];
 #pragma unroll
@@ -717,9 +739,17 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 *reinterpret_cast<float4*>(dm.dbg.O + tok[nt] * C + h * D + 16 * jt + 4 * q) =
                     make_float4(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3]);
         }
+        if constexpr (NG > 1) {
+#pragma unroll
+            for (int jt = 0; jt < TPH; ++jt)
+                if (nvalid[nt] && ((16 * jt + 16 <= D) || 16 * jt + 4 * q < D))
+                    *reinterpret_cast<float4*>(dm.ws_of + tok[nt] * C + h * D + 16 * jt + 4 * q) =
+                        make_float4(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3]);
+        }
         omx = quad_allmax(omx);
-        if (q == 0) omax[(tbase + 16 * nt + r16) * NH + h] = __float_as_uint(omx);
+        if (NG == 1 && q == 0) omax[(tbase + 16 * nt + r16) * NH + hl] = __float_as_uint(omx);
     }
+    if constexpr (NG > 1) return;  // the per-token quantization of A^ V~ and to_out are separate kernels
     __syncthreads();  // every wavefront is past its reads of the hidden codes
     float so[NTT];
 #pragma unroll
@@ -782,20 +812,21 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 }
 
-template <int D, int NH, int NTT>
+template <int D, int NH, int NTT, int NG>
 static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
-    using F = FusedCfg<D, NH, NTT>;
+    using F = FusedCfg<D, NH, NTT, NG>;
     static bool attr_set = false;
-    const size_t bytes = dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 + 32 * NH * 4;  // = fused_lds_bytes
+    const size_t bytes = NG == 1 ? dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 + 32 * NH * 4  // = fused_lds_bytes
+                                 : (size_t)NH * dm.I.head_bytes + 32 * F::TILE_RS + 32 * 4;             // = mid_lds_bytes
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles = (dm.N + 31) / 32;
-    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT>), dim3(tiles * dm.R * dm.B), dim3(F::NT), bytes, st, tab, dm);
+    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 
@@ -818,9 +849,46 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.I = kv_image(s);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
     dm.dbg = (dbg && R == 1) ? *dbg : none;
-    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8, TAQ_NTT_40>(tab, dm, st);
-    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8, 2>(tab, dm, st);
-    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10, 2>(tab, dm, st);
+    dm.ws_hcode = nullptr;
+    dm.ws_sh = nullptr;
+    dm.ws_of = nullptr;
+    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8, TAQ_NTT_40, 1>(tab, dm, st);
+    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8, 2, 1>(tab, dm, st);
+    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10, 2, 1>(tab, dm, st);
+    return hipErrorInvalidValue;
+}
+
+// Head-group variant: to_q, Q~ and the attention for layers too wide for one workgroup (C = 1280).
+hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, const int8_t* h_code, const float* s_h, float* o_f,
+                            const taq_debug* dbg, hipStream_t st) {
+    if (!mid_supported(s)) return hipErrorInvalidValue;
+    FusedTable tab;
+    for (int r = 0; r < TAQ_MAX_REQ; ++r) tab.req[r] = rq;
+    FusedDims dm;
+    dm.R = 1;
+    dm.B = s.B;
+    dm.N = s.N;
+    dm.T = s.T;
+    dm.nt16 = (s.T + 15) / 16;
+    dm.w_layout = s.w_layout;
+    dm.w_pack_off = (unsigned)weight_pack_offset(s);
+    const int d = s.C / s.H;
+    const float sigma = s.softmax_scale != 0.f ? s.softmax_scale : 1.0f / sqrtf((float)d);
+    dm.sig2 = sigma * 1.4426950408889634f;
+    dm.L = kv_layout(s);
+    dm.I = kv_image(s);
+    taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
+    dm.dbg = dbg ? *dbg : none;
+    dm.dbg.h_code = nullptr;  // taps of the stages this kernel does not run are served by the caller
+    dm.dbg.s_h = nullptr;
+    dm.dbg.O = nullptr;
+    dm.dbg.o_code = nullptr;
+    dm.dbg.s_o = nullptr;
+    dm.ws_hcode = h_code;
+    dm.ws_sh = s_h;
+    dm.ws_of = o_f;
+    if (d == 160 && s.H == 8) return launch_fused_cfg<160, 1, 1, 8>(tab, dm, st);
+    if (d == 64 && s.H == 20) return launch_fused_cfg<64, 2, 1, 10>(tab, dm, st);
     return hipErrorInvalidValue;
 }
 

@@ -97,6 +97,21 @@ static inline bool fused_supported(const taq_shape& s) {
     return fused_lds_bytes(s) <= 160 * 1024;
 }
 
+// Shapes of the head-group variant (to_q + Q~ + attention per head group; C = 1280 layers):
+// (d, H) = (160, 8) with one head per workgroup, (64, 20) with two.
+static inline size_t mid_lds_bytes(const taq_shape& s) {
+    const int d = s.C / s.H;
+    const size_t nh = d == 160 ? 1 : 2;
+    return nh * kv_image(s).head_bytes + 32 * ((size_t)s.C + 16) + 32 * 4;
+}
+static inline bool mid_supported(const taq_shape& s) {
+    if (s.bits_kv != 4 && s.bits_kv != 8) return false;
+    if (s.C % s.H) return false;
+    const int d = s.C / s.H;
+    if (!((d == 160 && s.H == 8) || (d == 64 && s.H == 20))) return false;
+    return mid_lds_bytes(s) <= 160 * 1024;
+}
+
 static inline KvLayout kv_layout(const taq_shape& s) {
     KvLayout L;
     size_t off = 0;
@@ -113,7 +128,7 @@ static inline KvLayout kv_layout(const taq_shape& s) {
     L.k16 = take(B * T * C * 2);
     L.v16 = take(B * T * C * 2);
     L.v16t = take(B * C * 96 * 2);
-    L.image_bytes = fused_supported(s) ? align_up(kv_image(s).bytes, 256) : 0;
+    L.image_bytes = (fused_supported(s) || mid_supported(s)) ? align_up(kv_image(s).bytes, 256) : 0;
     L.image = take(B * L.image_bytes);
     L.total = off;
     return L;
@@ -218,6 +233,9 @@ struct FusedReq {
 };
 // Whole block in one kernel (shapes of fused_supported only). dbg may be NULL.
 hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, const taq_debug* dbg, hipStream_t st);
+// to_q + Q~ + attention per head group (shapes of mid_supported): reads token codes, writes float32 A^ V~.
+hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, const int8_t* h_code, const float* s_h, float* o_f,
+                            const taq_debug* dbg, hipStream_t st);
 
 // Attention core: scores, softmax, Eq. (3), A^ V~ for all (batch, head, token).
 hipError_t launch_attn_core(const int8_t* q_code, const float* s_q, const uint8_t* packed,
