@@ -195,8 +195,13 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
         TAQ_TRY_HIP(launch_attn_core(q_code, s_q, static_cast<const uint8_t*>(qkv_packed), s, o_f, st));
     if (stages & TAQ_STAGE_O_QUANT)
         TAQ_TRY_HIP(launch_rowquant_f32(o_f, M, s.C, o_code, s_o, st));
-    if (stages & TAQ_STAGE_TO_OUT)
+    if (mid) {
+        FusedReq rq = {static_cast<const __half*>(hidden), static_cast<const uint8_t*>(qkv_packed), Wq, Wo, scales,
+                       static_cast<__half*>(out)};
+        TAQ_TRY_HIP(launch_to_out_tail(rq, s, o_code, s_o, st));
+    } else if (stages & TAQ_STAGE_TO_OUT) {
         TAQ_TRY_HIP(launch_gemm_i8(o_code, s_o, Wo, s_wo, bias_o, M, s.C, s.C, nullptr, static_cast<__half*>(out), s.C, st));
+    }
 
     if (dbg) {
         const size_t MC = (size_t)M * s.C;

@@ -812,6 +812,78 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 }
 
+// to_out for the head-group shapes (C = 1280, head dimension a multiple of 16): Y^T[c][n] = Wo[c][:] . o_code[n][:].
+// A workgroup owns 32 image tokens and OT output tiles of 16 channels; one wavefront per (output tile, token group
+// of 16), so that each wavefront has only C/64 weight loads in front of its MFMAs. The per-token codes and scales
+// of A^ V~ come from the workspace (ws_hcode / ws_sh carry them for this kernel). Same operand layout and epilogue
+// as the last phase of the fused kernel.
+template <int C, int OT>
+__global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, FusedDims dm) {
+    constexpr int KC = C / 64, NT = 128 * OT, TILE_RS = C + 16;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
+    const int gt = (int)blockIdx.y * OT + (wave % OT);  // output tile of the layer: channels 16*gt .. 16*gt+15
+    const int tl = (wave / OT) * 16 + r16;              // this lane's token within the 32-token tile
+    const int b = blockIdx.x % dm.B, tile = blockIdx.x / dm.B;
+    const FusedReq rq = tab.req[0];
+    const int N = dm.N, n0 = tile * 32;
+    int8_t* tileq = reinterpret_cast<int8_t*>(smem);               // [32][C+16]
+    float* s_o = reinterpret_cast<float*>(smem + 32 * TILE_RS);    // [32]
+    // weights first (they do not depend on the tile), then the tile
+    const int cr = 16 * gt + r16;
+    const int wrow = dm.w_layout ? (int)dm.w_pack_off + (gt * KC) * 1024 + lane * 16 : cr * C + 16 * q;
+    const int wstep = dm.w_layout ? 1024 : 64;
+    int32x4_t wa[KC];
+#pragma unroll
+    for (int ks = 0; ks < KC; ++ks) wa[ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow + wstep * ks);
+    for (int v = tid; v < 32 * (C / 16); v += NT) {
+        const int tk = v / (C / 16), col = (v % (C / 16)) * 16;
+        const int n = n0 + tk;
+        const size_t row = (size_t)b * N + (n < N ? n : N - 1);
+        *reinterpret_cast<uint4*>(tileq + tk * TILE_RS + col) = *reinterpret_cast<const uint4*>(dm.ws_hcode + row * C + col);
+    }
+    if (tid < 32) {
+        const int n = n0 + tid;
+        s_o[tid] = dm.ws_sh[(size_t)b * N + (n < N ? n : N - 1)];
+    }
+    __syncthreads();
+    const int n = n0 + tl;
+    const size_t tok = (size_t)b * N + (n < N ? n : N - 1);
+    const float so = s_o[tl];
+    int32x4_t acc = (int32x4_t){0, 0, 0, 0};
+#pragma unroll
+    for (int ks = 0; ks < KC; ++ks) {
+        const int32x4_t hb = *reinterpret_cast<const int32x4_t*>(tileq + tl * TILE_RS + 64 * ks + 16 * q);
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa[ks], hb, acc, 0, 0, 0);
+    }
+    const int c = 16 * gt + 4 * q;
+    const float4 w4 = *reinterpret_cast<const float4*>(rq.scales + C + c);
+    const float4 b4 = *reinterpret_cast<const float4*>(rq.scales + 2 * C + c);
+    const float y0 = (float)acc[0] * (so * w4.x) + b4.x;
+    const float y1 = (float)acc[1] * (so * w4.y) + b4.y;
+    const float y2 = (float)acc[2] * (so * w4.z) + b4.z;
+    const float y3 = (float)acc[3] * (so * w4.w) + b4.w;
+    if (n < N) {
+        const half4_t y = {(_Float16)y0, (_Float16)y1, (_Float16)y2, (_Float16)y3};
+        *reinterpret_cast<half4_t*>(rq.out + tok * C + c) = y;
+    }
+}
+
+template <int C, int OT>
+static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
+    const size_t bytes = 32 * (C + 16) + 32 * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&to_out_tail_kernel<C, OT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles = (dm.N + 31) / 32;
+    hipLaunchKernelGGL((to_out_tail_kernel<C, OT>), dim3(tiles * dm.B, C / 16 / OT), dim3(128 * OT), bytes, st, tab, dm);
+    return hipGetLastError();
+}
+
 template <int D, int NH, int NTT, int NG>
 static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     using F = FusedCfg<D, NH, NTT, NG>;
@@ -889,6 +961,24 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, const int8_t
     dm.ws_of = o_f;
     if (d == 160 && s.H == 8) return launch_fused_cfg<160, 1, 1, 8>(tab, dm, st);
     if (d == 64 && s.H == 20) return launch_fused_cfg<64, 2, 1, 10>(tab, dm, st);
+    return hipErrorInvalidValue;
+}
+
+// to_out for the head-group shapes, from the per-token codes and scales of A^ V~ in the workspace.
+hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const int8_t* o_code, const float* s_o, hipStream_t st) {
+    if (!mid_supported(s)) return hipErrorInvalidValue;
+    FusedTable tab;
+    for (int r = 0; r < TAQ_MAX_REQ; ++r) tab.req[r] = rq;
+    FusedDims dm = {};
+    dm.R = 1;
+    dm.B = s.B;
+    dm.N = s.N;
+    dm.T = s.T;
+    dm.w_layout = s.w_layout;
+    dm.w_pack_off = (unsigned)weight_pack_offset(s);
+    dm.ws_hcode = o_code;
+    dm.ws_sh = s_o;
+    if (s.C == 1280) return launch_tail_cfg<1280, 8>(tab, dm, st);
     return hipErrorInvalidValue;
 }
 

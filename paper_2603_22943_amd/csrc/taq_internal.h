@@ -236,6 +236,7 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
 // to_q + Q~ + attention per head group (shapes of mid_supported): reads token codes, writes float32 A^ V~.
 hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, const int8_t* h_code, const float* s_h, float* o_f,
                             const taq_debug* dbg, hipStream_t st);
+hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const int8_t* o_code, const float* s_o, hipStream_t st);
 
 // Attention core: scores, softmax, Eq. (3), A^ V~ for all (batch, head, token).
 hipError_t launch_attn_core(const int8_t* q_code, const float* s_q, const uint8_t* packed,
