@@ -402,15 +402,50 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         for (int ks = 0; ks < KC; ++ks)
             hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
     int32x4_t pacc[NTT][TPH];
+    if constexpr (F::PREFETCH_W) {
 #pragma unroll
-    for (int j = 0; j < TPH; ++j) {
+        for (int j = 0; j < TPH; ++j) {
 #pragma unroll
-        for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
+            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
-        for (int ks = 0; ks < KC; ++ks) {
-            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + wstep * ks);
+            for (int ks = 0; ks < KC; ++ks)
 #pragma unroll
-            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
+                for (int nt = 0; nt < NTT; ++nt)
+                    pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wreg[j][ks], hb[nt][ks], pacc[nt][j], 0, 0, 0);
+        }
+    } else if constexpr (NG == 1) {
+#pragma unroll
+        for (int j = 0; j < TPH; ++j) {
+#pragma unroll
+            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < KC; ++ks) {
+                const int32x4_t wa = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + wstep * ks);
+#pragma unroll
+                for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
+            }
+        }
+    } else {
+        // few wavefronts per CU here: the weight slice of the next 16-row tile is put in flight explicitly while the
+        // current tile's MFMAs run
+        int32x4_t wb[2][KC];
+#pragma unroll
+        for (int ks = 0; ks < KC; ++ks) wb[0][ks] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[0] + wstep * ks);
+#pragma unroll
+        for (int j = 0; j < TPH; ++j) {
+            if (j + 1 < TPH) {
+#pragma unroll
+                for (int ks = 0; ks < KC; ++ks)
+                    wb[(j + 1) & 1][ks] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j + 1 < TPH ? j + 1 : 0] + wstep * ks);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the loads ahead of the MFMAs of tile j
+#pragma unroll
+            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < KC; ++ks)
+#pragma unroll
+                for (int nt = 0; nt < NTT; ++nt)
+                    pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wb[j & 1][ks], hb[nt][ks], pacc[nt][j], 0, 0, 0);
         }
     }
     // Everything the Q~ step reads from LDS is fetched now, so that no LDS access sits between the issue of the
