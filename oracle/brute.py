@@ -66,7 +66,7 @@ def symq_f32(row, bits):
     return codes, scale
 
 
-def taq_block_brute(context, mask, Wq, Wk, Wv, Wo, bias_o, hidden, H, bits_kv):
+def taq_block_brute(context, mask, Wq, Wk, Wv, Wo, bias_o, hidden, H, bits_kv, bits_q=8, bits_prob=8):
     """context [B][T][Cc], mask [B][T], W* [C][in], hidden [B][N][C] as nested
     lists / arrays of fp16-valued numbers. Returns out [B][N][C] (Python floats,
     rounded through fp16) and a dict of intermediates."""
@@ -135,7 +135,7 @@ def taq_block_brute(context, mask, Wq, Wk, Wv, Wo, bias_o, hidden, H, bits_kv):
             O = [0.0] * C
             for h in range(H):
                 # ---- Q~ = Q_a(Q), Eq. (2) third line
-                qc, qs = symq_f32(Qf[h * d:(h + 1) * d], 8)
+                qc, qs = symq_f32(Qf[h * d:(h + 1) * d], bits_q)
                 for j in range(d):
                     dump["q_code"][(b, n, h * d + j)] = qc[j]
                 # ---- A = softmax(Q~ K~^T / sqrt(d))
@@ -155,9 +155,10 @@ def taq_block_brute(context, mask, Wq, Wk, Wv, Wo, bias_o, hidden, H, bits_kv):
                     if trig[t]:
                         Ah.append(A[t])
                     else:
-                        pc = int(np.rint(_f32(_f32(A[t]) * _f32(255.0))))
+                        pmax = (1 << bits_prob) - 1
+                        pc = int(np.rint(_f32(_f32(A[t]) * _f32(pmax))))
                         dump["p_code"][(b, n, h, t)] = pc
-                        Ah.append(pc / 255.0)
+                        Ah.append(pc / float(pmax))
                 # ---- O = A^ V~
                 for j in range(d):
                     s = 0.0

@@ -77,13 +77,22 @@ def symq(x, bits: int, axis: int = -1):
     return code, np.squeeze(scale, axis=axis)
 
 
-def uq8(p):
-    """Unsigned 8-bit quantizer of a probability in [0,1] (reading: the affine
+def uq(p, bits: int = 8):
+    """Unsigned b-bit quantizer of a probability in [0,1] (reading: the affine
     quantizer with the a-priori range of a softmax output, zero-point 0, fixed
-    scale 1/255):  code = rint(p * 255) in float32, half-to-even."""
+    scale 1/(2^b - 1)):  code = rint(p * (2^b - 1)) in float32, half-to-even.
+    b = 8 gives the 1/255 grid, b = 4 (the paper's 4-bit activation setting) 1/15."""
+    if bits not in (4, 8):
+        raise ValueError("uq: bits must be 4 or 8")
+    pmax = f32((1 << bits) - 1)
     p32 = np.asarray(p, dtype=f32)
-    code = np.rint((p32 * f32(255.0)).astype(f32))
-    return np.clip(code, 0, 255).astype(np.int32)
+    code = np.rint((p32 * pmax).astype(f32))
+    return np.clip(code, 0, int(pmax)).astype(np.int32)
+
+
+def uq8(p):
+    """8-bit case of ``uq``."""
+    return uq(p, 8)
 
 
 def pack_int4(codes):
@@ -237,9 +246,9 @@ def cross_attn(hidden, kv: QuantKV, wq_code, s_wq, wo_code, s_wo, bias_o=None,
 
     Steps, in the paper's order:
       Q  = to_q(hidden)                       (W8A8: reading)
-      Q~ = Q_a(Q)                             Eq. (2), third line; per (token, head): reading
+      Q~ = Q_a(Q)                             Eq. (2), third line; per (token, head): reading; 8 or 4 bits
       A  = softmax(Q~ K~^T / sqrt(d))         attention definition, per head
-      A^ = M_A*A + (1-M_A)*Q_a(A)             Eq. (3); no renormalisation
+      A^ = M_A*A + (1-M_A)*Q_a(A)             Eq. (3); no renormalisation; 8 or 4 bits
       O  = A^ V~
       out = to_out(O) + bias                  (W8A8: reading), stored as fp16
     With bits_proj == 16 the two projections use ``Wq_f16`` / ``Wo_f16`` unquantized.
@@ -260,14 +269,14 @@ def cross_attn(hidden, kv: QuantKV, wq_code, s_wq, wo_code, s_wo, bias_o=None,
     aux["Qf"] = Qf
 
     # ---- Q~ = Q_a(Q)
-    if bits_q == 8:
-        q_code, s_Q = symq(np.asarray(Qf, dtype=f32).reshape(B, N, H, d), 8, axis=-1)
+    if bits_q in (4, 8):
+        q_code, s_Q = symq(np.asarray(Qf, dtype=f32).reshape(B, N, H, d), bits_q, axis=-1)
         Qt = q_code.astype(f64) * s_Q.astype(f64)[..., None]  # [B,N,H,d]
         aux.update(q_code=q_code.reshape(B, N, C), s_Q=s_Q)
     elif bits_q == 16:
         Qt = np.asarray(Qf, dtype=f64).reshape(B, N, H, d)
     else:
-        raise ValueError("bits_q must be 8 or 16")
+        raise ValueError("bits_q must be 4, 8 or 16")
 
     # ---- K~, V~ as matrices (Eq. 2), split by head
     Kt = kv.dequant("k").reshape(B, T, H, d)
@@ -282,14 +291,14 @@ def cross_attn(hidden, kv: QuantKV, wq_code, s_wq, wo_code, s_wo, bias_o=None,
 
     # ---- A^ (Eq. 3): trigger columns keep A, the others are quantized
     M_A = kv.mask[:, None, None, :]  # [B,1,1,T] -> broadcast over N and heads
-    if bits_prob == 8:
-        p_code = uq8(A)
-        A_q = p_code.astype(f64) / 255.0
+    if bits_prob in (4, 8):
+        p_code = uq(A, bits_prob)
+        A_q = p_code.astype(f64) / f64((1 << bits_prob) - 1)
         aux["p_code"] = p_code
     elif bits_prob == 16:
         A_q = A
     else:
-        raise ValueError("bits_prob must be 8 or 16")
+        raise ValueError("bits_prob must be 4, 8 or 16")
     A_hat = np.where(M_A, A, A_q)
     aux["A_hat"] = A_hat
 

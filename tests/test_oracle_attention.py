@@ -257,3 +257,61 @@ def test_int4_codes_and_scales_shapes_and_ranges():
     for b in range(L.B):
         for t in (0, 5, 12):
             assert np.array_equal(acc[b, t], wc.astype(np.int64) @ xc[b, t].astype(np.int64))
+
+
+# ---------------------------------------------------------------- 4-bit activations (the paper's "8/4" setting)
+
+def test_a4_uniform_scores_closed_form():
+    """4-bit probabilities: 1/77 rounds to code 0 on the 1/15 grid, so with uniform scores every unprotected
+    column vanishes and only the protected column (kept exactly, Eq. 3) reaches the output: O = V_trigger / 77."""
+    B, N, H, d, T = 1, 3, 2, 4, 77
+    C = H * d
+    mask = np.zeros((B, T), dtype=bool)
+    mask[0, 5] = True
+    v_row = np.arange(1, C + 1, dtype=np.float64) / 8.0
+    v_code = np.zeros((B, T, C), dtype=np.int32)
+    v_code[:, ~mask[0]] = 7
+    s_V = np.full((B, H, T), 0.5, dtype=np.float32)
+    V16 = np.zeros((B, T, C))
+    V16[0, 5] = v_row
+    kv = O.QuantKV(B=B, T=T, C=C, H=H, bits_kv=4, mask=mask, k_code=np.zeros((B, T, C), dtype=np.int32), v_code=v_code,
+                   s_K=np.ones((B, H, T), dtype=np.float32), s_V=s_V, K16=np.zeros((B, T, C)), V16=V16)
+    hidden = np.random.Generator(np.random.PCG64(1)).standard_normal((B, N, C)).astype(np.float16)
+    wq, swq = O.quantize_weight(np.eye(C, dtype=np.float16))
+    out, aux = O.cross_attn(hidden, kv, wq, swq, wq, swq, bits_prob=4, bits_q=4, return_aux=True)
+    assert np.all(aux["p_code"] == 0)
+    assert np.max(np.abs(aux["O"] - v_row[None, None, :] / 77.0)) < 1e-14
+    assert np.abs(aux["q_code"]).max() == 7
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=21, B=1, N=4, C=8, H=2, T=5, Cc=6, bits_kv=4, trig=(1,)),
+    dict(seed=22, B=2, N=3, C=4, H=1, T=4, Cc=5, bits_kv=8, trig=()),
+])
+def test_a4_block_matches_scalar_brute_force(case):
+    L = synth.make_layer("t", seed=case["seed"], B=case["B"], N=case["N"], C=case["C"], H=case["H"], T=case["T"],
+                         Cc=case["Cc"], bits_kv=case["bits_kv"], trigger_positions=case["trig"], trigger_scale=3.0, bias=True)
+    out, aux = O.taq_block(L, bits_prob=4, bits_q=4, return_aux=True)
+    ref, dump = brute.taq_block_brute(L.context, L.mask, L.Wq, L.Wk, L.Wv, L.Wo, L.bias_o, L.hidden, L.H, L.bits_kv,
+                                      bits_q=4, bits_prob=4)
+    for (b, n, c), v in dump["q_code"].items():
+        assert aux["q_code"][b, n, c] == v and abs(v) <= 7
+    for (b, n, h, t), v in dump["p_code"].items():
+        assert aux["p_code"][b, n, h, t] == v and 0 <= v <= 15
+    for (b, n, c), v in dump["o_code"].items():
+        assert aux["o_code"][b, n, c] == v
+    ref = np.array(ref)
+    assert np.max(np.abs(out.astype(np.float64) - ref)) <= 1e-3 * max(1.0, np.abs(ref).max())
+
+
+def test_a4_is_coarser_than_a8_and_trigger_columns_still_pass_through():
+    L = small_layer(N=64)
+    ref = O.taq_block(L, bits_prob=16, bits_q=16, bits_proj=16, bits_kv=16, store_f16=False)
+    out8, aux8 = O.taq_block(L, return_aux=True)
+    out4, aux4 = O.taq_block(L, bits_prob=4, bits_q=4, return_aux=True)
+    e8 = np.linalg.norm(out8.astype(np.float64) - ref) / np.linalg.norm(ref)
+    e4 = np.linalg.norm(out4.astype(np.float64) - ref) / np.linalg.norm(ref)
+    assert e8 < e4 < 1.0
+    assert np.array_equal(aux4["A_hat"][..., [2, 3]], aux4["A"][..., [2, 3]])
+    g = aux4["A_hat"][..., [t for t in range(L.T) if t not in (2, 3)]] * 15.0
+    assert np.max(np.abs(g - np.rint(g))) < 1e-12

@@ -140,3 +140,16 @@ def test_bops_ratios_match_table1():
         assert rows[(model, "32/32")] / rows[(model, "8/4")] == pytest.approx(32.0, rel=0.02)
     # MAC count of the block, by hand, for a 1-token case
     assert O.block_bops(B=1, N=1, C=2, T=3, Cc=5, b_w=1, b_a=1) == 2.0 * (4 + 2 * 3 * 5 * 2 + 2 * 3 * 2 + 4)
+
+
+def test_uq4_known_values_and_bound():
+    # the 4-bit probability grid 1/15: 1/77 rounds to 0, 0.5*15 = 7.5 -> 8 (even), 0.1*15 = 1.5 -> 2 (even)
+    p = np.array([0.0, 1.0, 1.0 / 77.0, 0.5, 0.1, 0.0333, 0.0334])
+    code = O.uq(p, 4)
+    assert list(code) == [0, 15, 0, 8, 2, 0, 1]
+    grid = np.linspace(0.0, 1.0, 20001)
+    c = O.uq(grid, 4)
+    assert np.all(np.abs(c / 15.0 - grid) <= 1.0 / 30.0 + 1e-7) and np.all(np.diff(c) >= 0)
+    assert c.min() == 0 and c.max() == 15
+    with pytest.raises(ValueError):
+        O.uq(p, 5)
