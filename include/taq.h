@@ -15,7 +15,7 @@
  *     scale = amax/qmax, qmax = 2^(b-1)-1, all in IEEE float32, rint half-to-even;
  *   - rows: K/V per (head, text token); Q per (image token, head); hidden states and
  *     the attention output per image token; weights per output channel (8 bit);
- *   - Q_a on probabilities is the fixed grid code = rint(255*A), A^ = code/255;
+ *   - Q_a on probabilities is the fixed grid code = rint(pmax*A), A^ = code/pmax, pmax = 2^b - 1 (255 or 15);
  *   - to_q, to_out and the K/V projections of unprotected tokens are W8A8 integer
  *     contractions; protected K/V rows are computed from the unquantized fp16 context
  *     row (with the 8-bit weight codes) and stored as fp16.
@@ -54,8 +54,8 @@ typedef enum taq_status {
 typedef struct taq_shape {
     int B, N, C, H, T, Cc;   /* d = C / H                                                   */
     int bits_kv;             /* 4 | 8 : width of unprotected K/V rows; 16 : keep every row fp16 */
-    int bits_prob;           /* 8 : probabilities on the 1/255 grid outside trigger columns  */
-    int bits_q;              /* 8 : Q~ = Q_a(Q)                                              */
+    int bits_prob;           /* 8 | 4 : probabilities on the 1/255 or 1/15 grid outside trigger columns */
+    int bits_q;              /* 8 | 4 : Q~ = Q_a(Q), qmax = 127 or 7 (codes stay one per byte)  */
     int bits_proj;           /* 8 : W8A8 projections                                         */
     float softmax_scale;     /* 0 => 1/sqrt(d)                                               */
     int w_layout;            /* layout of the Wq / Wo buffers given to taq_cross_attn:

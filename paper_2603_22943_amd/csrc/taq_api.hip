@@ -14,7 +14,8 @@ int check_shape(const taq_shape* s, bool need_n) {
     if (s->B <= 0 || s->C <= 0 || s->H <= 0 || s->T <= 0 || s->Cc <= 0) return TAQ_ERR_INVALID_ARG;
     if (need_n && s->N <= 0) return TAQ_ERR_INVALID_ARG;
     if (s->bits_kv != 4 && s->bits_kv != 8 && s->bits_kv != 16) return TAQ_ERR_UNSUPPORTED_BITS;
-    if (s->bits_prob != 8 || s->bits_q != 8 || s->bits_proj != 8) return TAQ_ERR_UNSUPPORTED_BITS;
+    if ((s->bits_prob != 8 && s->bits_prob != 4) || (s->bits_q != 8 && s->bits_q != 4) || s->bits_proj != 8)
+        return TAQ_ERR_UNSUPPORTED_BITS;
     if (s->C % s->H != 0) return TAQ_ERR_BAD_SHAPE;
     const int d = s->C / s->H;
     if (d % 8 != 0 || d > TAQ_MAX_D) return TAQ_ERR_BAD_SHAPE;
@@ -190,7 +191,7 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
     if (!mid && (stages & TAQ_STAGE_TO_Q))
         TAQ_TRY_HIP(launch_gemm_i8(h_code, s_h, Wq, s_wq, nullptr, M, s.C, s.C, q_f, nullptr, s.C, st));
     if (!mid && (stages & TAQ_STAGE_Q_QUANT))
-        TAQ_TRY_HIP(launch_headquant_f32(q_f, M, s.C, s.H, q_code, s_q, st));
+        TAQ_TRY_HIP(launch_headquant_f32(q_f, M, s.C, s.H, s.bits_q, q_code, s_q, st));
     if (!mid && (stages & TAQ_STAGE_ATTN_CORE))
         TAQ_TRY_HIP(launch_attn_core(q_code, s_q, static_cast<const uint8_t*>(qkv_packed), s, o_f, st));
     if (stages & TAQ_STAGE_O_QUANT)

@@ -68,6 +68,7 @@ struct CoreArgs {
     float* o_f;             // [B][N][C]
     int N, C, H, T, bits;
     float sig2;             // softmax scale * log2(e)
+    float pmax;             // 255 or 15: grid of the probabilities (Eq. 3)
 };
 
 __device__ __forceinline__ int load_code(const uint8_t* codes, size_t row, int C, int c, int bits) {
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
                 half8_t phi, plo;  // protected columns keep A: 255*A as fp16 high + low parts
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float x = (Sf[ft][8 * blk + e] * inv) * 255.0f;
+                    const float x = (Sf[ft][8 * blk + e] * inv) * a.pmax;
                     const _Float16 xh = (_Float16)x;
                     phi[e] = xh;
                     plo[e] = (_Float16)(x - (float)xh);
@@ -325,7 +326,7 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
                 half8_t p;  // Eq. (3): integer probability codes, exact in fp16
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    p[e] = (_Float16)__builtin_rintf((S[tile][8 * blk + e] * inv) * 255.0f);
+                    p[e] = (_Float16)__builtin_rintf((S[tile][8 * blk + e] * inv) * a.pmax);
 #pragma unroll
                 for (int jt = 0; jt < DT; ++jt) {
                     const int o = (32 * jt + r) * L::RS_V + 32 * tile + 16 * blk + 8 * half;
@@ -340,7 +341,7 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
     // ---------------- store O (float32): lane holds channels 32*jt + 8*g + 4*half + 0..3
     if (nvalid) {
         float* orow = a.o_f + tok * C + h * d;
-        const float k = ldexpf(1.0f, -kexp) / 255.0f;
+        const float k = ldexpf(1.0f, -kexp) / a.pmax;
 #pragma unroll
         for (int jt = 0; jt < DT; ++jt)
 #pragma unroll
@@ -393,6 +394,7 @@ hipError_t launch_attn_core(const int8_t* q_code, const float* s_q, const uint8_
     const int d = s.C / s.H;
     const float sigma = s.softmax_scale != 0.f ? s.softmax_scale : 1.0f / sqrtf((float)d);
     a.sig2 = sigma * 1.4426950408889634f;
+    a.pmax = s.bits_prob == 4 ? 15.f : 255.f;
     switch ((d + 31) / 32) {
         case 1: return launch_core_dt<1>(a, s.B, st);
         case 2: return launch_core_dt<2>(a, s.B, st);

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
         vpre_s = ldexpf(1.0f, kexp);
         if (blockIdx.z == 0) {
             reinterpret_cast<float*>(img + I.vpre)[0] = ldexpf(1.0f, kexp);
-            reinterpret_cast<float*>(img + I.oscale)[0] = ldexpf(1.0f, -kexp) / 255.0f;
+            reinterpret_cast<float*>(img + I.oscale)[0] = ldexpf(1.0f, -kexp);
         }
     }
     __syncthreads();
@@ -166,6 +166,8 @@ struct FusedDims {
     int w_layout;      // 1: Wq / Wo carry an operand-ordered copy at w_pack_off
     unsigned w_pack_off;
     float sig2;        // softmax scale * log2(e)
+    float qmaxq;       // 127 or 7: grid of Q~ (Eq. 2, third line)
+    float pmax;        // 255 or 15: grid of the probabilities (Eq. 3)
     KvLayout L;
     KvImage I;
     taq_debug dbg;     // taps (NULL pointers = off); only used when R == 1
@@ -193,12 +195,14 @@ struct FusedCfg {
 };
 
 // Symmetric 8-bit codes of four values of one row, packed into a dword (low byte first).
-//   exact definition: code = rint((x * 127) / amax) with IEEE float32 multiply and divide.
+//   exact definition: code = rint((x * qmax) / amax) with IEEE float32 multiply and divide (qmax = 127, or 7 for
+//   4-bit Q~; the bounds below are stated for 127 and only shrink for 7).
 //   fast path: q0 = x * c with c = 127 * rcp(amax) (rcp within 1 ulp). q0 lies within 4 * 2^-24 * 127 = 3.0e-5
 //   of the exact ratio and the defined quotient within 2 * 2^-24 * 127 = 1.5e-5, so both round to the same
 //   integer unless q0 is within 4.6e-5 of a half-integer; those (rare) lanes redo the four values by the
 //   definition. Rounding uses the 1.5 * 2^23 trick: the low mantissa byte of q0 + magic is the code's byte.
-__device__ __forceinline__ unsigned quant4_i8(float x0, float x1, float x2, float x3, float c, float amax) {
+__device__ __forceinline__ unsigned quant4_i8(float x0, float x1, float x2, float x3, float c, float amax,
+                                              float qmaxf = 127.f) {
     const float magic = 12582912.0f;
     const float q0 = x0 * c, q1 = x1 * c, q2 = x2 * c, q3 = x3 * c;
     const float m0 = q0 + magic, m1 = q1 + magic, m2 = q2 + magic, m3 = q3 + magic;
@@ -208,8 +212,8 @@ __device__ __forceinline__ unsigned quant4_i8(float x0, float x1, float x2, floa
     const unsigned hi = __builtin_amdgcn_perm(__float_as_uint(m3), __float_as_uint(m2), 0x0c0c0400u);
     unsigned pk = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
     if (fmaxf(fmaxf(d0, d1), fmaxf(d2, d3)) > 0.49995f)
-        pk = pack4(symq_code_f(x0, 127.f, amax), symq_code_f(x1, 127.f, amax), symq_code_f(x2, 127.f, amax),
-                   symq_code_f(x3, 127.f, amax));
+        pk = pack4(symq_code_f(x0, qmaxf, amax), symq_code_f(x1, qmaxf, amax), symq_code_f(x2, qmaxf, amax),
+                   symq_code_f(x3, qmaxf, amax));
     return pk;
 }
 
@@ -516,11 +520,11 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         }
         qmax = quad_allmax(qmax);
         const bool qzero = qmax == 0.f;
-        const float sQ = qzero ? 1.f : qmax / 127.f;
+        const float sQ = qzero ? 1.f : qmax / dm.qmaxq;
         const float qsafe = qzero ? 1.f : qmax;
-        const float cq = 127.f * __builtin_amdgcn_rcpf(qsafe);
+        const float cq = dm.qmaxq * __builtin_amdgcn_rcpf(qsafe);
 #pragma unroll
-        for (int j = 0; j < TPH; ++j) qpk[nt][j] = quant4_i8(qf[j][0], qf[j][1], qf[j][2], qf[j][3], cq, qsafe);
+        for (int j = 0; j < TPH; ++j) qpk[nt][j] = quant4_i8(qf[j][0], qf[j][1], qf[j][2], qf[j][3], cq, qsafe, dm.qmaxq);
         if (dm.dbg.q_code && nvalid[nt]) {
 #pragma unroll
             for (int j = 0; j < TPH; ++j)
@@ -629,7 +633,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 
     // ================= softmax over the text tokens; Eq. (3); weights of O^T = V~^T A^^T
-    float kq[NTT];  // 255 / Z per image token
+    float kq[NTT];  // pmax / Z per image token (pmax = 255 or 15)
 #pragma unroll
     for (int nt = 0; nt < NTT; ++nt) {
         float mx = TAQ_NEG_INF;
@@ -661,7 +665,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 }
             }
         Z = quad_allsum(Z);
-        kq[nt] = 255.0f * __builtin_amdgcn_rcpf(Z);
+        kq[nt] = dm.pmax * __builtin_amdgcn_rcpf(Z);
     }
 
     floatx4_t oacc[NTT][TPH];
@@ -758,7 +762,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 
     // ================= per-token int8 codes of O over all heads
-    const float osc = reinterpret_cast<const float*>(imgh + dm.I.oscale)[0];
+    const float osc = reinterpret_cast<const float*>(imgh + dm.I.oscale)[0] * (1.0f / dm.pmax);
 #pragma unroll
     for (int nt = 0; nt < NTT; ++nt) {
         float omx = 0.f;
@@ -952,6 +956,8 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     const int d = s.C / s.H;
     const float sigma = s.softmax_scale != 0.f ? s.softmax_scale : 1.0f / sqrtf((float)d);
     dm.sig2 = sigma * 1.4426950408889634f;
+    dm.qmaxq = s.bits_q == 4 ? 7.f : 127.f;
+    dm.pmax = s.bits_prob == 4 ? 15.f : 255.f;
     dm.L = kv_layout(s);
     dm.I = kv_image(s);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
@@ -982,6 +988,8 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, const int8_t
     const int d = s.C / s.H;
     const float sigma = s.softmax_scale != 0.f ? s.softmax_scale : 1.0f / sqrtf((float)d);
     dm.sig2 = sigma * 1.4426950408889634f;
+    dm.qmaxq = s.bits_q == 4 ? 7.f : 127.f;
+    dm.pmax = s.bits_prob == 4 ? 15.f : 255.f;
     dm.L = kv_layout(s);
     dm.I = kv_image(s);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};

@@ -194,8 +194,8 @@ static inline AttnWorkspace attn_workspace(const taq_shape& s) {
 hipError_t launch_rowquant_f16(const __half* x, int M, int K, int8_t* code, float* scale, hipStream_t st);
 // Same for float32 rows.
 hipError_t launch_rowquant_f32(const float* x, int M, int K, int8_t* code, float* scale, hipStream_t st);
-// Per-(row, head) symmetric int8 codes of float32 rows: x [M][C] -> code [M][C], scale [M][H].
-hipError_t launch_headquant_f32(const float* x, int M, int C, int H, int8_t* code, float* scale, hipStream_t st);
+// Per-(row, head) symmetric codes (8 or 4 bit, one per byte) of float32 rows: x [M][C] -> code [M][C], scale [M][H].
+hipError_t launch_headquant_f32(const float* x, int M, int C, int H, int bits, int8_t* code, float* scale, hipStream_t st);
 
 // Protected-token bookkeeping of qkv_packed from the mask (all tokens when bits == 16).
 hipError_t launch_kv_mask_scan(const uint8_t* mask, int B, int T, int bits, int* ntrig, int* trig_idx,

@@ -118,7 +118,7 @@ hipError_t launch_rowquant_f32(const float* x, int M, int K, int8_t* code, float
 // One wavefront per row; per-head maxima through LDS atomics on the bit pattern of |x|
 // (non-negative floats order like unsigned integers). d % 4 == 0, H <= TAQ_MAX_H.
 __global__ __launch_bounds__(256) void headquant_f32_kernel(const float* __restrict__ x, int M, int C, int H,
-                                                            int8_t* __restrict__ code,
+                                                            float qmaxf, int8_t* __restrict__ code,
                                                             float* __restrict__ scale) {
     __shared__ unsigned smax[4][TAQ_MAX_H];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -140,22 +140,23 @@ __global__ __launch_bounds__(256) void headquant_f32_kernel(const float* __restr
     if (!live) return;
     for (int h = lane; h < H; h += 64) {
         float amax = __uint_as_float(smax[wave][h]);
-        scale[(size_t)row * H + h] = amax == 0.f ? 1.f : amax / 127.f;
+        scale[(size_t)row * H + h] = amax == 0.f ? 1.f : amax / qmaxf;
     }
     unsigned* cr = reinterpret_cast<unsigned*>(code + (size_t)row * C);
     for (int v = lane; v < nv; v += 64) {
         float4 f = xr[v];
         float amax = __uint_as_float(smax[wave][(v * 4) / d]);
         float safe = amax == 0.f ? 1.f : amax;
-        cr[v] = pack4_i8(symq_code(f.x, 127.f, safe), symq_code(f.y, 127.f, safe),
-                         symq_code(f.z, 127.f, safe), symq_code(f.w, 127.f, safe));
+        cr[v] = pack4_i8(symq_code(f.x, qmaxf, safe), symq_code(f.y, qmaxf, safe),
+                         symq_code(f.z, qmaxf, safe), symq_code(f.w, qmaxf, safe));
     }
 }
 
-hipError_t launch_headquant_f32(const float* x, int M, int C, int H, int8_t* code, float* scale,
+hipError_t launch_headquant_f32(const float* x, int M, int C, int H, int bits, int8_t* code, float* scale,
                                 hipStream_t st) {
     if (M <= 0) return hipSuccess;
-    hipLaunchKernelGGL(headquant_f32_kernel, dim3((M + 3) / 4), dim3(256), 0, st, x, M, C, H, code, scale);
+    hipLaunchKernelGGL(headquant_f32_kernel, dim3((M + 3) / 4), dim3(256), 0, st, x, M, C, H, bits == 4 ? 7.f : 127.f,
+                       code, scale);
     return hipGetLastError();
 }
 

@@ -60,7 +60,8 @@ def test_size_queries_are_host_only_and_consistent():
 
 @pytest.mark.parametrize("kw,expect", [
     (dict(bits_kv=5), T.TAQ_ERR_UNSUPPORTED_BITS),
-    (dict(bits_prob=4), T.TAQ_ERR_UNSUPPORTED_BITS),
+    (dict(bits_prob=5), T.TAQ_ERR_UNSUPPORTED_BITS),
+    (dict(bits_prob=16), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(bits_q=16), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(bits_proj=16), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(C=324), T.TAQ_ERR_BAD_SHAPE),  # C % H != 0
