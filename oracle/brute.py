@@ -7,7 +7,8 @@ disagreement. It follows PersonalQ Section III-B: the attention definition,
 Eq. (2) (K~, V~, Q~) and Eq. (3) (A^), with the same readings of the open
 details as the vectorised oracle (symmetric round-half-even quantizer, per
 (head, token) K/V rows, per (token, head) Q rows, per-token activations,
-per-output-channel 8-bit weights, probabilities on a fixed 1/255 grid).
+per-output-channel 8-bit weights, probabilities on a fixed 1/255 or 1/15 grid, or on
+powers of two for the logarithmic quantizer).
 
 Float32 steps of the quantizer definition are done with numpy float32 *scalars*;
 everything else is Python float (float64) or exact Fractions.
@@ -66,7 +67,8 @@ def symq_f32(row, bits):
     return codes, scale
 
 
-def taq_block_brute(context, mask, Wq, Wk, Wv, Wo, bias_o, hidden, H, bits_kv, bits_q=8, bits_prob=8):
+def taq_block_brute(context, mask, Wq, Wk, Wv, Wo, bias_o, hidden, H, bits_kv, bits_q=8, bits_prob=8,
+                    prob_grid="linear"):
     """context [B][T][Cc], mask [B][T], W* [C][in], hidden [B][N][C] as nested
     lists / arrays of fp16-valued numbers. Returns out [B][N][C] (Python floats,
     rounded through fp16) and a dict of intermediates."""
@@ -154,6 +156,13 @@ def taq_block_brute(context, mask, Wq, Wk, Wv, Wo, bias_o, hidden, H, bits_kv, b
                 for t in range(T):
                     if trig[t]:
                         Ah.append(A[t])
+                    elif prob_grid == "log2":
+                        # power-of-two grid: the exponent -log2 A, to float32, rounded half-even, clipped
+                        last = (1 << bits_prob) - 1
+                        ex = float(_f32(-math.log2(A[t]))) if A[t] > 0.0 else float(last)
+                        pc = min(last, max(0, int(np.rint(_f32(min(ex, float(last)))))))
+                        dump["p_code"][(b, n, h, t)] = pc
+                        Ah.append(math.ldexp(1.0, -pc))
                     else:
                         pmax = (1 << bits_prob) - 1
                         pc = int(np.rint(_f32(_f32(A[t]) * _f32(pmax))))

@@ -95,6 +95,23 @@ def uq8(p):
     return uq(p, 8)
 
 
+def uq_log2(p, bits: int = 8):
+    """Logarithmic b-bit quantizer of a probability (the "Logarithmic" rows of the
+    TAQ ablation table in Section IV). The paper names this quantizer without a
+    formula; reading: the power-of-two grid customary for post-softmax activations,
+        code = clip(rint(-log2 p), 0, 2^b - 1),   p^ = 2^(-code),
+    with -log2 p evaluated in float64, rounded once to float32, then rint
+    half-to-even. p = 0 takes the last code (its p^ = 2^-(2^b-1) is not zero)."""
+    if bits not in (4, 8):
+        raise ValueError("uq_log2: bits must be 4 or 8")
+    last = (1 << bits) - 1
+    p64 = np.asarray(p, dtype=f64)
+    with np.errstate(divide="ignore"):
+        x = (-np.log2(p64)).astype(f32)          # +inf where p == 0
+    code = np.rint(np.minimum(x, f32(last)))
+    return np.clip(code, 0, last).astype(np.int32)
+
+
 def pack_int4(codes):
     """Two's-complement nibbles, element 2j in the low nibble of byte j."""
     c = np.asarray(codes).astype(np.int32)
@@ -241,14 +258,15 @@ def _linear_w8a8(x, w_code, s_w):
 def cross_attn(hidden, kv: QuantKV, wq_code, s_wq, wo_code, s_wo, bias_o=None,
                bits_prob: int = 8, bits_q: int = 8, bits_proj: int = 8,
                softmax_scale: Optional[float] = None, store_f16: bool = True,
-               Wq_f16=None, Wo_f16=None, return_aux: bool = False):
+               Wq_f16=None, Wo_f16=None, return_aux: bool = False, prob_grid: str = "linear"):
     """The TAQ cross-attention block for image tokens ``hidden`` [B, N, C].
 
     Steps, in the paper's order:
       Q  = to_q(hidden)                       (W8A8: reading)
       Q~ = Q_a(Q)                             Eq. (2), third line; per (token, head): reading; 8 or 4 bits
       A  = softmax(Q~ K~^T / sqrt(d))         attention definition, per head
-      A^ = M_A*A + (1-M_A)*Q_a(A)             Eq. (3); no renormalisation; 8 or 4 bits
+      A^ = M_A*A + (1-M_A)*Q_a(A)             Eq. (3); no renormalisation; 8 or 4 bits;
+                                              Q_a on the linear grid (uq) or, prob_grid="log2", on powers of two (uq_log2)
       O  = A^ V~
       out = to_out(O) + bias                  (W8A8: reading), stored as fp16
     With bits_proj == 16 the two projections use ``Wq_f16`` / ``Wo_f16`` unquantized.
@@ -291,7 +309,13 @@ def cross_attn(hidden, kv: QuantKV, wq_code, s_wq, wo_code, s_wo, bias_o=None,
 
     # ---- A^ (Eq. 3): trigger columns keep A, the others are quantized
     M_A = kv.mask[:, None, None, :]  # [B,1,1,T] -> broadcast over N and heads
-    if bits_prob in (4, 8):
+    if prob_grid not in ("linear", "log2"):
+        raise ValueError("prob_grid must be 'linear' or 'log2'")
+    if bits_prob in (4, 8) and prob_grid == "log2":
+        p_code = uq_log2(A, bits_prob)
+        A_q = np.exp2(-p_code.astype(f64))
+        aux["p_code"] = p_code
+    elif bits_prob in (4, 8):
         p_code = uq(A, bits_prob)
         A_q = p_code.astype(f64) / f64((1 << bits_prob) - 1)
         aux["p_code"] = p_code
@@ -322,7 +346,8 @@ def cross_attn(hidden, kv: QuantKV, wq_code, s_wq, wo_code, s_wo, bias_o=None,
 
 
 def taq_block(layer, bits_prob: int = 8, bits_q: int = 8, bits_proj: int = 8,
-              bits_kv: Optional[int] = None, store_f16: bool = True, return_aux: bool = False):
+              bits_kv: Optional[int] = None, store_f16: bool = True, return_aux: bool = False,
+              prob_grid: str = "linear"):
     """Whole path for one synthetic layer: weight codes, K~/V~, then the block."""
     bk = layer.bits_kv if bits_kv is None else bits_kv
     kv = quantize_kv(layer.context, layer.mask, layer.Wk, layer.Wv, bk, layer.H,
@@ -331,7 +356,8 @@ def taq_block(layer, bits_prob: int = 8, bits_q: int = 8, bits_proj: int = 8,
     wo_code, s_wo = quantize_weight(layer.Wo)
     res = cross_attn(layer.hidden, kv, wq_code, s_wq, wo_code, s_wo, layer.bias_o,
                      bits_prob=bits_prob, bits_q=bits_q, bits_proj=bits_proj,
-                     store_f16=store_f16, Wq_f16=layer.Wq, Wo_f16=layer.Wo, return_aux=return_aux)
+                     store_f16=store_f16, Wq_f16=layer.Wq, Wo_f16=layer.Wo, return_aux=return_aux,
+                     prob_grid=prob_grid)
     if return_aux:
         out, aux = res
         aux["kv"] = kv

@@ -315,3 +315,72 @@ def test_a4_is_coarser_than_a8_and_trigger_columns_still_pass_through():
     assert np.array_equal(aux4["A_hat"][..., [2, 3]], aux4["A"][..., [2, 3]])
     g = aux4["A_hat"][..., [t for t in range(L.T) if t not in (2, 3)]] * 15.0
     assert np.max(np.abs(g - np.rint(g))) < 1e-12
+
+
+# ---------------------------------------------------------------- logarithmic probability grid
+
+def test_log2_grid_is_exact_on_uniform_attention_over_a_power_of_two_tokens():
+    """Zero keys give uniform attention A = 1/T. With T = 64 that is a power of two, so the logarithmic grid keeps
+    it exactly (codes 6) and the block equals the one with unquantized probabilities, while the linear 8-bit grid
+    does not (255/64 rounds to 4, A^ = 4/255)."""
+    B, N, H, d, T = 1, 5, 2, 4, 64
+    C = H * d
+    rng = np.random.Generator(np.random.PCG64(12))
+    mask = np.zeros((B, T), dtype=bool)
+    v_code = rng.integers(-127, 128, size=(B, T, C)).astype(np.int32)
+    s_V = rng.uniform(0.01, 0.02, size=(B, H, T)).astype(np.float32)
+    kv = O.QuantKV(B=B, T=T, C=C, H=H, bits_kv=8, mask=mask, k_code=np.zeros((B, T, C), dtype=np.int32), v_code=v_code,
+                   s_K=np.ones((B, H, T), dtype=np.float32), s_V=s_V, K16=np.zeros((B, T, C)), V16=np.zeros((B, T, C)))
+    hidden = rng.standard_normal((B, N, C)).astype(np.float16)
+    wq, swq = O.quantize_weight(np.eye(C, dtype=np.float16))
+    for bits in (4, 8):
+        out_log, aux_log = O.cross_attn(hidden, kv, wq, swq, wq, swq, bits_prob=bits, prob_grid="log2", return_aux=True)
+        out_fp, aux_fp = O.cross_attn(hidden, kv, wq, swq, wq, swq, bits_prob=16, return_aux=True)
+        assert np.all(aux_log["p_code"] == 6)
+        assert np.array_equal(aux_log["O"], aux_fp["O"]) and np.array_equal(out_log, out_fp)
+    # column mean of V~ by hand
+    Vt = kv.dequant("v")
+    assert np.max(np.abs(aux_log["O"] - Vt.mean(axis=1)[:, None, :])) < 1e-15
+    _, aux_lin = O.cross_attn(hidden, kv, wq, swq, wq, swq, bits_prob=8, return_aux=True)
+    assert np.all(aux_lin["p_code"] == 4) and not np.allclose(aux_lin["O"], aux_fp["O"], rtol=1e-3)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("case", [
+    dict(seed=31, B=1, N=4, C=8, H=2, T=5, Cc=6, bits_kv=4, trig=(1,)),
+    dict(seed=32, B=2, N=3, C=4, H=1, T=9, Cc=5, bits_kv=8, trig=()),
+])
+def test_log2_grid_block_matches_scalar_brute_force(case, bits):
+    L = synth.make_layer("t", seed=case["seed"], B=case["B"], N=case["N"], C=case["C"], H=case["H"], T=case["T"],
+                         Cc=case["Cc"], bits_kv=case["bits_kv"], trigger_positions=case["trig"], trigger_scale=3.0, bias=True)
+    out, aux = O.taq_block(L, bits_prob=bits, prob_grid="log2", return_aux=True)
+    ref, dump = brute.taq_block_brute(L.context, L.mask, L.Wq, L.Wk, L.Wv, L.Wo, L.bias_o, L.hidden, L.H, L.bits_kv,
+                                      bits_prob=bits, prob_grid="log2")
+    assert len(dump["p_code"]) == L.B * L.N * L.H * (L.T - len(case["trig"]))
+    for (b, n, h, t), v in dump["p_code"].items():
+        assert aux["p_code"][b, n, h, t] == v and 0 <= v <= (1 << bits) - 1
+    for (b, n, c), v in dump["o_code"].items():
+        assert aux["o_code"][b, n, c] == v
+    ref = np.array(ref)
+    assert np.max(np.abs(out.astype(np.float64) - ref)) <= 1e-3 * max(1.0, np.abs(ref).max())
+
+
+def test_log2_grid_keeps_trigger_columns_and_puts_the_rest_on_powers_of_two():
+    L = small_layer(N=64)
+    out, aux = O.taq_block(L, bits_prob=4, prob_grid="log2", return_aux=True)
+    assert np.array_equal(aux["A_hat"][..., [2, 3]], aux["A"][..., [2, 3]])       # Eq. (3): M_A columns keep A
+    rest = aux["A_hat"][..., [t for t in range(L.T) if t not in (2, 3)]]
+    e = -np.log2(rest)
+    assert np.array_equal(e, np.rint(e)) and e.min() >= 0 and e.max() <= 15
+    # nearest power of two in the log domain: within sqrt(2) unless clipped at 2^-15
+    A_rest = aux["A"][..., [t for t in range(L.T) if t not in (2, 3)]]
+    inside = A_rest >= 2.0 ** -15.5
+    r = rest[inside] / A_rest[inside]
+    assert r.max() <= 2 ** 0.5 * (1 + 1e-6) and r.min() >= 2 ** -0.5 * (1 - 1e-6)
+    assert np.all(rest[~inside] == 2.0 ** -15)
+    # at 8 bits the grid reaches 2^-255, so nothing is clipped and the relative error bound holds everywhere
+    _, aux8 = O.taq_block(L, bits_prob=8, prob_grid="log2", return_aux=True)
+    r8 = aux8["A_hat"] / aux8["A"]
+    assert r8.max() <= 2 ** 0.5 * (1 + 1e-6) and r8.min() >= 2 ** -0.5 * (1 - 1e-6)
+    with pytest.raises(ValueError):
+        O.taq_block(L, prob_grid="sqrt")

@@ -153,3 +153,30 @@ def test_uq4_known_values_and_bound():
     assert c.min() == 0 and c.max() == 15
     with pytest.raises(ValueError):
         O.uq(p, 5)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_uq_log2_known_values_bound_and_fixed_points(bits):
+    last = (1 << bits) - 1
+    # -log2: 1 -> 0, .5 -> 1, .25 -> 2, .3 -> 1.737 -> 2, .36 -> 1.474 -> 1, .7 -> .515 -> 1, .71 -> .494 -> 0
+    p = np.array([1.0, 0.5, 0.25, 0.3, 0.36, 0.7, 0.71, 1e-6, 0.0])
+    code = O.uq_log2(p, bits)
+    assert list(code[:7]) == [0, 1, 2, 2, 1, 1, 0]
+    assert code[7] == min(last, 20) and code[8] == last      # -log2(1e-6) = 19.93; zero takes the last code
+    # every power of two on the grid is a fixed point
+    k = np.arange(0, last + 1)
+    assert np.array_equal(O.uq_log2(np.exp2(-k.astype(np.float64)), bits), k)
+    # inside the grid's range the dequantised value is within a factor sqrt(2) of p; codes fall as p grows
+    grid = np.exp(np.linspace(np.log(2.0 ** -(min(last, 40) + 0.49)), 0.0, 50001))
+    c = O.uq_log2(grid, bits)
+    ratio = np.exp2(-c.astype(np.float64)) / grid
+    assert ratio.max() <= 2 ** 0.5 * (1 + 1e-6) and ratio.min() >= 2 ** -0.5 * (1 - 1e-6)
+    assert np.all(np.diff(c) <= 0) and c.max() == min(last, 40) and c.min() == 0
+    # decision boundaries sit at the geometric means 2^-(k+1/2) of neighbouring grid points (no logarithm needed
+    # to state that): just above one the code is k, just below it k + 1
+    kk = np.arange(0, min(last, 60))
+    edge = np.sqrt(np.exp2(-kk.astype(np.float64)) * np.exp2(-(kk + 1).astype(np.float64)))
+    assert np.array_equal(O.uq_log2(edge * (1 + 1e-5), bits), kk)
+    assert np.array_equal(O.uq_log2(edge * (1 - 1e-5), bits), kk + 1)
+    with pytest.raises(ValueError):
+        O.uq_log2(p, 16)
