@@ -137,9 +137,9 @@ def other_configs(dev, use_graph):
     to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
     out = {}
 
-    def prep(L, bits_q=8, bits_prob=8):
+    def prep(L, bits_q=8, bits_prob=8, prob_grid=T.TAQ_PROB_LINEAR):
         s = T.make_shape(B=L.B, N=L.N, C=L.C, H=L.H, T=L.T, Cc=L.Cc, bits_kv=L.bits_kv, bits_q=bits_q,
-                         bits_prob=bits_prob, w_layout=1 if L.C % 64 == 0 else 0)
+                         bits_prob=bits_prob, w_layout=1 if L.C % 64 == 0 else 0, prob_grid=prob_grid)
         wq, swq = T.taq_quantize_weight(to(L.Wq))
         wo, swo = T.taq_quantize_weight(to(L.Wo))
         if s.w_layout:
@@ -164,6 +164,8 @@ def other_configs(dev, use_graph):
     import dataclasses
     d2 = prep(dataclasses.replace(synth.config2(), bits_kv=4), bits_q=4, bits_prob=4)  # the 8/4 setting (Table 1)
     out["config2_w8a4_int4kv_q4_p4"] = round(timed([attn_call(d2)] * 4) / 4, 2)
+    d2 = prep(dataclasses.replace(synth.config2(), bits_kv=4), bits_q=4, bits_prob=4, prob_grid=T.TAQ_PROB_LOG2)
+    out["config2_w8a4_log2_probabilities"] = round(timed([attn_call(d2)] * 4) / 4, 2)
     d1 = prep(synth.config1())
     out["config1_64x1280"] = round(timed([attn_call(d1)] * 4) / 4, 2)
     layers = [prep(L) for L in synth.config3()]

@@ -63,7 +63,14 @@ typedef struct taq_shape {
                                 1 : buffers written by taq_pack_weight (row-major codes followed by a copy
                                     in matrix-core operand order, which the single-kernel path reads with
                                     fully coalesced loads)                                      */
+    int prob_grid;           /* grid of Q_a on the probabilities in Eq. (3):
+                                TAQ_PROB_LINEAR (0) : code = rint(pmax*A), A^ = code/pmax
+                                TAQ_PROB_LOG2   (1) : code = clip(rint(-log2 A), 0, 2^bits_prob - 1),
+                                                      A^ = 2^-code (the "Logarithmic" quantizer of the
+                                                      trigger-separation ablation, Section IV)          */
 } taq_shape;
+
+enum { TAQ_PROB_LINEAR = 0, TAQ_PROB_LOG2 = 1 };
 
 /* Optional taps for tests and profiling (all pointers device memory or NULL). */
 typedef struct taq_debug {

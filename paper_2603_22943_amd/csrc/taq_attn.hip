@@ -68,7 +68,9 @@ struct CoreArgs {
     float* o_f;             // [B][N][C]
     int N, C, H, T, bits;
     float sig2;             // softmax scale * log2(e)
-    float pmax;             // 255 or 15: grid of the probabilities (Eq. 3)
+    float pmax;             // linear grid: 255 or 15 (Eq. 3); log2 grid: 2^15, the factor that puts 2^-code into fp16's range
+    float plast;            // log2 grid: the last code, 255 or 15
+    int plog;               // 1: log2 grid
 };
 
 __device__ __forceinline__ int load_code(const uint8_t* codes, size_t row, int C, int c, int bits) {
@@ -276,12 +278,15 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
     for (int tile = 0; tile < 3; ++tile)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            S[tile][i] = __builtin_amdgcn_exp2f(S[tile][i] - mx);
+            const float arg = S[tile][i] - mx;
+            const float ex = __builtin_amdgcn_exp2f(arg);
             Sf[tile][i] = __builtin_amdgcn_exp2f(Sf[tile][i] - mx);
-            Z += S[tile][i] + Sf[tile][i];
+            Z += ex + Sf[tile][i];
+            S[tile][i] = a.plog ? arg : ex;  // the log2 grid rounds the exponent itself
         }
     Z += __shfl_xor(Z, 32);
     const float inv = 1.0f / Z;
+    const float lz = __builtin_amdgcn_logf(Z);  // log2 Z >= 0 (the largest term is 1)
 
     // ---------------- O^T = V~^T A^^T
     floatx16_t oacc[DT];
@@ -325,8 +330,16 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
             for (int blk = 0; blk < 2; ++blk) {
                 half8_t p;  // Eq. (3): integer probability codes, exact in fp16
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    p[e] = (_Float16)__builtin_rintf((S[tile][8 * blk + e] * inv) * a.pmax);
+                for (int e = 0; e < 8; ++e) {
+                    if (a.plog) {
+                        // -code = clip(rint(log2 A)) = clip(rint(arg - log2 Z)); weight 2^(15 - code), a power of
+                        // two that fp16 holds exactly down to 2^-24 (smaller ones vanish: below 2^-39 of the row sum)
+                        const float c = fminf(fmaxf(__builtin_rintf(S[tile][8 * blk + e] - lz), -a.plast), 0.f);
+                        p[e] = (_Float16)ldexpf(1.0f, 15 + (int)c);
+                    } else {
+                        p[e] = (_Float16)__builtin_rintf((S[tile][8 * blk + e] * inv) * a.pmax);
+                    }
+                }
 #pragma unroll
                 for (int jt = 0; jt < DT; ++jt) {
                     const int o = (32 * jt + r) * L::RS_V + 32 * tile + 16 * blk + 8 * half;
@@ -394,7 +407,9 @@ hipError_t launch_attn_core(const int8_t* q_code, const float* s_q, const uint8_
     const int d = s.C / s.H;
     const float sigma = s.softmax_scale != 0.f ? s.softmax_scale : 1.0f / sqrtf((float)d);
     a.sig2 = sigma * 1.4426950408889634f;
-    a.pmax = s.bits_prob == 4 ? 15.f : 255.f;
+    a.pmax = s.prob_grid == TAQ_PROB_LOG2 ? 32768.f : s.bits_prob == 4 ? 15.f : 255.f;
+    a.plast = s.bits_prob == 4 ? 15.f : 255.f;
+    a.plog = s.prob_grid == TAQ_PROB_LOG2;
     switch ((d + 31) / 32) {
         case 1: return launch_core_dt<1>(a, s.B, st);
         case 2: return launch_core_dt<2>(a, s.B, st);

@@ -167,7 +167,8 @@ struct FusedDims {
     unsigned w_pack_off;
     float sig2;        // softmax scale * log2(e)
     float qmaxq;       // 127 or 7: grid of Q~ (Eq. 2, third line)
-    float pmax;        // 255 or 15: grid of the probabilities (Eq. 3)
+    float pmax;        // linear grid: 255 or 15 (Eq. 3); log2 grid: 256, which brings 2^-code * s_V to the linear grid's magnitudes
+    float plast;       // log2 grid: the last code, 255 or 15
     KvLayout L;
     KvImage I;
     taq_debug dbg;     // taps (NULL pointers = off); only used when R == 1
@@ -257,7 +258,7 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // NG > 1 (layers too wide for one workgroup's LDS): the workgroup owns head group blockIdx.y (NH of the NH*NG
 // heads), takes the per-token codes of `hidden` from the workspace, and stops after A^ V~, which it writes to
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
-template <int D, int NH, int NTT, int NG>
+template <int D, int NH, int NTT, int NG, bool LOGP>
 __global__ __launch_bounds__(64 * NH * (2 / NTT)) __attribute__((amdgpu_waves_per_eu(1, (NH * (2 / NTT) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
     using F = FusedCfg<D, NH, NTT, NG>;
@@ -633,7 +634,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 
     // ================= softmax over the text tokens; Eq. (3); weights of O^T = V~^T A^^T
-    float kq[NTT];  // pmax / Z per image token (pmax = 255 or 15)
+    float kq[NTT];  // pmax / Z per image token
+    float lz[NTT];  // log2 Z (log2 grid only)
 #pragma unroll
     for (int nt = 0; nt < NTT; ++nt) {
         float mx = TAQ_NEG_INF;
@@ -651,8 +653,10 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             if (tt < dm.nt16) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    S[nt][tt][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[nt][tt][i], sc, off));
-                    Z += S[nt][tt][i];
+                    const float arg = __builtin_fmaf(S[nt][tt][i], sc, off);
+                    const float ex = __builtin_amdgcn_exp2f(arg);
+                    Z += ex;
+                    S[nt][tt][i] = LOGP ? arg : ex;  // the log2 grid rounds the exponent itself
                 }
             }
 #pragma unroll
@@ -666,6 +670,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             }
         Z = quad_allsum(Z);
         kq[nt] = dm.pmax * __builtin_amdgcn_rcpf(Z);
+        lz[nt] = LOGP ? __builtin_amdgcn_logf(Z) : 0.f;  // log2 Z >= 0: the largest term of Z is 1
     }
 
     floatx4_t oacc[NTT][TPH];
@@ -727,7 +732,14 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                         for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
-                                const float w = __builtin_rintf(S[nt][2 * s + a][i] * kq[nt]) * svv[i];  // Eq. (3)
+                                float w;
+                                if constexpr (LOGP) {
+                                    // -code = clip(rint(log2 A)) = clip(rint(arg - log2 Z)); weight 2^(8 - code) * s_V, exact
+                                    const float c = fminf(fmaxf(__builtin_rintf(S[nt][2 * s + a][i] - lz[nt]), -dm.plast), 0.f);
+                                    w = ldexpf(svv[i], 8 + (int)c);
+                                } else {
+                                    w = __builtin_rintf(S[nt][2 * s + a][i] * kq[nt]) * svv[i];  // Eq. (3)
+                                }
                                 const _Float16 wh = (_Float16)w;
                                 phi[nt][4 * a + i] = wh;
                                 plo[nt][4 * a + i] = (_Float16)__builtin_fmaf((float)wh, -1.0f, w);  // w - hi, exact
@@ -923,22 +935,27 @@ static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hi
     return hipGetLastError();
 }
 
-template <int D, int NH, int NTT, int NG>
-static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
+template <int D, int NH, int NTT, int NG, bool LOGP>
+static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     using F = FusedCfg<D, NH, NTT, NG>;
     static bool attr_set = false;
     const size_t bytes = NG == 1 ? dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 + 32 * NH * 4  // = fused_lds_bytes
                                  : (size_t)NH * dm.I.head_bytes + 32 * F::TILE_RS + 32 * 4;             // = mid_lds_bytes
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, LOGP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles = (dm.N + 31) / 32;
-    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
+    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, LOGP>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();
+}
+
+template <int D, int NH, int NTT, int NG>
+static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, bool logp, hipStream_t st) {
+    return logp ? launch_fused_grid<D, NH, NTT, NG, true>(tab, dm, st) : launch_fused_grid<D, NH, NTT, NG, false>(tab, dm, st);
 }
 
 hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, const taq_debug* dbg, hipStream_t st) {
@@ -957,7 +974,9 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     const float sigma = s.softmax_scale != 0.f ? s.softmax_scale : 1.0f / sqrtf((float)d);
     dm.sig2 = sigma * 1.4426950408889634f;
     dm.qmaxq = s.bits_q == 4 ? 7.f : 127.f;
-    dm.pmax = s.bits_prob == 4 ? 15.f : 255.f;
+    const bool logp = s.prob_grid == TAQ_PROB_LOG2;
+    dm.plast = s.bits_prob == 4 ? 15.f : 255.f;
+    dm.pmax = logp ? 256.f : dm.plast;
     dm.L = kv_layout(s);
     dm.I = kv_image(s);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
@@ -965,9 +984,9 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.ws_hcode = nullptr;
     dm.ws_sh = nullptr;
     dm.ws_of = nullptr;
-    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8, TAQ_NTT_40, 1>(tab, dm, st);
-    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8, 2, 1>(tab, dm, st);
-    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10, 2, 1>(tab, dm, st);
+    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8, TAQ_NTT_40, 1>(tab, dm, logp, st);
+    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8, 2, 1>(tab, dm, logp, st);
+    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10, 2, 1>(tab, dm, logp, st);
     return hipErrorInvalidValue;
 }
 
@@ -989,7 +1008,9 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, const int8_t
     const float sigma = s.softmax_scale != 0.f ? s.softmax_scale : 1.0f / sqrtf((float)d);
     dm.sig2 = sigma * 1.4426950408889634f;
     dm.qmaxq = s.bits_q == 4 ? 7.f : 127.f;
-    dm.pmax = s.bits_prob == 4 ? 15.f : 255.f;
+    const bool logp = s.prob_grid == TAQ_PROB_LOG2;
+    dm.plast = s.bits_prob == 4 ? 15.f : 255.f;
+    dm.pmax = logp ? 256.f : dm.plast;
     dm.L = kv_layout(s);
     dm.I = kv_image(s);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
@@ -1002,8 +1023,8 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, const int8_t
     dm.ws_hcode = h_code;
     dm.ws_sh = s_h;
     dm.ws_of = o_f;
-    if (d == 160 && s.H == 8) return launch_fused_cfg<160, 1, 1, 8>(tab, dm, st);
-    if (d == 64 && s.H == 20) return launch_fused_cfg<64, 2, 1, 10>(tab, dm, st);
+    if (d == 160 && s.H == 8) return launch_fused_cfg<160, 1, 1, 8>(tab, dm, logp, st);
+    if (d == 64 && s.H == 20) return launch_fused_cfg<64, 2, 1, 10>(tab, dm, logp, st);
     return hipErrorInvalidValue;
 }
 

@@ -11,10 +11,10 @@ from paper_2603_22943_amd import taq as T
 DEV = "cuda:0"
 
 
-def shape_of(L, bits_kv=None, N=None, w_layout=0, bits_q=8, bits_prob=8):
+def shape_of(L, bits_kv=None, N=None, w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear"):
     return T.make_shape(B=L.B, N=L.N if N is None else N, C=L.C, H=L.H, T=L.T, Cc=L.Cc,
                         bits_kv=L.bits_kv if bits_kv is None else bits_kv, bits_q=bits_q, bits_prob=bits_prob,
-                        w_layout=w_layout)
+                        w_layout=w_layout, prob_grid=T.TAQ_PROB_LOG2 if prob_grid == "log2" else T.TAQ_PROB_LINEAR)
 
 
 def dev(a, dtype=None):
@@ -27,9 +27,9 @@ def dev(a, dtype=None):
 class GpuRun:
     """Everything the HIP path produces for one layer (tensors brought back as numpy)."""
 
-    def __init__(self, L, taps=True, hidden=None, w_layout=0, bits_q=8, bits_prob=8):
+    def __init__(self, L, taps=True, hidden=None, w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear"):
         self.L = L
-        self.shape = s = shape_of(L, w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob)
+        self.shape = s = shape_of(L, w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid)
         ctx, mask = dev(L.context), dev(L.mask)
         Wq, Wk, Wv, Wo = dev(L.Wq), dev(L.Wk), dev(L.Wv), dev(L.Wo)
         self.wq_code, self.s_wq = T.taq_quantize_weight(Wq)
@@ -44,7 +44,8 @@ class GpuRun:
         self.mask_d = mask
         self.hidden_d = dev(L.hidden if hidden is None else hidden)
         if hidden is not None:
-            self.shape = s = shape_of(L, N=hidden.shape[1], w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob)
+            self.shape = s = shape_of(L, N=hidden.shape[1], w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob,
+                                      prob_grid=prob_grid)
         if taps:
             dbg, t = T.make_debug(s, DEV)
             self.out_d = T.taq_cross_attn(self.hidden_d, self.packed, self.wq_code, self.wo_code, self.scales,
@@ -59,12 +60,12 @@ class GpuRun:
         self.out = self.out_d.cpu().numpy()
 
 
-def oracle_run(L, hidden=None, bits_q=8, bits_prob=8):
+def oracle_run(L, hidden=None, bits_q=8, bits_prob=8, prob_grid="linear"):
     kv = O.quantize_kv(L.context, L.mask, L.Wk, L.Wv, L.bits_kv, L.H)
     wq_code, s_wq = O.quantize_weight(L.Wq)
     wo_code, s_wo = O.quantize_weight(L.Wo)
     out, aux = O.cross_attn(L.hidden if hidden is None else hidden, kv, wq_code, s_wq, wo_code, s_wo, L.bias_o,
-                            bits_q=bits_q, bits_prob=bits_prob, return_aux=True)
+                            bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid, return_aux=True)
     aux.update(kv=kv, wq_code=wq_code, s_wq=s_wq, wo_code=wo_code, s_wo=s_wo)
     return out, aux
 

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert ctypes.sizeof(T.taq_shape) == 12 * 4
+    assert ctypes.sizeof(T.taq_shape) == 13 * 4
     assert ctypes.sizeof(T.taq_request) == 7 * 8
     assert ctypes.sizeof(T.taq_debug) == 7 * 8 + 8
 
@@ -63,6 +63,7 @@ def test_size_queries_are_host_only_and_consistent():
     (dict(bits_prob=5), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(bits_prob=16), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(bits_q=16), T.TAQ_ERR_UNSUPPORTED_BITS),
+    (dict(prob_grid=2), T.TAQ_ERR_INVALID_ARG),
     (dict(bits_proj=16), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(C=324), T.TAQ_ERR_BAD_SHAPE),  # C % H != 0
     (dict(C=96, H=8), T.TAQ_ERR_BAD_SHAPE),  # d = 12, not a multiple of 8

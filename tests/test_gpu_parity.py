@@ -27,11 +27,11 @@ OUT_MAX_ABS = 2e-2
 OUT_REL_L2 = 5e-3
 
 
-def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8):
+def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear"):
     print(f"[case] {label or L.name}: B={L.B} N={L.N} C={L.C} H={L.H} T={L.T} Cc={L.Cc} bits_kv={L.bits_kv} "
-          f"bits_q={bits_q} bits_prob={bits_prob} ntrig={L.mask.sum(axis=1).tolist()} w_layout={w_layout}", flush=True)
-    g = G.GpuRun(L, w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob)
-    ref_out, aux = G.oracle_run(L, bits_q=bits_q, bits_prob=bits_prob)
+          f"bits_q={bits_q} bits_prob={bits_prob} grid={prob_grid} ntrig={L.mask.sum(axis=1).tolist()} w_layout={w_layout}", flush=True)
+    g = G.GpuRun(L, w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid)
+    ref_out, aux = G.oracle_run(L, bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid)
     kv = aux["kv"]
     pmax = float((1 << bits_prob) - 1)
     # ---- weights
@@ -78,24 +78,35 @@ def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8):
     dcode = np.abs(g.taps["o_code"].astype(np.int32) - aux["o_code"])
     print(f"    O: max|d|/max|O|={dO.max() / scale_o:.3e} frac(>{far:g})={frac_far:.3e}  "
           f"o_code mismatches={float(np.mean(dcode != 0)):.3e} max={int(dcode.max())}", flush=True)
-    # Where pmax*A lies within the float32-vs-float64 gap of a k+1/2 tie, either neighbouring code is a correct
-    # rounding and that column's weight may differ by one grid step; every other element must agree closely.
-    # The gap: relative error of the kernel's float32 softmax (scores up to a few tens, exp2, sum, reciprocal).
+    # Where the quantity being rounded (pmax*A, or -log2 A on the power-of-two grid) lies within the
+    # float32-vs-float64 gap of a k+1/2 tie, either neighbouring code is a correct rounding and that column's
+    # weight may differ by one grid step; every other element must agree closely. The gap: relative error of
+    # the kernel's float32 softmax (scores up to a few tens, exp2, sum, reciprocal or logarithm).
     d = L.C // L.H
-    x = aux["A"] * pmax                                              # [B,N,H,T]
-    tie_rel = 1e-5 if rows_equal else 2e-3
-    near = (np.abs(x - np.floor(x) - 0.5) <= tie_rel * x + 1e-6) & ~kv.mask[:, None, None, :]
-    vstep = np.abs(kv.v_code.astype(np.float64)).reshape(L.B, L.T, L.H, d) * \
-        np.transpose(kv.s_V.astype(np.float64), (0, 2, 1))[..., None] / pmax     # [B,T,H,d]
-    slack = np.einsum("bnht,bthj->bnhj", near.astype(np.float64), vstep).reshape(L.B, L.N, L.C)
+    unprot = ~kv.mask[:, None, None, :]
+    if prob_grid == "log2":
+        last = (1 << bits_prob) - 1
+        x = -np.log2(aux["A"])                                       # [B,N,H,T]
+        tol = 1e-5 * (1 + x) + (0.0 if rows_equal else 0.02)
+        near = (np.abs(x - np.floor(x) - 0.5) <= tol) & (np.floor(x) < last) & unprot
+        step = np.where(near, np.exp2(-(np.floor(x) + 1)), 0.0)      # 2^-k - 2^-(k+1)
+    else:
+        x = aux["A"] * pmax
+        tie_rel = 1e-5 if rows_equal else 2e-3
+        near = (np.abs(x - np.floor(x) - 0.5) <= tie_rel * x + 1e-6) & unprot
+        step = near / pmax
+    vabs = np.abs(kv.v_code.astype(np.float64)).reshape(L.B, L.T, L.H, d) * \
+        np.transpose(kv.s_V.astype(np.float64), (0, 2, 1))[..., None]             # |V~| [B,T,H,d]
+    slack = np.einsum("bnht,bthj->bnhj", step, vabs).reshape(L.B, L.N, L.C)
     print(f"    near-tie probabilities: {int(near.sum())} of {near.size}", flush=True)
-    assert np.all(dO <= slack + (0.02 if pmax == 255 else far) * scale_o), float((dO - slack).max() / scale_o)
+    coarse = bits_prob == 4 or prob_grid == "log2"  # one grid step is a visible fraction of the output
+    assert np.all(dO <= slack + (far if coarse else 0.02) * scale_o), float((dO - slack).max() / scale_o)
     assert frac_far < 5e-3
     # an int8 code of O may move by one where O is within rounding of a tie, plus however many
     # steps a flipped probability code moved O itself (with 4-bit V rows or a 4-bit probability
     # grid one probability step, s_V*|v|/pmax, can exceed one step of O's own grid)
     assert np.all(dcode <= 1 + np.ceil(dO / aux["s_o"].astype(np.float64)[..., None]))
-    assert dcode.max() <= (3 if pmax == 255 else 12) and np.mean(dcode != 0) < 2e-3
+    assert dcode.max() <= (12 if coarse else 3) and np.mean(dcode != 0) < 2e-3
     # the row maximum is 1-Lipschitz: a token's scale moves by at most its largest |dO| / 127
     ds = np.abs(g.taps["s_o"].astype(np.float64) - aux["s_o"].astype(np.float64))
     assert np.all(ds <= dO.max(axis=-1) / 127.0 + 1e-6 * aux["s_o"])
@@ -300,3 +311,43 @@ def test_four_bit_activations_mask_extremes(trig):
     L = synth.make_layer("a4m", seed=410 + len(pos), B=1, N=100, C=320, H=8, Cc=64, T=77, bits_kv=8,
                          trigger_positions=pos, trigger_scale=3.0)
     check_layer(L, f"A4 mask ntrig={len(pos)}", bits_q=4, bits_prob=4)
+
+
+# ---------------------------------------------------------------- logarithmic probability grid (ablation table, Section IV)
+
+@pytest.mark.parametrize("bits_prob", [8, 4])
+@pytest.mark.parametrize("C,H,N,T_,bits_kv,bits_q", [
+    (320, 8, 200, 77, 8, 8),    # single kernel, d = 40
+    (320, 8, 77, 77, 4, 4),     # ... 4-bit K~/V~ rows and 4-bit Q~
+    (640, 8, 45, 77, 8, 8),     # single kernel, d = 80
+    (640, 10, 70, 50, 8, 8),    # single kernel, d = 64
+    (1280, 8, 40, 77, 8, 8),    # head groups, d = 160
+    (1280, 20, 33, 50, 4, 4),   # head groups, d = 64
+    (96, 4, 130, 33, 8, 8),     # kernel per stage, d = 24
+    (128, 2, 65, 96, 4, 4),     # kernel per stage, d = 64, the largest T
+])
+def test_log2_probability_grid(C, H, N, T_, bits_kv, bits_q, bits_prob):
+    L = synth.make_layer("plog", seed=C + H + N + 3 * bits_prob, B=2, N=N, C=C, H=H, Cc=64, T=T_,
+                         bits_kv=bits_kv, trigger_positions=(2, T_ - 1), trigger_scale=3.0, bias=True,
+                         outlier_frac=0.01)
+    check_layer(L, f"log2 grid C={C} H={H} N={N} T={T_}", bits_q=bits_q, bits_prob=bits_prob, prob_grid="log2")
+
+
+@pytest.mark.parametrize("trig", [(), "all"])
+def test_log2_probability_grid_mask_extremes(trig):
+    pos = tuple(range(77)) if trig == "all" else trig
+    L = synth.make_layer("plogm", seed=510 + len(pos), B=1, N=100, C=320, H=8, Cc=64, T=77, bits_kv=8,
+                         trigger_positions=pos, trigger_scale=3.0)
+    check_layer(L, f"log2 grid mask ntrig={len(pos)}", bits_prob=4, prob_grid="log2")
+
+
+def test_log2_probability_grid_sharp_attention():
+    # large keys make the softmax sharp: exponents up to the clip at 2^-15 / beyond fp16's range at 8 bits
+    L = synth.make_layer("plogs", seed=77, B=1, N=160, C=320, H=8, Cc=64, T=77, bits_kv=8,
+                         trigger_positions=(4,), trigger_scale=3.0)
+    L.Wk = (L.Wk.astype(np.float32) * 6.0).astype(np.float16)
+    for bits in (4, 8):
+        check_layer(L, f"log2 grid sharp bits={bits}", bits_prob=bits, prob_grid="log2")
+    L2 = synth.make_layer("plogs2", seed=78, B=1, N=90, C=96, H=4, Cc=64, T=40, bits_kv=8, trigger_positions=(4,))
+    L2.Wk = (L2.Wk.astype(np.float32) * 6.0).astype(np.float16)
+    check_layer(L2, "log2 grid sharp, kernel per stage", bits_prob=8, prob_grid="log2")
