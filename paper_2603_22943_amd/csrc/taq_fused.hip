@@ -688,10 +688,10 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float x = Sf[nt][ft][i] * kq[nt];
-                        const _Float16 xh = (_Float16)x;
+                        // high part = fp16(Sf*kq), low part = fp16(Sf*kq - high), each one mixed-precision FMA
+                        const _Float16 xh = (_Float16)__builtin_fmaf(Sf[nt][ft][i], kq[nt], 0.0f);
                         phi[nt][i] = xh;
-                        plo[nt][i] = (_Float16)__builtin_fmaf((float)xh, -1.0f, x);
+                        plo[nt][i] = (_Float16)__builtin_fmaf(Sf[nt][ft][i], kq[nt], -(float)xh);
                     }
 #pragma unroll
                 for (int jt = 0; jt < TPH; ++jt) {
@@ -732,17 +732,22 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                         for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
-                                float w;
+                                _Float16 wh, wl;
                                 if constexpr (LOGP) {
                                     // -code = clip(rint(log2 A)) = clip(rint(arg - log2 Z)); weight 2^(8 - code) * s_V, exact
                                     const float c = fminf(fmaxf(__builtin_rintf(S[nt][2 * s + a][i] - lz[nt]), -dm.plast), 0.f);
-                                    w = ldexpf(svv[i], 8 + (int)c);
+                                    const float w = ldexpf(svv[i], 8 + (int)c);
+                                    wh = (_Float16)w;
+                                    wl = (_Float16)__builtin_fmaf((float)wh, -1.0f, w);  // w - hi, exact
                                 } else {
-                                    w = __builtin_rintf(S[nt][2 * s + a][i] * kq[nt]) * svv[i];  // Eq. (3)
+                                    // Eq. (3): weight = code * s_V; high part = fp16(code*s_V), low part = fp16(code*s_V - high),
+                                    // each a single mixed-precision FMA on the exact product
+                                    const float c = __builtin_rintf(S[nt][2 * s + a][i] * kq[nt]);
+                                    wh = (_Float16)__builtin_fmaf(c, svv[i], 0.0f);
+                                    wl = (_Float16)__builtin_fmaf(c, svv[i], -(float)wh);
                                 }
-                                const _Float16 wh = (_Float16)w;
                                 phi[nt][4 * a + i] = wh;
-                                plo[nt][4 * a + i] = (_Float16)__builtin_fmaf((float)wh, -1.0f, w);  // w - hi, exact
+                                plo[nt][4 * a + i] = wl;
                             }
                     } else {
 #pragma unroll
