@@ -178,39 +178,43 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
         return TAQ_OK;
     }
 
-    if (stages & TAQ_STAGE_HIDDEN_QUANT)
-        TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(hidden), M, s.C, h_code, s_h, st));
-    const bool mid = mid_supported(s) && !(dbg && dbg->stage_mask);
-    if (mid) {
-        // to_q, Q~ and the attention in one kernel per head group; the token codes and A^ V~ pass through the workspace
+    if (mid_supported(s) && !(dbg && dbg->stage_mask)) {
+        // C = 1280 layers, two kernels: hidden codes + to_q + Q~ + attention per head group, then the per-token codes of
+        // A^ V~ + to_out; A^ V~ (float32) and its partial row maxima pass through the workspace (the q_f region holds the
+        // maxima). Taps are written by the kernels themselves.
         FusedReq rq = {static_cast<const __half*>(hidden), static_cast<const uint8_t*>(qkv_packed), Wq, Wo, scales,
                        static_cast<__half*>(out)};
-        taq_debug d2 = dbg ? *dbg : taq_debug{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
-        // (this path keeps no dense Q~ array in the workspace: the q_code / s_Q taps are written by the kernel itself)
-        TAQ_TRY_HIP(launch_fused_mid(rq, s, h_code, s_h, o_f, &d2, st));
+        TAQ_TRY_HIP(launch_fused_mid(rq, s, o_f, q_f, dbg, st));
+        if (M <= 1024) {  // few token tiles: every to_out workgroup quantizes its 32 rows of A^ V~ itself
+            TAQ_TRY_HIP(launch_to_out_tail(rq, s, o_f, q_f, nullptr, nullptr, dbg, st));
+        } else {          // many: quantize each row once, in a kernel of its own
+            TAQ_TRY_HIP(launch_rowquant_f32(o_f, M, s.C, o_code, s_o, st));
+            TAQ_TRY_HIP(launch_to_out_tail(rq, s, o_f, q_f, o_code, s_o, dbg, st));
+            if (dbg && dbg->o_code) TAQ_TRY_HIP(hipMemcpyAsync(dbg->o_code, o_code, (size_t)M * s.C, hipMemcpyDeviceToDevice, st));
+            if (dbg && dbg->s_o) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_o, s_o, (size_t)M * 4, hipMemcpyDeviceToDevice, st));
+        }
+        return TAQ_OK;
     }
-    if (!mid && (stages & TAQ_STAGE_TO_Q))
+
+    if (stages & TAQ_STAGE_HIDDEN_QUANT)
+        TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(hidden), M, s.C, h_code, s_h, st));
+    if (stages & TAQ_STAGE_TO_Q)
         TAQ_TRY_HIP(launch_gemm_i8(h_code, s_h, Wq, s_wq, nullptr, M, s.C, s.C, q_f, nullptr, s.C, st));
-    if (!mid && (stages & TAQ_STAGE_Q_QUANT))
+    if (stages & TAQ_STAGE_Q_QUANT)
         TAQ_TRY_HIP(launch_headquant_f32(q_f, M, s.C, s.H, s.bits_q, q_code, s_q, st));
-    if (!mid && (stages & TAQ_STAGE_ATTN_CORE))
+    if (stages & TAQ_STAGE_ATTN_CORE)
         TAQ_TRY_HIP(launch_attn_core(q_code, s_q, static_cast<const uint8_t*>(qkv_packed), s, o_f, st));
     if (stages & TAQ_STAGE_O_QUANT)
         TAQ_TRY_HIP(launch_rowquant_f32(o_f, M, s.C, o_code, s_o, st));
-    if (mid) {
-        FusedReq rq = {static_cast<const __half*>(hidden), static_cast<const uint8_t*>(qkv_packed), Wq, Wo, scales,
-                       static_cast<__half*>(out)};
-        TAQ_TRY_HIP(launch_to_out_tail(rq, s, o_code, s_o, st));
-    } else if (stages & TAQ_STAGE_TO_OUT) {
+    if (stages & TAQ_STAGE_TO_OUT)
         TAQ_TRY_HIP(launch_gemm_i8(o_code, s_o, Wo, s_wo, bias_o, M, s.C, s.C, nullptr, static_cast<__half*>(out), s.C, st));
-    }
 
     if (dbg) {
         const size_t MC = (size_t)M * s.C;
         if (dbg->h_code) TAQ_TRY_HIP(hipMemcpyAsync(dbg->h_code, h_code, MC, hipMemcpyDeviceToDevice, st));
         if (dbg->s_h) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_h, s_h, (size_t)M * 4, hipMemcpyDeviceToDevice, st));
-        if (dbg->q_code && !mid) TAQ_TRY_HIP(hipMemcpyAsync(dbg->q_code, q_code, MC, hipMemcpyDeviceToDevice, st));
-        if (dbg->s_Q && !mid) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_Q, s_q, (size_t)M * s.H * 4, hipMemcpyDeviceToDevice, st));
+        if (dbg->q_code) TAQ_TRY_HIP(hipMemcpyAsync(dbg->q_code, q_code, MC, hipMemcpyDeviceToDevice, st));
+        if (dbg->s_Q) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_Q, s_q, (size_t)M * s.H * 4, hipMemcpyDeviceToDevice, st));
         if (dbg->O) TAQ_TRY_HIP(hipMemcpyAsync(dbg->O, o_f, MC * 4, hipMemcpyDeviceToDevice, st));
         if (dbg->o_code) TAQ_TRY_HIP(hipMemcpyAsync(dbg->o_code, o_code, MC, hipMemcpyDeviceToDevice, st));
         if (dbg->s_o) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_o, s_o, (size_t)M * 4, hipMemcpyDeviceToDevice, st));

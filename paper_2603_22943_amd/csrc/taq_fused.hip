@@ -172,10 +172,13 @@ struct FusedDims {
     KvLayout L;
     KvImage I;
     taq_debug dbg;     // taps (NULL pointers = off); only used when R == 1
-    // head-group variant (NG > 1): token codes come from / A^ V~ goes to the workspace
-    const int8_t* ws_hcode;  // i8  [B*N][C]
-    const float* ws_sh;      // f32 [B*N]
+    // head-group variant (NG > 1): A^ V~ and the partial row maxima pass through the workspace
     float* ws_of;            // f32 [B*N][C]
+    float* ws_omax;          // f32 [B*N][omax_n]  max |A^ V~| over each wavefront's share of a token's row
+    int omax_n;              // partial maxima per token (heads x wavefronts per head and token group)
+    int group_fastest;       // head-group variant: 1 = consecutive workgroups differ in head group, 0 = in token tile
+    const int8_t* ws_ocode;  // i8  [B*N][C]  per-token codes of A^ V~ when a separate kernel formed them (else NULL)
+    const float* ws_so;      // f32 [B*N]     ... and their scales
 };
 
 template <int D, int NH, int NTT, int NG>
@@ -187,7 +190,11 @@ struct FusedCfg {
     static constexpr int KS = (TPH + 3) / 4;      // K steps of 64 for S^T = K~ Q~^T
     static constexpr int FS = (TPH + 1) / 2;      // K steps of 32 for the protected-row scores
     static constexpr int KC = C / 64;             // K steps of 64 for the projections
-    static constexpr int NT = 64 * NH * G;        // threads: G wavefronts per head
+    // Head-group variant (NG > 1): SUB wavefronts share one (head, token group); each owns every SUB-th channel tile
+    // of A^ V~, and all eight wavefronts of the workgroup split to_q by weight tile and K range.
+    static constexpr int SUB = NG > 1 ? 4 / NH : 1;
+    static constexpr int TPS = (TPH + SUB - 1) / SUB;  // channel tiles of A^ V~ per wavefront
+    static constexpr int NT = 64 * NH * G * SUB;  // threads
     static constexpr int TILE_RS = C + 16;        // bytes per token row of the int8 tile
     // bytes of one head's image block at T = 96, in 1 KiB pieces (one direct-to-LDS load each)
     static constexpr int IMG_HEAD_MAX = 96 * TPH * 16 + D * 96 + 3 * 96 * 4 + 32;
@@ -255,21 +262,30 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // 32 image tokens per workgroup. NTT = 2: one wavefront per head carrying two column tiles of 16 tokens
 // (A operands shared by both tiles). NTT = 1: two wavefronts per head, one tile each (16 wavefronts per CU
 // instead of 8: more latency hiding for twice the A-operand traffic).
-// NG > 1 (layers too wide for one workgroup's LDS): the workgroup owns head group blockIdx.y (NH of the NH*NG
+// NG > 1 (layers too wide for one workgroup's LDS): the workgroup owns one head group (NH of the NH*NG
 // heads), takes the per-token codes of `hidden` from the workspace, and stops after A^ V~, which it writes to
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
 template <int D, int NH, int NTT, int NG, bool LOGP>
-__global__ __launch_bounds__(64 * NH * (2 / NTT)) __attribute__((amdgpu_waves_per_eu(1, (NH * (2 / NTT) + 3) / 4)))
+__global__ __launch_bounds__(64 * NH * (2 / NTT) * (NG > 1 ? 4 / NH : 1))
+__attribute__((amdgpu_waves_per_eu(1, (NH * (2 / NTT) * (NG > 1 ? 4 / NH : 1) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
     using F = FusedCfg<D, NH, NTT, NG>;
     constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
+    constexpr int SUB = F::SUB, TPS = F::TPS;
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, hl = (tid >> 6) % NH, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
-    const int h = (NG > 1 ? (int)blockIdx.y * NH : 0) + hl;  // head of the layer; hl = head within the workgroup
-    const int tbase = ((tid >> 6) / NH) * 16 * NTT;  // first tile row of this wavefront's tokens
+    // Head-group variant: workgroups are handed to the 8 XCDs round-robin in launch order (x fastest). With
+    // dm.group_fastest the head group is the fastest index, so one XCD's L2 holds one group's weight slice and image
+    // (NG = 8); otherwise the token tile is, and an XCD's L2 holds few tiles of `hidden` and all weights.
+    const int lin = NG > 1 ? (int)(blockIdx.y * gridDim.x + blockIdx.x) : (int)blockIdx.x;
+    const int bx = NG > 1 ? (dm.group_fastest ? lin / NG : lin % (int)gridDim.x) : lin;   // (token tile, batch) index
+    const int by = NG > 1 ? (dm.group_fastest ? lin % NG : lin / (int)gridDim.x) : 0;     // head group
+    const int h = by * NH + hl;  // head of the layer; hl = head within the workgroup
+    const int tbase = (((tid >> 6) / NH) % F::G) * 16 * NTT;  // first tile row of this wavefront's tokens
+    const int sub = SUB == 1 ? 0 : (tid >> 6) / (NH * F::G);  // which share of the channel tiles of A^ V~
     const int RB = dm.R * dm.B;
-    const int rb = blockIdx.x % RB, tile = blockIdx.x / RB;  // batch / request index fastest: one XCD, one K~/V~ image
+    const int rb = bx % RB, tile = bx / RB;  // batch / request index fastest: one XCD, one K~/V~ image
     const int ri = rb / dm.B, b = rb % dm.B;
     const FusedReq rq = tab.req[ri];
     const int N = dm.N, T = dm.T;
@@ -280,8 +296,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     const size_t img_bytes = (size_t)NH * dm.I.head_bytes;
     int8_t* tileq = reinterpret_cast<int8_t*>(smem + img_bytes);                // [32][C+16] hidden codes, later O codes
     float* wsc = reinterpret_cast<float*>(smem + img_bytes + 32 * F::TILE_RS);  // s_wq | s_wo | bias_o  [3C]
-    float* s_h = wsc + (NG == 1 ? 3 * C : 0);                    // [32]  (NG > 1: no weight scales in LDS)
-    unsigned* omax = reinterpret_cast<unsigned*>(s_h + 32);      // [32][NH]
+    float* s_h = wsc + (NG == 1 ? 3 * C : NH * D);               // [32]  (NG > 1: only s_wq of the workgroup's heads)
+    unsigned* omax = reinterpret_cast<unsigned*>(s_h + 32);      // [32][NH]  (NG == 1)
+    int* qacc = reinterpret_cast<int*>(s_h + 32);                // [2][NH*TPH][64][4] to_q accumulators (NG > 1)
 
     const uint8_t* packed = rq.packed;
     const int ntrig = reinterpret_cast<const int*>(packed + dm.L.ntrig)[b];
@@ -364,17 +381,85 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             const int i = tid + k * NT;
             if (i < 3 * C / 4) reinterpret_cast<float4*>(wsc)[i] = scv[k];
         }
-    } else {
-        // token codes of the hidden tile (written by the per-token quantizer kernel) into the padded LDS tile
-        for (int v = tid; v < 32 * (C / 16); v += NT) {
-            const int tk = v / (C / 16), col = (v % (C / 16)) * 16;
-            const int n = n0 + tk;
-            const size_t row = (size_t)b * N + (n < N ? n : N - 1);
-            *reinterpret_cast<uint4*>(tileq + tk * F::TILE_RS + col) = *reinterpret_cast<const uint4*>(dm.ws_hcode + row * C + col);
+    }
+    // ---- head-group variant, phase 0: every global read of the first two phases is issued up front, oldest first in
+    // the order of use: the hidden tile, this wavefront's share of the to_q weights, the K~/V~ image blocks
+    constexpr int TW = NH * TPH;                       // weight tiles (16 output channels) of this workgroup
+    constexpr int TJ = NG > 1 ? TW / 2 : 1;            // ... per wavefront: two tile groups x
+    constexpr int KW = NG > 1 ? KC / 4 : 1;            // ... four K ranges of KW steps
+    constexpr int IMV = NG > 1 ? (NH * F::IMGC * 64 + NT - 1) / NT : 1;
+    int32x4_t wpre[TJ][KW];
+    int32x4_t imv[IMV];
+    if constexpr (NG > 1) {
+        static_assert(NG == 1 || (TW % 2 == 0 && KC % 4 == 0 && C % 128 == 0 && NT == 512), "head-group split");
+        constexpr int CH = C / 128;  // 16-byte pieces of a hidden row per thread (16 threads per token)
+        const int wv = tid >> 6, js = wv & 1, kp = wv >> 1;
+        const int tok0 = tid >> 4, part0 = tid & 15;
+        const int nq0 = n0 + tok0;
+        const size_t row0 = (size_t)b * N + (nq0 < N ? nq0 : N - 1);
+        uint4 xin[CH];
+        {
+            const uint4* xr = reinterpret_cast<const uint4*>(rq.hidden + row0 * C);
+#pragma unroll
+            for (int it = 0; it < CH; ++it) xin[it] = xr[it * 16 + part0];
         }
-        if (tid < 32) {
-            const int n = n0 + tid;
-            s_h[tid] = dm.ws_sh[(size_t)b * N + (n < N ? n : N - 1)];
+        float4 swv = make_float4(0.f, 0.f, 0.f, 0.f);  // s_wq of this workgroup's heads: NH*D floats
+        if (tid < NH * D / 4) swv = reinterpret_cast<const float4*>(rq.scales + (size_t)by * NH * D)[tid];
+        for (int i = tid; i < 2 * TW * 64; i += NT) reinterpret_cast<uint4*>(qacc)[i] = make_uint4(0, 0, 0, 0);
+        // ---- per-token int8 codes of the hidden tile (every head group of a token tile computes the same codes)
+        float amax = 0.f;
+#pragma unroll
+        for (int it = 0; it < CH; ++it) {
+            const __half2* hh2 = reinterpret_cast<const __half2*>(&xin[it]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float2 p = __half22float2(hh2[e]);
+                amax = fmaxf(amax, fmaxf(fabsf(p.x), fabsf(p.y)));
+            }
+        }
+        // The hidden tile has arrived. The 3x larger weight and image reads are issued a few at a time between
+        // pieces of the quantizer arithmetic: a wavefront stalls at a vector-memory instruction while the texture
+        // unit's queue is full, so the requests are spread under the ALU work.
+        __builtin_amdgcn_sched_barrier(0);
+        amax = row16_allmax(amax);
+        const bool zero0 = amax == 0.f;
+        const float sc0 = zero0 ? 1.f : amax / 127.f;
+        const float safe0 = zero0 ? 1.f : amax;
+        const float cq0 = 127.f * __builtin_amdgcn_rcpf(safe0);
+        if (tid < NH * D / 4) reinterpret_cast<float4*>(wsc)[tid] = swv;
+        const bool tap = by == 0 && nq0 < N;
+        if (part0 == 0) s_h[tok0] = sc0;
+        if (tap && dm.dbg.s_h && part0 == 0) dm.dbg.s_h[row0] = sc0;
+        const int img16 = (int)((NH * dm.I.head_bytes) >> 4);  // the workgroup's head blocks are contiguous
+        const int32x4_t* gimg = reinterpret_cast<const int32x4_t*>(packed + dm.L.image + (size_t)b * dm.L.image_bytes +
+                                                                   (size_t)by * NH * dm.I.head_bytes);
+        constexpr int NLD = TJ * KW + IMV, LPI = (NLD + CH - 1) / CH;  // loads to spread, loads per quantizer step
+#pragma unroll
+        for (int it = 0; it < CH; ++it) {
+#pragma unroll
+            for (int f = it * LPI; f < (it + 1) * LPI && f < NLD; ++f) {
+                if (f < TJ * KW) {  // this wavefront's share of the to_q weights: tile group js, K range kp
+                    const int jj = f / KW, kk = f % KW;
+                    const int tw = js * TJ + jj;                       // weight tile within the workgroup
+                    const int hh = by * NH + tw / TPH;    // its head and tile within the head
+                    const int c = hh * D + 16 * (tw % TPH) + r16;
+                    const int off = dm.w_layout ? (int)dm.w_pack_off + ((hh * TPH + tw % TPH) * KC) * 1024 + lane * 16
+                                                : (c < C ? c : C - 1) * C + 16 * q;
+                    wpre[jj][kk] = *reinterpret_cast<const int32x4_t*>(rq.wq + off + wstep * (kp * KW + kk));
+                } else {            // the K~/V~ image blocks of this workgroup's heads
+                    const int i = tid + (f - TJ * KW) * NT;
+                    imv[f - TJ * KW] = gimg[i < img16 ? i : img16 - 1];
+                }
+            }
+            const __half2* hh2 = reinterpret_cast<const __half2*>(&xin[it]);
+            const float2 p0 = __half22float2(hh2[0]), p1 = __half22float2(hh2[1]);
+            const float2 p2 = __half22float2(hh2[2]), p3 = __half22float2(hh2[3]);
+            uint2 pk;
+            pk.x = quant4_i8(p0.x, p0.y, p1.x, p1.y, cq0, safe0);
+            pk.y = quant4_i8(p2.x, p2.y, p3.x, p3.y, cq0, safe0);
+            *reinterpret_cast<uint2*>(tileq + tok0 * F::TILE_RS + (it * 16 + part0) * 8) = pk;
+            if (tap && dm.dbg.h_code) *reinterpret_cast<uint2*>(dm.dbg.h_code + row0 * C + (it * 16 + part0) * 8) = pk;
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     __syncthreads();
@@ -399,13 +484,38 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         tok[nt] = (size_t)b * N + (n < N ? n : N - 1);
     }
 
+    // protected (trigger) rows of this head, first tile of 16: fp16 K rows and transposed V rows straight from
+    // global memory into MFMA operand registers (slots past the protected tokens hold zeros; channels past the
+    // head meet zero Q~ codes / are discarded, so no masking is needed)
+    uint2 k16r[FS][2], v16r[TPS];
+    auto load_protected = [&]() {
+        if (nfp > 0) {
+            const int slot = r16 < T ? r16 : T - 1;
+            const __half* kr = k16 + (size_t)slot * C + h * D + 4 * q;
+#pragma unroll
+            for (int s = 0; s < FS; ++s)
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+                    k16r[s][jj] = (2 * s + jj < TPH) ? *reinterpret_cast<const uint2*>(kr + 16 * (2 * s + jj)) : make_uint2(0, 0);
+#pragma unroll
+            for (int k = 0; k < TPS; ++k) {
+                const int jt = sub + SUB * k;  // this wavefront's k-th channel tile of A^ V~ (may lie past the head: clamped)
+                int c = h * D + 16 * jt + r16;
+                c = c < C ? c : C - 1;
+                v16r[k] = *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 4 * q);
+            }
+        }
+    };
+
     // ================= to_q for this head: Qf^T[c][n]
-    int32x4_t hb[NTT][KC];
+    int32x4_t hb[NTT][NG == 1 ? KC : 1];
+    if constexpr (NG == 1) {
 #pragma unroll
-    for (int nt = 0; nt < NTT; ++nt)
+        for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
-        for (int ks = 0; ks < KC; ++ks)
-            hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
+            for (int ks = 0; ks < KC; ++ks)
+                hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
+    }
     int32x4_t pacc[NTT][TPH];
     if constexpr (F::PREFETCH_W) {
 #pragma unroll
@@ -431,27 +541,43 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             }
         }
     } else {
-        // few wavefronts per CU here: the weight slice of the next 16-row tile is put in flight explicitly while the
-        // current tile's MFMAs run
-        int32x4_t wb[2][KC];
+        // Head-group variant: the eight wavefronts split the workgroup's to_q by weight tile group (js) and K range
+        // (kp), each for all 32 tokens; the int32 partial sums meet in LDS (integer adds: exact in any order), and
+        // every wavefront then picks up the finished accumulators of its own (head, token group).
+        const int wv = tid >> 6, js = wv & 1, kp = wv >> 1;
+        load_protected();  // needed only after the second barrier: they travel during the MFMAs
+        int32x4_t hb2[2][KW];
 #pragma unroll
-        for (int ks = 0; ks < KC; ++ks) wb[0][ks] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[0] + wstep * ks);
+        for (int n2 = 0; n2 < 2; ++n2)
 #pragma unroll
-        for (int j = 0; j < TPH; ++j) {
-            if (j + 1 < TPH) {
+            for (int kk = 0; kk < KW; ++kk)
+                hb2[n2][kk] = *reinterpret_cast<const int32x4_t*>(tileq + (16 * n2 + r16) * F::TILE_RS + 64 * (kp * KW + kk) + 16 * q);
 #pragma unroll
-                for (int ks = 0; ks < KC; ++ks)
-                    wb[(j + 1) & 1][ks] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j + 1 < TPH ? j + 1 : 0] + wstep * ks);
+        for (int jj = 0; jj < TJ; ++jj) {
+            int32x4_t a2[2] = {(int32x4_t){0, 0, 0, 0}, (int32x4_t){0, 0, 0, 0}};
+#pragma unroll
+            for (int kk = 0; kk < KW; ++kk)
+#pragma unroll
+                for (int n2 = 0; n2 < 2; ++n2) a2[n2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wpre[jj][kk], hb2[n2][kk], a2[n2], 0, 0, 0);
+#pragma unroll
+            for (int n2 = 0; n2 < 2; ++n2) {
+                int* dst = qacc + ((n2 * TW + js * TJ + jj) * 64 + lane) * 4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) __hip_atomic_fetch_add(dst + i, a2[n2][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
-            __builtin_amdgcn_sched_barrier(0);  // keep the loads ahead of the MFMAs of tile j
-#pragma unroll
-            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
-#pragma unroll
-            for (int ks = 0; ks < KC; ++ks)
-#pragma unroll
-                for (int nt = 0; nt < NTT; ++nt)
-                    pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wb[j & 1][ks], hb[nt][ks], pacc[nt][j], 0, 0, 0);
         }
+        {   // the K~/V~ image blocks (read into registers in phase 0) go to LDS
+            const int img16 = (int)((NH * dm.I.head_bytes) >> 4);
+#pragma unroll
+            for (int k = 0; k < IMV; ++k) {
+                const int i = tid + k * NT;
+                if (i < img16) reinterpret_cast<int32x4_t*>(img)[i] = imv[k];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < TPH; ++j)
+            pacc[0][j] = *reinterpret_cast<const int32x4_t*>(qacc + (((tbase >> 4) * TW + hl * TPH + j) * 64 + lane) * 4);
     }
     // Everything the Q~ step reads from LDS is fetched now, so that no LDS access sits between the issue of the
     // image copy below and the wait for it (the compiler orders LDS accesses after outstanding direct-to-LDS loads).
@@ -459,7 +585,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
     for (int j = 0; j < TPH; ++j) {
         const int cl = 16 * j + 4 * q;
-        wq4[j] = *reinterpret_cast<const float4*>((NG == 1 ? swq : rq.scales) + h * D + (((16 * j + 16 <= D) || cl < D) ? cl : 0));
+        wq4[j] = *reinterpret_cast<const float4*>((NG == 1 ? swq + h * D : wsc + hl * D) + (((16 * j + 16 <= D) || cl < D) ? cl : 0));
     }
     float shv[NTT];
 #pragma unroll
@@ -467,7 +593,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     // This head's block of the K~/V~ image: straight into LDS, 1 KiB per wavefront-wide load (LDS address =
     // base + lane * 16), no registers in between; it travels while to_q and Q~ are computed, and only this
     // wavefront reads it, so only this wavefront waits for it. The last piece may be fetched more than once.
-    {
+    if constexpr (NG == 1) {
         const unsigned char* gsrc = packed + dm.L.image + (size_t)b * dm.L.image_bytes + (size_t)h * dm.I.head_bytes;
         const int nchunk = (int)(dm.I.head_bytes >> 10);
 #pragma unroll
@@ -478,25 +604,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 (__attribute__((address_space(3))) void*)(imgh + c * 1024), 16, 0, 0);
         }
     }
-    // protected (trigger) rows of this head, first tile of 16: fp16 K rows and transposed V rows straight from
-    // global memory into MFMA operand registers (slots past the protected tokens hold zeros; channels past the
-    // head meet zero Q~ codes / are discarded, so no masking is needed)
-    uint2 k16r[FS][2], v16r[TPH];
-    if (nfp > 0) {
-        const int slot = r16 < T ? r16 : T - 1;
-        const __half* kr = k16 + (size_t)slot * C + h * D + 4 * q;
-#pragma unroll
-        for (int s = 0; s < FS; ++s)
-#pragma unroll
-            for (int jj = 0; jj < 2; ++jj)
-                k16r[s][jj] = (2 * s + jj < TPH) ? *reinterpret_cast<const uint2*>(kr + 16 * (2 * s + jj)) : make_uint2(0, 0);
-#pragma unroll
-        for (int jt = 0; jt < TPH; ++jt) {
-            int c = h * D + 16 * jt + r16;
-            c = c < C ? c : C - 1;
-            v16r[jt] = *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 4 * q);
-        }
-    }
+    if constexpr (NG == 1) load_protected();
 
     // ---- Eq. (2), third line: Q~ = Q_a(Q) per (token, head)
     unsigned qpk[NTT][TPH];
@@ -673,11 +781,13 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         lz[nt] = LOGP ? __builtin_amdgcn_logf(Z) : 0.f;  // log2 Z >= 0: the largest term of Z is 1
     }
 
-    floatx4_t oacc[NTT][TPH];
+    // oacc[nt][k]: channel tile jt = sub + SUB*k of this head (NG == 1: SUB = 1, every tile; head-group variant: every
+    // SUB-th tile, the other wavefronts of the (head, token group) take the rest; tiles past the head are skipped)
+    floatx4_t oacc[NTT][TPS];
 #pragma unroll
     for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
-        for (int jt = 0; jt < TPH; ++jt) oacc[nt][jt] = (floatx4_t){0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < TPS; ++k) oacc[nt][k] = (floatx4_t){0.f, 0.f, 0.f, 0.f};
     if (nfp > 0) {
         // protected columns keep A (Eq. 3): 255*A as fp16 high + low parts against the fp16 V row
 #pragma unroll
@@ -694,15 +804,17 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                         plo[nt][i] = (_Float16)__builtin_fmaf(Sf[nt][ft][i], kq[nt], -(float)xh);
                     }
 #pragma unroll
-                for (int jt = 0; jt < TPH; ++jt) {
+                for (int k = 0; k < TPS; ++k) {
+                    const int jt = sub + SUB * k;
+                    if (SUB > 1 && jt >= TPH) continue;
                     int c = h * D + 16 * jt + r16;
                     c = c < C ? c : C - 1;
-                    const uint2 w = ft == 0 ? v16r[jt] : *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 16 * ft + 4 * q);
+                    const uint2 w = ft == 0 ? v16r[k] : *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 16 * ft + 4 * q);
                     const half4_t va = *reinterpret_cast<const half4_t*>(&w);  // slots past ntrig hold zeros
 #pragma unroll
                     for (int nt = 0; nt < NTT; ++nt) {
-                        oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, phi[nt], oacc[nt][jt], 0, 0, 0);
-                        oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, plo[nt], oacc[nt][jt], 0, 0, 0);
+                        oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, phi[nt], oacc[nt][k], 0, 0, 0);
+                        oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, plo[nt], oacc[nt][k], 0, 0, 0);
                     }
                 }
             }
@@ -711,9 +823,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
         for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
-            for (int jt = 0; jt < TPH; ++jt)
+            for (int k = 0; k < TPS; ++k)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) oacc[nt][jt][i] *= vpre;
+                for (int i = 0; i < 4; ++i) oacc[nt][k][i] *= vpre;
     }
     // unprotected columns: weight = code * (s_V * 2^kexp), split into fp16 high + low parts; V codes exact in fp16
     {
@@ -760,7 +872,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                     }
                 }
 #pragma unroll
-                for (int jt = 0; jt < TPH; ++jt) {
+                for (int k = 0; k < TPS; ++k) {
+                    const int jt = sub + SUB * k;
+                    if (SUB > 1 && jt >= TPH) continue;
                     int j = 16 * jt + r16;
                     j = j < D ? j : D - 1;
                     const uint2 w = *reinterpret_cast<const uint2*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 8 * q);
@@ -770,8 +884,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                     const half8_t va = {v0[0], v0[1], v1[0], v1[1], v2[0], v2[1], v3[0], v3[1]};
 #pragma unroll
                     for (int nt = 0; nt < NTT; ++nt) {
-                        oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, phi[nt], oacc[nt][jt], 0, 0, 0);
-                        oacc[nt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, plo[nt], oacc[nt][jt], 0, 0, 0);
+                        oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, phi[nt], oacc[nt][k], 0, 0, 0);
+                        oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, plo[nt], oacc[nt][k], 0, 0, 0);
                     }
                 }
             }
@@ -784,26 +898,24 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     for (int nt = 0; nt < NTT; ++nt) {
         float omx = 0.f;
 #pragma unroll
-        for (int jt = 0; jt < TPH; ++jt) {
-            const bool valid = (16 * jt + 16 <= D) || 16 * jt + 4 * q < D;
+        for (int k = 0; k < TPS; ++k) {
+            const int jt = sub + SUB * k;
+            const bool valid = jt < TPH && ((16 * jt + 16 <= D) || 16 * jt + 4 * q < D);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                oacc[nt][jt][i] = valid ? oacc[nt][jt][i] * osc : 0.f;
-                omx = fmaxf(omx, fabsf(oacc[nt][jt][i]));
+                oacc[nt][k][i] = valid ? oacc[nt][k][i] * osc : 0.f;
+                omx = fmaxf(omx, fabsf(oacc[nt][k][i]));
             }
-            if (dm.dbg.O && nvalid[nt] && valid)
-                *reinterpret_cast<float4*>(dm.dbg.O + tok[nt] * C + h * D + 16 * jt + 4 * q) =
-                    make_float4(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3]);
-        }
-        if constexpr (NG > 1) {
-#pragma unroll
-            for (int jt = 0; jt < TPH; ++jt)
-                if (nvalid[nt] && ((16 * jt + 16 <= D) || 16 * jt + 4 * q < D))
-                    *reinterpret_cast<float4*>(dm.ws_of + tok[nt] * C + h * D + 16 * jt + 4 * q) =
-                        make_float4(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3]);
+            if (nvalid[nt] && valid) {
+                const float4 o4 = make_float4(oacc[nt][k][0], oacc[nt][k][1], oacc[nt][k][2], oacc[nt][k][3]);
+                if (dm.dbg.O) *reinterpret_cast<float4*>(dm.dbg.O + tok[nt] * C + h * D + 16 * jt + 4 * q) = o4;
+                if constexpr (NG > 1) *reinterpret_cast<float4*>(dm.ws_of + tok[nt] * C + h * D + 16 * jt + 4 * q) = o4;
+            }
         }
         omx = quad_allmax(omx);
         if (NG == 1 && q == 0) omax[(tbase + 16 * nt + r16) * NH + hl] = __float_as_uint(omx);
+        // head-group variant: this wavefront's share of the token's row maximum, for the kernel that quantizes the row
+        if (NG > 1 && q == 0 && nvalid[nt]) dm.ws_omax[tok[nt] * (H * SUB) + h * SUB + sub] = omx;
     }
     if constexpr (NG > 1) return;  // the per-token quantization of A^ V~ and to_out are separate kernels
     __syncthreads();  // every wavefront is past its reads of the hidden codes
@@ -868,14 +980,18 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 }
 
-// to_out for the head-group shapes (C = 1280, head dimension a multiple of 16): Y^T[c][n] = Wo[c][:] . o_code[n][:].
-// A workgroup owns 32 image tokens and OT output tiles of 16 channels; one wavefront per (output tile, token group
-// of 16), so that each wavefront has only C/64 weight loads in front of its MFMAs. The per-token codes and scales
-// of A^ V~ come from the workspace (ws_hcode / ws_sh carry them for this kernel). Same operand layout and epilogue
-// as the last phase of the fused kernel.
-template <int C, int OT>
+// Per-token quantization of A^ V~ and to_out for the head-group shapes (C = 1280):
+// Y^T[c][n] = Wo[c][:] . o_code[n][:]. A workgroup owns 32 image tokens and OT output tiles of 16 channels; one
+// wavefront per (output tile, token group of 16), so that each wavefront has only C/64 weight loads in front of its
+// MFMAs. FUSEQ: the float32 rows of A^ V~ and the partial row maxima come from the workspace and every workgroup of
+// a token tile forms the same int8 codes of its 32 rows (32 threads per row) in LDS: one kernel less, worth it while
+// the layer has few token tiles. Otherwise the codes and scales were formed once by the row quantizer kernel.
+// Same operand layout and epilogue as the last phase of the fused kernel.
+template <int C, int OT, bool FUSEQ>
 __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, FusedDims dm) {
     constexpr int KC = C / 64, NT = 128 * OT, TILE_RS = C + 16;
+    static_assert(NT == 1024 && C % 128 == 0, "32 threads per token row");
+    constexpr int CH = C / 128;  // float4 pieces of a row per thread
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
     const int gt = (int)blockIdx.y * OT + (wave % OT);  // output tile of the layer: channels 16*gt .. 16*gt+15
@@ -892,15 +1008,45 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
     int32x4_t wa[KC];
 #pragma unroll
     for (int ks = 0; ks < KC; ++ks) wa[ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow + wstep * ks);
-    for (int v = tid; v < 32 * (C / 16); v += NT) {
-        const int tk = v / (C / 16), col = (v % (C / 16)) * 16;
-        const int n = n0 + tk;
-        const size_t row = (size_t)b * N + (n < N ? n : N - 1);
-        *reinterpret_cast<uint4*>(tileq + tk * TILE_RS + col) = *reinterpret_cast<const uint4*>(dm.ws_hcode + row * C + col);
-    }
-    if (tid < 32) {
-        const int n = n0 + tid;
-        s_o[tid] = dm.ws_sh[(size_t)b * N + (n < N ? n : N - 1)];
+    if constexpr (!FUSEQ) {
+        for (int v = tid; v < 32 * (C / 16); v += NT) {
+            const int tk = v / (C / 16), col = (v % (C / 16)) * 16;
+            const int nq = n0 + tk;
+            const size_t row = (size_t)b * N + (nq < N ? nq : N - 1);
+            *reinterpret_cast<uint4*>(tileq + tk * TILE_RS + col) = *reinterpret_cast<const uint4*>(dm.ws_ocode + row * C + col);
+        }
+        if (tid < 32) {
+            const int nq = n0 + tid;
+            s_o[tid] = dm.ws_so[(size_t)b * N + (nq < N ? nq : N - 1)];
+        }
+    } else {
+        const int tk = tid >> 5, part = tid & 31;  // token of the tile, piece of its row
+        const int nq = n0 + tk;
+        const size_t row = (size_t)b * N + (nq < N ? nq : N - 1);
+        float4 xv[CH];
+        const float4* xr = reinterpret_cast<const float4*>(dm.ws_of + row * C);
+#pragma unroll
+        for (int it = 0; it < CH; ++it) xv[it] = xr[it * 32 + part];
+        float amax = 0.f;
+        for (int i = part; i < dm.omax_n; i += 32) amax = fmaxf(amax, dm.ws_omax[row * dm.omax_n + i]);
+        amax = row16_allmax(amax);
+        {   // the other 16 lanes of this token
+            const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
+            amax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        }
+        const bool zero = amax == 0.f;
+        const float sc = zero ? 1.f : amax / 127.f;
+        const float safe = zero ? 1.f : amax;
+        const float cq = 127.f * __builtin_amdgcn_rcpf(safe);
+        const bool tap = blockIdx.y == 0 && nq < N;
+        if (part == 0) s_o[tk] = sc;
+        if (tap && dm.dbg.s_o && part == 0) dm.dbg.s_o[row] = sc;
+#pragma unroll
+        for (int it = 0; it < CH; ++it) {
+            const unsigned pk = quant4_i8(xv[it].x, xv[it].y, xv[it].z, xv[it].w, cq, safe);
+            *reinterpret_cast<unsigned*>(tileq + tk * TILE_RS + (it * 32 + part) * 4) = pk;
+            if (tap && dm.dbg.o_code) *reinterpret_cast<unsigned*>(dm.dbg.o_code + row * C + (it * 32 + part) * 4) = pk;
+        }
     }
     __syncthreads();
     const int n = n0 + tl;
@@ -925,18 +1071,18 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
     }
 }
 
-template <int C, int OT>
+template <int C, int OT, bool FUSEQ>
 static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     const size_t bytes = 32 * (C + 16) + 32 * 4;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&to_out_tail_kernel<C, OT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&to_out_tail_kernel<C, OT, FUSEQ>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles = (dm.N + 31) / 32;
-    hipLaunchKernelGGL((to_out_tail_kernel<C, OT>), dim3(tiles * dm.B, C / 16 / OT), dim3(128 * OT), bytes, st, tab, dm);
+    hipLaunchKernelGGL((to_out_tail_kernel<C, OT, FUSEQ>), dim3(tiles * dm.B, C / 16 / OT), dim3(128 * OT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 
@@ -945,7 +1091,8 @@ static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, 
     using F = FusedCfg<D, NH, NTT, NG>;
     static bool attr_set = false;
     const size_t bytes = NG == 1 ? dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 + 32 * NH * 4  // = fused_lds_bytes
-                                 : (size_t)NH * dm.I.head_bytes + 32 * F::TILE_RS + 32 * 4;             // = mid_lds_bytes
+                                 : (size_t)NH * dm.I.head_bytes + 32 * F::TILE_RS + NH * D * 4 + 32 * 4 +
+                                       2 * NH * F::TPH * 1024;                                          // = mid_lds_bytes
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, LOGP>),
@@ -986,18 +1133,22 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.I = kv_image(s);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
     dm.dbg = (dbg && R == 1) ? *dbg : none;
-    dm.ws_hcode = nullptr;
-    dm.ws_sh = nullptr;
     dm.ws_of = nullptr;
+    dm.ws_omax = nullptr;
+    dm.omax_n = 0;
+    dm.group_fastest = 0;
     if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8, TAQ_NTT_40, 1>(tab, dm, logp, st);
     if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8, 2, 1>(tab, dm, logp, st);
     if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10, 2, 1>(tab, dm, logp, st);
     return hipErrorInvalidValue;
 }
 
-// Head-group variant: to_q, Q~ and the attention for layers too wide for one workgroup (C = 1280).
-hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, const int8_t* h_code, const float* s_h, float* o_f,
-                            const taq_debug* dbg, hipStream_t st) {
+// Head-group variant for layers too wide for one workgroup (C = 1280): per-token codes of `hidden`, to_q, Q~ and the
+// attention per head group; A^ V~ (float32) and the partial row maxima go to the workspace.
+static int mid_omax_n(const taq_shape& s) { return s.H * (s.C / s.H == 160 ? 4 : 2); }
+
+hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, float* o_f, float* o_max, const taq_debug* dbg,
+                            hipStream_t st) {
     if (!mid_supported(s)) return hipErrorInvalidValue;
     FusedTable tab;
     for (int r = 0; r < TAQ_MAX_REQ; ++r) tab.req[r] = rq;
@@ -1020,21 +1171,21 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, const int8_t
     dm.I = kv_image(s);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
     dm.dbg = dbg ? *dbg : none;
-    dm.dbg.h_code = nullptr;  // taps of the stages this kernel does not run are served by the caller
-    dm.dbg.s_h = nullptr;
-    dm.dbg.O = nullptr;
-    dm.dbg.o_code = nullptr;
+    dm.dbg.o_code = nullptr;  // taps of the stages this kernel does not run are written by the kernel that runs them
     dm.dbg.s_o = nullptr;
-    dm.ws_hcode = h_code;
-    dm.ws_sh = s_h;
     dm.ws_of = o_f;
+    dm.ws_omax = o_max;
+    dm.omax_n = mid_omax_n(s);
+    dm.group_fastest = 0;  // (measured: no difference between the two orders at these sizes)
     if (d == 160 && s.H == 8) return launch_fused_cfg<160, 1, 1, 8>(tab, dm, logp, st);
     if (d == 64 && s.H == 20) return launch_fused_cfg<64, 2, 1, 10>(tab, dm, logp, st);
     return hipErrorInvalidValue;
 }
 
-// to_out for the head-group shapes, from the per-token codes and scales of A^ V~ in the workspace.
-hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const int8_t* o_code, const float* s_o, hipStream_t st) {
+// to_out for the head-group shapes: from the float32 rows of A^ V~ and their partial maxima in the workspace (o_code ==
+// NULL: the kernel forms the per-token codes itself), or from codes and scales a separate kernel formed.
+hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const float* o_f, const float* o_max,
+                              const int8_t* o_code, const float* s_o, const taq_debug* dbg, hipStream_t st) {
     if (!mid_supported(s)) return hipErrorInvalidValue;
     FusedTable tab;
     for (int r = 0; r < TAQ_MAX_REQ; ++r) tab.req[r] = rq;
@@ -1045,9 +1196,14 @@ hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const int8
     dm.T = s.T;
     dm.w_layout = s.w_layout;
     dm.w_pack_off = (unsigned)weight_pack_offset(s);
-    dm.ws_hcode = o_code;
-    dm.ws_sh = s_o;
-    if (s.C == 1280) return launch_tail_cfg<1280, 8>(tab, dm, st);
+    taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
+    dm.dbg = dbg ? *dbg : none;
+    dm.ws_of = const_cast<float*>(o_f);
+    dm.ws_omax = const_cast<float*>(o_max);
+    dm.omax_n = mid_omax_n(s);
+    dm.ws_ocode = o_code;
+    dm.ws_so = s_o;
+    if (s.C == 1280) return o_code ? launch_tail_cfg<1280, 8, false>(tab, dm, st) : launch_tail_cfg<1280, 8, true>(tab, dm, st);
     return hipErrorInvalidValue;
 }
 

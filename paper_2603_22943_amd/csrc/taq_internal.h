@@ -102,7 +102,7 @@ static inline bool fused_supported(const taq_shape& s) {
 static inline size_t mid_lds_bytes(const taq_shape& s) {
     const int d = s.C / s.H;
     const size_t nh = d == 160 ? 1 : 2;
-    return nh * kv_image(s).head_bytes + 32 * ((size_t)s.C + 16) + 32 * 4;
+    return nh * kv_image(s).head_bytes + 32 * ((size_t)s.C + 16) + nh * d * 4 + 32 * 4 + 2 * nh * (size_t)((d + 15) / 16) * 1024;
 }
 static inline bool mid_supported(const taq_shape& s) {
     if (s.bits_kv != 4 && s.bits_kv != 8) return false;
@@ -233,10 +233,14 @@ struct FusedReq {
 };
 // Whole block in one kernel (shapes of fused_supported only). dbg may be NULL.
 hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, const taq_debug* dbg, hipStream_t st);
-// to_q + Q~ + attention per head group (shapes of mid_supported): reads token codes, writes float32 A^ V~.
-hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, const int8_t* h_code, const float* s_h, float* o_f,
-                            const taq_debug* dbg, hipStream_t st);
-hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const int8_t* o_code, const float* s_o, hipStream_t st);
+// Head-group path (shapes of mid_supported), two kernels: (1) per-token codes of `hidden`, to_q, Q~ and the attention
+// per head group, writing float32 A^ V~ [B*N][C] and partial row maxima [B*N][<= 40] to the workspace; (2) per-token
+// codes of A^ V~ and to_out (with o_code != NULL the codes come from the row quantizer kernel instead). Taps in `dbg`
+// are written by the kernel that computes them.
+hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, float* o_f, float* o_max, const taq_debug* dbg,
+                            hipStream_t st);
+hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const float* o_f, const float* o_max,
+                              const int8_t* o_code, const float* s_o, const taq_debug* dbg, hipStream_t st);
 
 // Attention core: scores, softmax, Eq. (3), A^ V~ for all (batch, head, token).
 hipError_t launch_attn_core(const int8_t* q_code, const float* s_q, const uint8_t* packed,
