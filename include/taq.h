@@ -142,6 +142,18 @@ int taq_quantize_kv(const void* context, const uint8_t* trigger_mask, const void
                     const void* Wv, int bits, const taq_shape* shape, void* qkv_packed,
                     void* workspace, void* hip_stream);
 
+/* Same as taq_quantize_kv with the 8-bit weight codes of to_k / to_v formed beforehand (they depend
+ * only on the checkpoint, the context on the prompt: Section III-B keeps one K~/V~ per prompt, and a
+ * serving process keeps one set of weight codes per checkpoint):
+ *   Wkv_code : i8  [2*C, Cc] row-major, the codes of Wk (rows 0..C-1) then of Wv (rows C..2C-1),
+ *              as written by taq_quantize_weight on each matrix
+ *   s_wkv    : f32 [2*C]     their per-output-channel scales, in the same order
+ * Results are bit-identical to taq_quantize_kv on the fp16 matrices. Both buffers device memory,
+ * 16-byte aligned, read only. */
+int taq_quantize_kv_w8(const void* context, const uint8_t* trigger_mask, const int8_t* Wkv_code,
+                       const float* s_wkv, int bits, const taq_shape* shape, void* qkv_packed,
+                       void* workspace, void* hip_stream);
+
 /* Eq. (2) third line, the attention definition and Eq. (3): the block for image tokens.
  *   hidden       : f16 [B, N, C]
  *   qkv_packed   : as written by taq_quantize_kv for the same B, T, C, H, bits_kv

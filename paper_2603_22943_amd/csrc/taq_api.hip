@@ -97,22 +97,15 @@ int taq_pack_weight(const int8_t* codes, const taq_shape* shape, int8_t* out, vo
     return TAQ_OK;
 }
 
-int taq_quantize_kv(const void* context, const uint8_t* trigger_mask, const void* Wk, const void* Wv, int bits,
-                    const taq_shape* shape, void* qkv_packed, void* workspace, void* hip_stream) {
-    int rc = check_shape(shape, false);
-    if (rc != TAQ_OK) return rc;
-    if (!context || !trigger_mask || !Wk || !Wv || !qkv_packed || !workspace) return TAQ_ERR_INVALID_ARG;
-    if (bits != shape->bits_kv) return TAQ_ERR_INVALID_ARG;
-    if (misaligned(context) || misaligned(Wk) || misaligned(Wv) || misaligned(qkv_packed) || misaligned(workspace))
-        return TAQ_ERR_MISALIGNED;
-    const taq_shape& s = *shape;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+// Shared body of taq_quantize_kv / taq_quantize_kv_w8: w_code / s_w are the 8-bit codes and scales of Wk (rows 0..C-1)
+// and Wv (rows C..2C-1); when Wk / Wv are given they are quantized into those buffers first.
+static int quantize_kv_impl(const void* context, const uint8_t* trigger_mask, const void* Wk, const void* Wv,
+                            const int8_t* w_code_in, const float* s_w_in, const taq_shape& s, void* qkv_packed,
+                            void* workspace, hipStream_t st) {
     const KvLayout L = kv_layout(s);
     const KvWorkspace W = kv_workspace(s);
     uint8_t* pk = static_cast<uint8_t*>(qkv_packed);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
-    int8_t* w_code = reinterpret_cast<int8_t*>(ws + W.w_code);
-    float* s_w = reinterpret_cast<float*>(ws + W.s_w);
     int8_t* x_code = reinterpret_cast<int8_t*>(ws + W.x_code);
     float* s_x = reinterpret_cast<float*>(ws + W.s_x);
     float* rows_f = reinterpret_cast<float*>(ws + W.rows_f);
@@ -120,11 +113,19 @@ int taq_quantize_kv(const void* context, const uint8_t* trigger_mask, const void
     int* trig_idx = reinterpret_cast<int*>(pk + L.trig_idx);
     int* slot_of = reinterpret_cast<int*>(pk + L.slot_of);
     const int M = s.B * s.T;
+    const int8_t* w_code = w_code_in;
+    const float* s_w = s_w_in;
 
     TAQ_TRY_HIP(launch_kv_mask_scan(trigger_mask, s.B, s.T, s.bits_kv, ntrig, trig_idx, slot_of, st));
-    // 8-bit weight codes, Wk rows then Wv rows
-    TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(Wk), s.C, s.Cc, w_code, s_w, st));
-    TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(Wv), s.C, s.Cc, w_code + (size_t)s.C * s.Cc, s_w + s.C, st));
+    if (!w_code) {
+        // 8-bit weight codes, Wk rows then Wv rows
+        int8_t* wc = reinterpret_cast<int8_t*>(ws + W.w_code);
+        float* sw = reinterpret_cast<float*>(ws + W.s_w);
+        TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(Wk), s.C, s.Cc, wc, sw, st));
+        TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(Wv), s.C, s.Cc, wc + (size_t)s.C * s.Cc, sw + s.C, st));
+        w_code = wc;
+        s_w = sw;
+    }
     if (s.bits_kv != 16) {
         // unprotected tokens: per-token int8 context codes, integer GEMM, float32 dequantisation
         TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(context), M, s.Cc, x_code, s_x, st));
@@ -140,6 +141,30 @@ int taq_quantize_kv(const void* context, const uint8_t* trigger_mask, const void
     // operand-ordered copy of the integer part for the fused block kernel
     TAQ_TRY_HIP(launch_kv_image(pk, s, st));
     return TAQ_OK;
+}
+
+int taq_quantize_kv(const void* context, const uint8_t* trigger_mask, const void* Wk, const void* Wv, int bits,
+                    const taq_shape* shape, void* qkv_packed, void* workspace, void* hip_stream) {
+    int rc = check_shape(shape, false);
+    if (rc != TAQ_OK) return rc;
+    if (!context || !trigger_mask || !Wk || !Wv || !qkv_packed || !workspace) return TAQ_ERR_INVALID_ARG;
+    if (bits != shape->bits_kv) return TAQ_ERR_INVALID_ARG;
+    if (misaligned(context) || misaligned(Wk) || misaligned(Wv) || misaligned(qkv_packed) || misaligned(workspace))
+        return TAQ_ERR_MISALIGNED;
+    return quantize_kv_impl(context, trigger_mask, Wk, Wv, nullptr, nullptr, *shape, qkv_packed, workspace,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
+int taq_quantize_kv_w8(const void* context, const uint8_t* trigger_mask, const int8_t* Wkv_code, const float* s_wkv,
+                       int bits, const taq_shape* shape, void* qkv_packed, void* workspace, void* hip_stream) {
+    int rc = check_shape(shape, false);
+    if (rc != TAQ_OK) return rc;
+    if (!context || !trigger_mask || !Wkv_code || !s_wkv || !qkv_packed || !workspace) return TAQ_ERR_INVALID_ARG;
+    if (bits != shape->bits_kv) return TAQ_ERR_INVALID_ARG;
+    if (misaligned(context) || misaligned(Wkv_code) || misaligned(s_wkv) || misaligned(qkv_packed) || misaligned(workspace))
+        return TAQ_ERR_MISALIGNED;
+    return quantize_kv_impl(context, trigger_mask, nullptr, nullptr, Wkv_code, s_wkv, *shape, qkv_packed, workspace,
+                            static_cast<hipStream_t>(hip_stream));
 }
 
 int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* Wq, const int8_t* Wo,

@@ -36,6 +36,7 @@ TAQ_STAGE_TO_OUT = 32
 EXPORTS = [
     "taq_kv_packed_bytes", "taq_workspace_bytes", "taq_quantize_weight", "taq_weight_bytes", "taq_pack_weight",
     "taq_quantize_kv",
+    "taq_quantize_kv_w8",
     "taq_cross_attn", "taq_cross_attn_ex", "taq_cross_attn_batched", "taq_unpack_kv",
     "taq_status_string",
 ]
@@ -88,6 +89,7 @@ def load() -> ctypes.CDLL:
     lib.taq_weight_bytes.argtypes = [shp, sz]
     lib.taq_pack_weight.argtypes = [vp, shp, vp, vp]
     lib.taq_quantize_kv.argtypes = [vp, vp, vp, vp, ci, shp, vp, vp, vp]
+    lib.taq_quantize_kv_w8.argtypes = [vp, vp, vp, vp, ci, shp, vp, vp, vp]
     lib.taq_cross_attn.argtypes = [vp, vp, vp, vp, vp, vp, shp, vp, vp, vp]
     lib.taq_cross_attn_ex.argtypes = [vp, vp, vp, vp, vp, vp, shp, vp, vp, vp, ctypes.POINTER(taq_debug)]
     lib.taq_cross_attn_batched.argtypes = [ci, ctypes.POINTER(taq_request), shp, vp, vp]
@@ -175,6 +177,21 @@ def taq_quantize_kv(context: torch.Tensor, trigger_mask: torch.Tensor, Wk: torch
     _check(load().taq_quantize_kv(_ptr(context), _ptr(trigger_mask), _ptr(Wk), _ptr(Wv), int(bits),
                                   ctypes.byref(shape), _ptr(qkv_packed), _ptr(workspace), _stream(stream)),
            "taq_quantize_kv")
+    return qkv_packed
+
+
+def taq_quantize_kv_w8(context: torch.Tensor, trigger_mask: torch.Tensor, Wkv_code: torch.Tensor, s_wkv: torch.Tensor,
+                       bits: int, shape: taq_shape, qkv_packed: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """taq_quantize_kv with the weight codes of to_k / to_v (int8 [2C, Cc], f32 [2C]) formed beforehand."""
+    dev = context.device
+    if qkv_packed is None:
+        qkv_packed = torch.empty(taq_kv_packed_bytes(shape), dtype=torch.uint8, device=dev)
+    if workspace is None:
+        workspace = torch.empty(taq_workspace_bytes(shape), dtype=torch.uint8, device=dev)
+    _check(load().taq_quantize_kv_w8(_ptr(context), _ptr(trigger_mask), _ptr(Wkv_code), _ptr(s_wkv), int(bits),
+                                     ctypes.byref(shape), _ptr(qkv_packed), _ptr(workspace), _stream(stream)),
+           "taq_quantize_kv_w8")
     return qkv_packed
 
 

@@ -93,6 +93,10 @@ def test_entry_points_reject_null_misaligned_and_inconsistent_arguments_without_
     assert lib.taq_quantize_kv(FAKE, FAKE, FAKE, FAKE, 4, sp, FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG  # bits != shape
     assert lib.taq_quantize_kv(ODD, FAKE, FAKE, FAKE, 8, sp, FAKE, FAKE, None) == T.TAQ_ERR_MISALIGNED
     assert lib.taq_quantize_kv(FAKE, FAKE, FAKE, FAKE, 8, None, FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    # taq_quantize_kv_w8
+    assert lib.taq_quantize_kv_w8(FAKE, FAKE, None, FAKE, 8, sp, FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    assert lib.taq_quantize_kv_w8(FAKE, FAKE, FAKE, FAKE, 4, sp, FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    assert lib.taq_quantize_kv_w8(FAKE, FAKE, ODD, FAKE, 8, sp, FAKE, FAKE, None) == T.TAQ_ERR_MISALIGNED
     # taq_cross_attn
     assert lib.taq_cross_attn(FAKE, FAKE, FAKE, FAKE, FAKE, None, sp, None, FAKE, None) == T.TAQ_ERR_INVALID_ARG
     assert lib.taq_cross_attn(FAKE, FAKE, FAKE, ODD, FAKE, None, sp, FAKE, FAKE, None) == T.TAQ_ERR_MISALIGNED

@@ -351,3 +351,22 @@ def test_log2_probability_grid_sharp_attention():
     L2 = synth.make_layer("plogs2", seed=78, B=1, N=90, C=96, H=4, Cc=64, T=40, bits_kv=8, trigger_positions=(4,))
     L2.Wk = (L2.Wk.astype(np.float32) * 6.0).astype(np.float16)
     check_layer(L2, "log2 grid sharp, kernel per stage", bits_prob=8, prob_grid="log2")
+
+
+def test_quantize_kv_with_cached_weight_codes_is_bit_identical():
+    """taq_quantize_kv_w8 (weight codes of to_k / to_v formed once per checkpoint) writes the same qkv_packed
+    bytes as taq_quantize_kv on the fp16 matrices, for int8, int4 and all-protected rows."""
+    for bits, C, H in ((8, 320, 8), (4, 96, 4), (16, 128, 2)):
+        L = synth.make_layer("kvw8", seed=60 + bits, B=2, N=8, C=C, H=H, Cc=96, T=77, bits_kv=bits,
+                             trigger_positions=(3, 40), trigger_scale=3.0)
+        s = G.shape_of(L)
+        ctx, mask, Wk, Wv = G.dev(L.context), G.dev(L.mask), G.dev(L.Wk), G.dev(L.Wv)
+        # the workspace is scratch and qkv_packed has alignment gaps: start both runs from zeroed buffers
+        p0 = torch.zeros(T.taq_kv_packed_bytes(s), dtype=torch.uint8, device=G.DEV)
+        p1 = torch.zeros_like(p0)
+        T.taq_quantize_kv(ctx, mask, Wk, Wv, bits, s, p0)
+        kc, ks = T.taq_quantize_weight(Wk)
+        vc, vs = T.taq_quantize_weight(Wv)
+        T.taq_quantize_kv_w8(ctx, mask, torch.cat([kc, vc]).contiguous(), torch.cat([ks, vs]).contiguous(), bits, s, p1)
+        torch.cuda.synchronize()
+        assert torch.equal(p0, p1), bits
