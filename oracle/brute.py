@@ -153,9 +153,23 @@ def taq_block_brute(context, mask, Wq, Wk, Wv, Wo, bias_o, hidden, H, bits_kv, b
                 A = [e / Z for e in E]
                 # ---- A^, Eq. (3)
                 Ah = []
+                row_amax = _f32(0)  # "rowmax" grid: largest float32 probability among the columns that get quantized
+                for t in range(T):
+                    if not trig[t] and _f32(A[t]) > row_amax:
+                        row_amax = _f32(A[t])
                 for t in range(T):
                     if trig[t]:
                         Ah.append(A[t])
+                    elif prob_grid == "rowmax":
+                        pmax = (1 << bits_prob) - 1
+                        if row_amax == _f32(0):
+                            pc, sc = 0, _f32(1)
+                        else:
+                            sc = _f32(row_amax / _f32(pmax))
+                            pc = int(np.rint(_f32(_f32(_f32(A[t]) * _f32(pmax)) / row_amax)))
+                            pc = min(pmax, max(0, pc))
+                        dump["p_code"][(b, n, h, t)] = pc
+                        Ah.append(pc * float(sc))
                     elif prob_grid == "log2":
                         # power-of-two grid: the exponent -log2 A, to float32, rounded half-even, clipped
                         last = (1 << bits_prob) - 1

@@ -112,6 +112,29 @@ def uq_log2(p, bits: int = 8):
     return np.clip(code, 0, last).astype(np.int32)
 
 
+def uq_rowmax(p, bits: int = 8, quantized=None):
+    """Unsigned b-bit quantizer of a row of probabilities with the row's own range (reading of the
+    "standard affine quantizer" of Section III-B with a dynamic per-row scale instead of the a-priori
+    range [0, 1]): over the entries of the last axis that are quantized at all (``quantized`` mask;
+    default: all),
+        amax = max p,  scale = amax / (2^b - 1),  code = clamp(rint((p * (2^b - 1)) / amax), 0, 2^b - 1),
+    in float32 with the multiply-then-divide order of ``symq``; a row whose quantized entries are all zero
+    gets scale 1 and codes 0. Returns (codes int32, scale float32 [...]); p^ = code * scale."""
+    if bits not in (4, 8):
+        raise ValueError("uq_rowmax: bits must be 4 or 8")
+    pmax = f32((1 << bits) - 1)
+    p32 = np.asarray(p, dtype=f32)
+    q = np.ones(p32.shape, dtype=bool) if quantized is None else np.broadcast_to(np.asarray(quantized, dtype=bool), p32.shape)
+    amax = np.where(q, p32, f32(0)).max(axis=-1).astype(f32)
+    zero = amax == 0
+    safe = np.where(zero, f32(1), amax).astype(f32)
+    scale = np.where(zero, f32(1), (amax / pmax).astype(f32)).astype(f32)
+    t = (p32 * pmax).astype(f32)
+    code = np.rint((t / safe[..., None]).astype(f32))
+    code = np.where(q, np.clip(code, 0, int(pmax)), 0).astype(np.int32)
+    return code, scale
+
+
 def pack_int4(codes):
     """Two's-complement nibbles, element 2j in the low nibble of byte j."""
     c = np.asarray(codes).astype(np.int32)
@@ -266,7 +289,8 @@ def cross_attn(hidden, kv: QuantKV, wq_code, s_wq, wo_code, s_wo, bias_o=None,
       Q~ = Q_a(Q)                             Eq. (2), third line; per (token, head): reading; 8 or 4 bits
       A  = softmax(Q~ K~^T / sqrt(d))         attention definition, per head
       A^ = M_A*A + (1-M_A)*Q_a(A)             Eq. (3); no renormalisation; 8 or 4 bits;
-                                              Q_a on the linear grid (uq) or, prob_grid="log2", on powers of two (uq_log2)
+                                              Q_a on the fixed linear grid (uq), on powers of two (prob_grid="log2",
+                                              uq_log2) or on the row's own range (prob_grid="rowmax", uq_rowmax)
       O  = A^ V~
       out = to_out(O) + bias                  (W8A8: reading), stored as fp16
     With bits_proj == 16 the two projections use ``Wq_f16`` / ``Wo_f16`` unquantized.
@@ -309,9 +333,13 @@ def cross_attn(hidden, kv: QuantKV, wq_code, s_wq, wo_code, s_wo, bias_o=None,
 
     # ---- A^ (Eq. 3): trigger columns keep A, the others are quantized
     M_A = kv.mask[:, None, None, :]  # [B,1,1,T] -> broadcast over N and heads
-    if prob_grid not in ("linear", "log2"):
-        raise ValueError("prob_grid must be 'linear' or 'log2'")
-    if bits_prob in (4, 8) and prob_grid == "log2":
+    if prob_grid not in ("linear", "log2", "rowmax"):
+        raise ValueError("prob_grid must be 'linear', 'log2' or 'rowmax'")
+    if bits_prob in (4, 8) and prob_grid == "rowmax":
+        p_code, s_P = uq_rowmax(A, bits_prob, quantized=~M_A)
+        A_q = p_code.astype(f64) * s_P.astype(f64)[..., None]
+        aux.update(p_code=p_code, s_P=s_P)
+    elif bits_prob in (4, 8) and prob_grid == "log2":
         p_code = uq_log2(A, bits_prob)
         A_q = np.exp2(-p_code.astype(f64))
         aux["p_code"] = p_code

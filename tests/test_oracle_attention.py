@@ -384,3 +384,65 @@ def test_log2_grid_keeps_trigger_columns_and_puts_the_rest_on_powers_of_two():
     assert r8.max() <= 2 ** 0.5 * (1 + 1e-6) and r8.min() >= 2 ** -0.5 * (1 - 1e-6)
     with pytest.raises(ValueError):
         O.taq_block(L, prob_grid="sqrt")
+
+
+# ---------------------------------------------------------------- per-row dynamic probability scale
+
+def test_rowmax_grid_is_exact_on_uniform_attention_of_any_length():
+    """Uniform attention A = 1/T with nothing protected: every entry equals the row maximum, takes the last code,
+    and code * scale reproduces float32(1/T), so the block matches unquantized probabilities to float32 rounding
+    (the fixed 1/255 grid is off by percents here)."""
+    B, N, H, d, T = 1, 4, 2, 4, 77
+    C = H * d
+    rng = np.random.Generator(np.random.PCG64(13))
+    mask = np.zeros((B, T), dtype=bool)
+    v_code = rng.integers(-127, 128, size=(B, T, C)).astype(np.int32)
+    s_V = rng.uniform(0.01, 0.02, size=(B, H, T)).astype(np.float32)
+    kv = O.QuantKV(B=B, T=T, C=C, H=H, bits_kv=8, mask=mask, k_code=np.zeros((B, T, C), dtype=np.int32), v_code=v_code,
+                   s_K=np.ones((B, H, T), dtype=np.float32), s_V=s_V, K16=np.zeros((B, T, C)), V16=np.zeros((B, T, C)))
+    hidden = rng.standard_normal((B, N, C)).astype(np.float16)
+    wq, swq = O.quantize_weight(np.eye(C, dtype=np.float16))
+    _, aux_fp = O.cross_attn(hidden, kv, wq, swq, wq, swq, bits_prob=16, return_aux=True)
+    for bits in (4, 8):
+        _, aux = O.cross_attn(hidden, kv, wq, swq, wq, swq, bits_prob=bits, prob_grid="rowmax", return_aux=True)
+        assert np.all(aux["p_code"] == (1 << bits) - 1)
+        assert np.max(np.abs(aux["O"] - aux_fp["O"])) <= 2e-7 * np.abs(aux_fp["O"]).max()
+    _, aux_lin = O.cross_attn(hidden, kv, wq, swq, wq, swq, bits_prob=8, return_aux=True)
+    assert np.max(np.abs(aux_lin["O"] - aux_fp["O"])) > 1e-3 * np.abs(aux_fp["O"]).max()
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("case", [
+    dict(seed=41, B=1, N=4, C=8, H=2, T=5, Cc=6, bits_kv=4, trig=(1,)),
+    dict(seed=42, B=2, N=3, C=4, H=1, T=9, Cc=5, bits_kv=8, trig=()),
+])
+def test_rowmax_grid_block_matches_scalar_brute_force(case, bits):
+    L = synth.make_layer("t", seed=case["seed"], B=case["B"], N=case["N"], C=case["C"], H=case["H"], T=case["T"],
+                         Cc=case["Cc"], bits_kv=case["bits_kv"], trigger_positions=case["trig"], trigger_scale=3.0, bias=True)
+    out, aux = O.taq_block(L, bits_prob=bits, prob_grid="rowmax", return_aux=True)
+    ref, dump = brute.taq_block_brute(L.context, L.mask, L.Wq, L.Wk, L.Wv, L.Wo, L.bias_o, L.hidden, L.H, L.bits_kv,
+                                      bits_prob=bits, prob_grid="rowmax")
+    assert len(dump["p_code"]) == L.B * L.N * L.H * (L.T - len(case["trig"]))
+    for (b, n, h, t), v in dump["p_code"].items():
+        assert aux["p_code"][b, n, h, t] == v
+    for (b, n, c), v in dump["o_code"].items():
+        assert aux["o_code"][b, n, c] == v
+    ref = np.array(ref)
+    assert np.max(np.abs(out.astype(np.float64) - ref)) <= 1e-3 * max(1.0, np.abs(ref).max())
+
+
+def test_rowmax_grid_keeps_trigger_columns_and_is_finer_than_the_fixed_grid():
+    L = small_layer(N=64)
+    ref = O.taq_block(L, bits_prob=16, store_f16=False)
+    _, aux = O.taq_block(L, bits_prob=4, prob_grid="rowmax", return_aux=True)
+    assert np.array_equal(aux["A_hat"][..., [2, 3]], aux["A"][..., [2, 3]])       # Eq. (3): M_A columns keep A
+    rest = [t for t in range(L.T) if t not in (2, 3)]
+    # the range comes from the quantized columns only, and the largest of them takes the last code
+    assert np.all(aux["p_code"][..., rest].max(axis=-1) == 15)
+    assert np.array_equal(aux["s_P"], (aux["A"][..., rest].astype(np.float32).max(axis=-1) / np.float32(15)).astype(np.float32))
+    assert np.all(np.abs(aux["A_hat"][..., rest] - aux["A"][..., rest]) <= aux["s_P"][..., None] * (0.5 + 1e-5))
+    e = {}
+    for grid in ("linear", "rowmax"):
+        out = O.taq_block(L, bits_prob=4, prob_grid=grid, store_f16=False)
+        e[grid] = np.linalg.norm(out - ref) / np.linalg.norm(ref)
+    assert e["rowmax"] < e["linear"]

@@ -180,3 +180,40 @@ def test_uq_log2_known_values_bound_and_fixed_points(bits):
     assert np.array_equal(O.uq_log2(edge * (1 - 1e-5), bits), kk + 1)
     with pytest.raises(ValueError):
         O.uq_log2(p, 16)
+
+
+def test_uq_rowmax_known_values_bound_and_mask():
+    # 4 bits, amax = 0.5: 15, 0.25*15/0.5 = 7.5 -> 8 (even), 0.125 -> 3.75 -> 4, 0.05 -> 1.5 -> 2 (even)
+    code, scale = O.uq_rowmax(np.array([[0.5, 0.25, 0.125, 0.05, 0.0]]), 4)
+    assert list(code[0]) == [15, 8, 4, 2, 0] and scale[0] == np.float32(0.5) / np.float32(15)
+    # the largest quantized entry always takes the last code; error at most half a step of the row's own scale
+    rng = np.random.Generator(np.random.PCG64(4))
+    p = rng.dirichlet(np.ones(77) * 0.3, size=200)
+    for bits in (4, 8):
+        last = (1 << bits) - 1
+        c, sc = O.uq_rowmax(p, bits)
+        assert np.all(c.max(axis=1) == last) and c.min() >= 0
+        assert np.all(np.abs(c * sc[:, None].astype(np.float64) - p) <= sc[:, None] * (0.5 + 1e-5))
+        # never coarser than the fixed 1/(2^b-1) grid, whose step the row scale cannot exceed
+        assert np.all(sc <= np.float32(1.0) / np.float32(last) * (1 + 1e-6))
+        # scaling a row by a power of two scales its scale and leaves the codes alone
+        c2, sc2 = O.uq_rowmax(p * 0.25, bits)
+        assert np.array_equal(c2, c) and np.array_equal(sc2, sc * np.float32(0.25))
+    # entries outside the mask neither set the range nor get codes
+    m = np.ones(77, dtype=bool)
+    m[[0, 5]] = False
+    big = p.copy()
+    big[:, 0] = 0.9
+    c3, sc3 = O.uq_rowmax(big, 8, quantized=m)
+    assert np.all(c3[:, [0, 5]] == 0)
+    assert np.array_equal(sc3, (big[:, m].astype(np.float32).max(axis=1) / np.float32(255)).astype(np.float32))
+    # a row of zeros: scale 1, codes 0
+    cz, sz = O.uq_rowmax(np.zeros((2, 5)), 8)
+    assert np.all(cz == 0) and np.all(sz == 1)
+    # exact rational rounding on fp16-valued rows (products and quotients exact enough to decide every code)
+    q = (rng.uniform(0, 1, size=(6, 40))).astype(np.float16)
+    cq, _ = O.uq_rowmax(q.astype(np.float32), 8)
+    for r in range(6):
+        fr = [Fraction(float(v)) for v in q[r]]
+        amax = max(fr)
+        assert list(cq[r]) == [brute.round_half_even(v * 255 / amax) for v in fr]
