@@ -67,10 +67,13 @@ typedef struct taq_shape {
                                 TAQ_PROB_LINEAR (0) : code = rint(pmax*A), A^ = code/pmax
                                 TAQ_PROB_LOG2   (1) : code = clip(rint(-log2 A), 0, 2^bits_prob - 1),
                                                       A^ = 2^-code (the "Logarithmic" quantizer of the
-                                                      trigger-separation ablation, Section IV)          */
+                                                      trigger-separation ablation, Section IV)
+                                TAQ_PROB_ROWMAX (2) : the affine quantizer with the row's own range:
+                                                      amax = largest unprotected A of the (token, head) row,
+                                                      code = rint(pmax*A/amax), A^ = code*amax/pmax     */
 } taq_shape;
 
-enum { TAQ_PROB_LINEAR = 0, TAQ_PROB_LOG2 = 1 };
+enum { TAQ_PROB_LINEAR = 0, TAQ_PROB_LOG2 = 1, TAQ_PROB_ROWMAX = 2 };
 
 /* Optional taps for tests and profiling (all pointers device memory or NULL). */
 typedef struct taq_debug {

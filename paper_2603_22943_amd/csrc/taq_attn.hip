@@ -71,6 +71,7 @@ struct CoreArgs {
     float pmax;             // linear grid: 255 or 15 (Eq. 3); log2 grid: 2^15, the factor that puts 2^-code into fp16's range
     float plast;            // log2 grid: the last code, 255 or 15
     int plog;               // 1: log2 grid
+    int prow;               // 1: linear grid over the row's own range (largest unprotected probability)
 };
 
 __device__ __forceinline__ int load_code(const uint8_t* codes, size_t row, int C, int c, int bits) {
@@ -273,7 +274,7 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, fmaxf(S[tile][i], Sf[tile][i]));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    float Z = 0.f;
+    float Z = 0.f, eu = 0.f;
 #pragma unroll
     for (int tile = 0; tile < 3; ++tile)
 #pragma unroll
@@ -282,11 +283,19 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
             const float ex = __builtin_amdgcn_exp2f(arg);
             Sf[tile][i] = __builtin_amdgcn_exp2f(Sf[tile][i] - mx);
             Z += ex + Sf[tile][i];
+            eu = fmaxf(eu, ex);
             S[tile][i] = a.plog ? arg : ex;  // the log2 grid rounds the exponent itself
         }
     Z += __shfl_xor(Z, 32);
+    eu = fmaxf(eu, __shfl_xor(eu, 32));
     const float inv = 1.0f / Z;
     const float lz = __builtin_amdgcn_logf(Z);  // log2 Z >= 0 (the largest term is 1)
+    // Row-range grid: codes = rint(pmax * E / range) with range = largest unprotected E, A^ = code * (range / Z) / pmax.
+    // Unprotected columns that together weigh less than 2^-40 of the row (or none at all) are dropped.
+    const bool ranged = a.prow && eu > Z * 9.094947e-13f;
+    const float invc = ranged ? 1.0f / eu : inv;    // code = rint((E * invc) * pmax)
+    const float rz = ranged ? Z / eu : 1.f;         // protected partial sums into the units of the coded ones
+    const float fz = ranged ? eu / Z : 1.f;         // and the result back
 
     // ---------------- O^T = V~^T A^^T
     floatx16_t oacc[DT];
@@ -321,7 +330,7 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
 #pragma unroll
         for (int jt = 0; jt < DT; ++jt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[jt][i] *= vpre;
+            for (int i = 0; i < 16; ++i) oacc[jt][i] *= vpre * rz;
     }
 #pragma unroll
     for (int tile = 0; tile < 3; ++tile) {
@@ -337,7 +346,7 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
                         const float c = fminf(fmaxf(__builtin_rintf(S[tile][8 * blk + e] - lz), -a.plast), 0.f);
                         p[e] = (_Float16)ldexpf(1.0f, 15 + (int)c);
                     } else {
-                        p[e] = (_Float16)__builtin_rintf((S[tile][8 * blk + e] * inv) * a.pmax);
+                        p[e] = (_Float16)__builtin_rintf((S[tile][8 * blk + e] * invc) * a.pmax);
                     }
                 }
 #pragma unroll
@@ -354,7 +363,7 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
     // ---------------- store O (float32): lane holds channels 32*jt + 8*g + 4*half + 0..3
     if (nvalid) {
         float* orow = a.o_f + tok * C + h * d;
-        const float k = ldexpf(1.0f, -kexp) / a.pmax;
+        const float k = (ldexpf(1.0f, -kexp) / a.pmax) * fz;
 #pragma unroll
         for (int jt = 0; jt < DT; ++jt)
 #pragma unroll
@@ -410,6 +419,7 @@ hipError_t launch_attn_core(const int8_t* q_code, const float* s_q, const uint8_
     a.pmax = s.prob_grid == TAQ_PROB_LOG2 ? 32768.f : s.bits_prob == 4 ? 15.f : 255.f;
     a.plast = s.bits_prob == 4 ? 15.f : 255.f;
     a.plog = s.prob_grid == TAQ_PROB_LOG2;
+    a.prow = s.prob_grid == TAQ_PROB_ROWMAX;
     switch ((d + 31) / 32) {
         case 1: return launch_core_dt<1>(a, s.B, st);
         case 2: return launch_core_dt<2>(a, s.B, st);

@@ -265,13 +265,14 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // NG > 1 (layers too wide for one workgroup's LDS): the workgroup owns one head group (NH of the NH*NG
 // heads), takes the per-token codes of `hidden` from the workspace, and stops after A^ V~, which it writes to
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
-template <int D, int NH, int NTT, int NG, bool LOGP>
+template <int D, int NH, int NTT, int NG, int PG>
 __global__ __launch_bounds__(64 * NH * (2 / NTT) * (NG > 1 ? 4 / NH : 1))
 __attribute__((amdgpu_waves_per_eu(1, (NH * (2 / NTT) * (NG > 1 ? 4 / NH : 1) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
     using F = FusedCfg<D, NH, NTT, NG>;
     constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
     constexpr int SUB = F::SUB, TPS = F::TPS;
+    constexpr bool LOGP = PG == TAQ_PROB_LOG2, ROWMAX = PG == TAQ_PROB_ROWMAX;  // grid of the probabilities, Eq. (3)
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, hl = (tid >> 6) % NH, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
@@ -485,8 +486,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 
     // protected (trigger) rows of this head, first tile of 16: fp16 K rows and transposed V rows straight from
-    // global memory into MFMA operand registers (slots past the protected tokens hold zeros; channels past the
-    // head meet zero Q~ codes / are discarded, so no masking is needed)
+    // global memory into MFMA operand registers (slots past the protected tokens hold zeros; K channels past the
+    // head are not read: they would belong to the next head, or lie past the last row of the last head, and a
+    // non-finite bit pattern there would survive the multiplication with a zero Q~ code)
     uint2 k16r[FS][2], v16r[TPS];
     auto load_protected = [&]() {
         if (nfp > 0) {
@@ -496,7 +498,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             for (int s = 0; s < FS; ++s)
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj)
-                    k16r[s][jj] = (2 * s + jj < TPH) ? *reinterpret_cast<const uint2*>(kr + 16 * (2 * s + jj)) : make_uint2(0, 0);
+                    k16r[s][jj] = (2 * s + jj < TPH && 16 * (2 * s + jj) + 4 * q < D)
+                                      ? *reinterpret_cast<const uint2*>(kr + 16 * (2 * s + jj)) : make_uint2(0, 0);
 #pragma unroll
             for (int k = 0; k < TPS; ++k) {
                 const int jt = sub + SUB * k;  // this wavefront's k-th channel tile of A^ V~ (may lie past the head: clamped)
@@ -720,7 +723,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                             const int j = 2 * s + jj;
                             uint2 w = make_uint2(0, 0);
                             if (ft == 0) w = k16r[s][jj];
-                            else if (j < TPH) w = *reinterpret_cast<const uint2*>(kr + 16 * j);
+                            else if (j < TPH && 16 * j + 4 * q < D) w = *reinterpret_cast<const uint2*>(kr + 16 * j);
                             const half4_t hv = *reinterpret_cast<const half4_t*>(&w);
                             ka[4 * jj + 0] = hv[0];
                             ka[4 * jj + 1] = hv[1];
@@ -742,8 +745,10 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 
     // ================= softmax over the text tokens; Eq. (3); weights of O^T = V~^T A^^T
-    float kq[NTT];  // pmax / Z per image token
-    float lz[NTT];  // log2 Z (log2 grid only)
+    float kq[NTT];   // code = rint(E * kq): pmax / Z per image token (row-range grid: pmax / largest unprotected E)
+    float kqp[NTT];  // protected columns: weight = E * kqp = pmax * A
+    float lz[NTT];   // log2 Z (log2 grid only)
+    float rz[NTT], fz[NTT];  // row-range grid only: Z / range and range / Z, which move between the two units
 #pragma unroll
     for (int nt = 0; nt < NTT; ++nt) {
         float mx = TAQ_NEG_INF;
@@ -755,7 +760,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             if (ft < nfp) mx = fmaxf(mx, fmaxf(fmaxf(Sf[nt][ft][0], Sf[nt][ft][1]), fmaxf(Sf[nt][ft][2], Sf[nt][ft][3])));
         mx = quad_allmax(mx);
         const float sc = sq2[nt], off = -mx * sc;
-        float Z = 0.f;
+        float Z = 0.f, eu = 0.f;
 #pragma unroll
         for (int tt = 0; tt < 6; ++tt)
             if (tt < dm.nt16) {
@@ -764,6 +769,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                     const float arg = __builtin_fmaf(S[nt][tt][i], sc, off);
                     const float ex = __builtin_amdgcn_exp2f(arg);
                     Z += ex;
+                    if (ROWMAX) eu = fmaxf(eu, ex);  // the row's range: its largest unprotected probability (times Z)
                     S[nt][tt][i] = LOGP ? arg : ex;  // the log2 grid rounds the exponent itself
                 }
             }
@@ -777,8 +783,22 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 }
             }
         Z = quad_allsum(Z);
-        kq[nt] = dm.pmax * __builtin_amdgcn_rcpf(Z);
+        kqp[nt] = dm.pmax * __builtin_amdgcn_rcpf(Z);
+        kq[nt] = kqp[nt];
         lz[nt] = LOGP ? __builtin_amdgcn_logf(Z) : 0.f;  // log2 Z >= 0: the largest term of Z is 1
+        rz[nt] = 1.f;
+        fz[nt] = 1.f;
+        if constexpr (ROWMAX) {
+            // codes = rint(pmax * E / range), A^ = code * (range / Z) / pmax. Unprotected columns that together weigh
+            // less than 2^-40 of the row (or none at all) are dropped: their codes would scale a vanishing range.
+            eu = quad_allmax(eu);
+            if (eu > Z * 9.094947e-13f) {
+                const float re = __builtin_amdgcn_rcpf(eu);
+                kq[nt] = dm.pmax * re;
+                rz[nt] = Z * re;
+                fz[nt] = eu * __builtin_amdgcn_rcpf(Z);
+            }
+        }
     }
 
     // oacc[nt][k]: channel tile jt = sub + SUB*k of this head (NG == 1: SUB = 1, every tile; head-group variant: every
@@ -799,9 +819,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         // high part = fp16(Sf*kq), low part = fp16(Sf*kq - high), each one mixed-precision FMA
-                        const _Float16 xh = (_Float16)__builtin_fmaf(Sf[nt][ft][i], kq[nt], 0.0f);
+                        const _Float16 xh = (_Float16)__builtin_fmaf(Sf[nt][ft][i], kqp[nt], 0.0f);
                         phi[nt][i] = xh;
-                        plo[nt][i] = (_Float16)__builtin_fmaf(Sf[nt][ft][i], kq[nt], -(float)xh);
+                        plo[nt][i] = (_Float16)__builtin_fmaf(Sf[nt][ft][i], kqp[nt], -(float)xh);
                     }
 #pragma unroll
                 for (int k = 0; k < TPS; ++k) {
@@ -825,7 +845,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
             for (int k = 0; k < TPS; ++k)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) oacc[nt][k][i] *= vpre;
+                for (int i = 0; i < 4; ++i) oacc[nt][k][i] *= ROWMAX ? vpre * rz[nt] : vpre;
     }
     // unprotected columns: weight = code * (s_V * 2^kexp), split into fp16 high + low parts; V codes exact in fp16
     {
@@ -903,7 +923,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             const bool valid = jt < TPH && ((16 * jt + 16 <= D) || 16 * jt + 4 * q < D);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                oacc[nt][k][i] = valid ? oacc[nt][k][i] * osc : 0.f;
+                oacc[nt][k][i] = valid ? oacc[nt][k][i] * (ROWMAX ? osc * fz[nt] : osc) : 0.f;
                 omx = fmaxf(omx, fabsf(oacc[nt][k][i]));
             }
             if (nvalid[nt] && valid) {
@@ -1086,7 +1106,7 @@ static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hi
     return hipGetLastError();
 }
 
-template <int D, int NH, int NTT, int NG, bool LOGP>
+template <int D, int NH, int NTT, int NG, int PG>
 static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     using F = FusedCfg<D, NH, NTT, NG>;
     static bool attr_set = false;
@@ -1095,19 +1115,21 @@ static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, 
                                        2 * NH * F::TPH * 1024;                                          // = mid_lds_bytes
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, LOGP>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles = (dm.N + 31) / 32;
-    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, LOGP>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
+    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 
 template <int D, int NH, int NTT, int NG>
-static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, bool logp, hipStream_t st) {
-    return logp ? launch_fused_grid<D, NH, NTT, NG, true>(tab, dm, st) : launch_fused_grid<D, NH, NTT, NG, false>(tab, dm, st);
+static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, int grid, hipStream_t st) {
+    if (grid == TAQ_PROB_LOG2) return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_LOG2>(tab, dm, st);
+    if (grid == TAQ_PROB_ROWMAX) return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_ROWMAX>(tab, dm, st);
+    return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_LINEAR>(tab, dm, st);
 }
 
 hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, const taq_debug* dbg, hipStream_t st) {
@@ -1137,9 +1159,9 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.ws_omax = nullptr;
     dm.omax_n = 0;
     dm.group_fastest = 0;
-    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8, TAQ_NTT_40, 1>(tab, dm, logp, st);
-    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8, 2, 1>(tab, dm, logp, st);
-    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10, 2, 1>(tab, dm, logp, st);
+    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8, TAQ_NTT_40, 1>(tab, dm, s.prob_grid, st);
+    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8, 2, 1>(tab, dm, s.prob_grid, st);
+    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10, 2, 1>(tab, dm, s.prob_grid, st);
     return hipErrorInvalidValue;
 }
 
@@ -1177,8 +1199,8 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, float* o_f, 
     dm.ws_omax = o_max;
     dm.omax_n = mid_omax_n(s);
     dm.group_fastest = 0;  // (measured: no difference between the two orders at these sizes)
-    if (d == 160 && s.H == 8) return launch_fused_cfg<160, 1, 1, 8>(tab, dm, logp, st);
-    if (d == 64 && s.H == 20) return launch_fused_cfg<64, 2, 1, 10>(tab, dm, logp, st);
+    if (d == 160 && s.H == 8) return launch_fused_cfg<160, 1, 1, 8>(tab, dm, s.prob_grid, st);
+    if (d == 64 && s.H == 20) return launch_fused_cfg<64, 2, 1, 10>(tab, dm, s.prob_grid, st);
     return hipErrorInvalidValue;
 }
 

@@ -25,6 +25,7 @@ TAQ_ERR_HIP = -5
 
 TAQ_PROB_LINEAR = 0
 TAQ_PROB_LOG2 = 1
+TAQ_PROB_ROWMAX = 2
 
 TAQ_STAGE_HIDDEN_QUANT = 1
 TAQ_STAGE_TO_Q = 2

@@ -14,7 +14,8 @@ DEV = "cuda:0"
 def shape_of(L, bits_kv=None, N=None, w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear"):
     return T.make_shape(B=L.B, N=L.N if N is None else N, C=L.C, H=L.H, T=L.T, Cc=L.Cc,
                         bits_kv=L.bits_kv if bits_kv is None else bits_kv, bits_q=bits_q, bits_prob=bits_prob,
-                        w_layout=w_layout, prob_grid=T.TAQ_PROB_LOG2 if prob_grid == "log2" else T.TAQ_PROB_LINEAR)
+                        w_layout=w_layout, prob_grid={"linear": T.TAQ_PROB_LINEAR, "log2": T.TAQ_PROB_LOG2,
+                                                       "rowmax": T.TAQ_PROB_ROWMAX}[prob_grid])
 
 
 def dev(a, dtype=None):
@@ -39,7 +40,11 @@ class GpuRun:
             self.wq_code = T.taq_pack_weight(self.wq_plain, s)
             self.wo_code = T.taq_pack_weight(self.wo_plain, s)
         self.scales = torch.cat([self.s_wq, self.s_wo, dev(L.bias_o)]).contiguous()
-        self.packed = T.taq_quantize_kv(ctx, mask, Wk, Wv, L.bits_kv, s)
+        # qkv_packed and the workspace start as 0xFF bytes (NaN as fp16 / float32, -1 as int8): a kernel that reads a
+        # byte nobody wrote (alignment gaps, rows past the end of a section) shows up as NaN instead of passing by luck
+        self.packed = torch.full((T.taq_kv_packed_bytes(s),), 0xFF, dtype=torch.uint8, device=DEV)
+        self.ws = torch.full((T.taq_workspace_bytes(s),), 0xFF, dtype=torch.uint8, device=DEV)
+        T.taq_quantize_kv(ctx, mask, Wk, Wv, L.bits_kv, s, self.packed, self.ws)
         self.kv = {k: v.cpu().numpy() for k, v in T.taq_unpack_kv(self.packed, s).items()}
         self.mask_d = mask
         self.hidden_d = dev(L.hidden if hidden is None else hidden)
@@ -48,13 +53,15 @@ class GpuRun:
                                       prob_grid=prob_grid)
         if taps:
             dbg, t = T.make_debug(s, DEV)
+            self.ws.fill_(0xFF)
             self.out_d = T.taq_cross_attn(self.hidden_d, self.packed, self.wq_code, self.wo_code, self.scales,
-                                          mask, s, debug=dbg)
+                                          mask, s, workspace=self.ws, debug=dbg)
             torch.cuda.synchronize()
             self.taps = {k: v.cpu().numpy() for k, v in t.items()}
         else:
+            self.ws.fill_(0xFF)
             self.out_d = T.taq_cross_attn(self.hidden_d, self.packed, self.wq_code, self.wo_code, self.scales,
-                                          mask, s)
+                                          mask, s, workspace=self.ws)
             torch.cuda.synchronize()
             self.taps = {}
         self.out = self.out_d.cpu().numpy()

@@ -63,7 +63,7 @@ def test_size_queries_are_host_only_and_consistent():
     (dict(bits_prob=5), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(bits_prob=16), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(bits_q=16), T.TAQ_ERR_UNSUPPORTED_BITS),
-    (dict(prob_grid=2), T.TAQ_ERR_INVALID_ARG),
+    (dict(prob_grid=3), T.TAQ_ERR_INVALID_ARG),
     (dict(bits_proj=16), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(C=324), T.TAQ_ERR_BAD_SHAPE),  # C % H != 0
     (dict(C=96, H=8), T.TAQ_ERR_BAD_SHAPE),  # d = 12, not a multiple of 8

@@ -69,6 +69,8 @@ def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linea
     # ---- A^ V~ and its codes
     O_ref = aux["O"]
     scale_o = max(np.abs(O_ref).max(), 1e-30)
+    bad = ~np.isfinite(g.taps["O"])
+    assert not bad.any(), ("non-finite A^ V~", int(bad.sum()), [np.unique(a)[:12].tolist() for a in np.where(bad)])
     dO = np.abs(g.taps["O"].astype(np.float64) - O_ref)
     # float32 vs float64 arithmetic keeps O within ~1e-6 of its scale; a protected K/V row that differs from the
     # oracle's by its allowed single fp16 step (5e-4 relative) shifts the scores of a head or a whole channel
@@ -90,6 +92,12 @@ def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linea
         tol = 1e-5 * (1 + x) + (0.0 if rows_equal else 0.02)
         near = (np.abs(x - np.floor(x) - 0.5) <= tol) & (np.floor(x) < last) & unprot
         step = np.where(near, np.exp2(-(np.floor(x) + 1)), 0.0)      # 2^-k - 2^-(k+1)
+    elif prob_grid == "rowmax":
+        s_P = aux["s_P"].astype(np.float64)[..., None]               # the row's own step, amax / pmax
+        x = aux["A"] / s_P
+        tie_rel = 1e-5 if rows_equal else 2e-3
+        near = (np.abs(x - np.floor(x) - 0.5) <= tie_rel * x + 1e-6) & unprot
+        step = near * s_P
     else:
         x = aux["A"] * pmax
         tie_rel = 1e-5 if rows_equal else 2e-3
@@ -370,3 +378,42 @@ def test_quantize_kv_with_cached_weight_codes_is_bit_identical():
         T.taq_quantize_kv_w8(ctx, mask, torch.cat([kc, vc]).contiguous(), torch.cat([ks, vs]).contiguous(), bits, s, p1)
         torch.cuda.synchronize()
         assert torch.equal(p0, p1), bits
+
+
+# ---------------------------------------------------------------- probabilities on the row's own range
+
+@pytest.mark.parametrize("bits_prob", [8, 4])
+@pytest.mark.parametrize("C,H,N,T_,bits_kv,bits_q", [
+    (320, 8, 200, 77, 8, 8),    # single kernel, d = 40
+    (320, 8, 77, 77, 4, 4),     # ... 4-bit K~/V~ rows and 4-bit Q~
+    (640, 8, 45, 77, 8, 8),     # single kernel, d = 80
+    (640, 10, 70, 50, 8, 8),    # single kernel, d = 64
+    (1280, 8, 40, 77, 8, 8),    # head groups, d = 160
+    (1280, 20, 33, 50, 4, 4),   # head groups, d = 64
+    (96, 4, 130, 33, 8, 8),     # kernel per stage, d = 24
+    (128, 2, 65, 96, 4, 4),     # kernel per stage, d = 64, the largest T
+])
+def test_rowmax_probability_grid(C, H, N, T_, bits_kv, bits_q, bits_prob):
+    L = synth.make_layer("prow", seed=C + H + N + 5 * bits_prob, B=2, N=N, C=C, H=H, Cc=64, T=T_,
+                         bits_kv=bits_kv, trigger_positions=(2, T_ - 1), trigger_scale=3.0, bias=True,
+                         outlier_frac=0.01)
+    check_layer(L, f"rowmax grid C={C} H={H} N={N} T={T_}", bits_q=bits_q, bits_prob=bits_prob, prob_grid="rowmax")
+
+
+@pytest.mark.parametrize("trig", [(), "all"])
+def test_rowmax_probability_grid_mask_extremes(trig):
+    pos = tuple(range(77)) if trig == "all" else trig
+    L = synth.make_layer("prowm", seed=610 + len(pos), B=1, N=100, C=320, H=8, Cc=64, T=77, bits_kv=8,
+                         trigger_positions=pos, trigger_scale=3.0)
+    check_layer(L, f"rowmax grid mask ntrig={len(pos)}", bits_prob=4, prob_grid="rowmax")
+
+
+def test_rowmax_probability_grid_when_a_trigger_takes_the_whole_row():
+    # a strongly scaled trigger row makes the protected column dominate: the unprotected range becomes tiny
+    # (down to nothing in float32), which the kernels must survive without overflow or NaN
+    for scale, C, H in ((6.0, 320, 8), (40.0, 320, 8), (40.0, 96, 4)):
+        L = synth.make_layer("prowt", seed=88, B=1, N=120, C=C, H=H, Cc=64, T=40, bits_kv=8,
+                             trigger_positions=(4,), trigger_scale=scale)
+        L.Wk = (L.Wk.astype(np.float32) * 4.0).astype(np.float16)
+        L.Wv = (L.Wv.astype(np.float32) / scale).astype(np.float16)  # keeps the outputs (~ the trigger's V row) of order 1
+        check_layer(L, f"rowmax grid dominant trigger x{scale} C={C}", bits_prob=8, prob_grid="rowmax")
