@@ -129,7 +129,7 @@ def uq_rowmax(p, bits: int = 8, quantized=None):
     zero = amax == 0
     safe = np.where(zero, f32(1), amax).astype(f32)
     scale = np.where(zero, f32(1), (amax / pmax).astype(f32)).astype(f32)
-    t = (p32 * pmax).astype(f32)
+    t = (np.where(q, p32, f32(0)) * pmax).astype(f32)      # entries outside the mask get no code
     code = np.rint((t / safe[..., None]).astype(f32))
     code = np.where(q, np.clip(code, 0, int(pmax)), 0).astype(np.int32)
     return code, scale

@@ -94,7 +94,8 @@ def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linea
         step = np.where(near, np.exp2(-(np.floor(x) + 1)), 0.0)      # 2^-k - 2^-(k+1)
     elif prob_grid == "rowmax":
         s_P = aux["s_P"].astype(np.float64)[..., None]               # the row's own step, amax / pmax
-        x = aux["A"] / s_P
+        with np.errstate(divide="ignore", invalid="ignore"):         # a range that underflowed to 0: codes weigh nothing
+            x = np.where(s_P > 0, aux["A"] / s_P, 0.0)
         tie_rel = 1e-5 if rows_equal else 2e-3
         near = (np.abs(x - np.floor(x) - 0.5) <= tie_rel * x + 1e-6) & unprot
         step = near * s_P
