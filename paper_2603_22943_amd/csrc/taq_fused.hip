@@ -181,9 +181,9 @@ struct FusedDims {
     const float* ws_so;      // f32 [B*N]     ... and their scales
 };
 
-template <int D, int NH, int NTT, int NG>
+template <int D, int NH, int NTT, int NG, int TOK = 32>
 struct FusedCfg {
-    static constexpr int G = 2 / NTT;             // wavefronts per head (token groups of 16*NTT tokens)
+    static constexpr int G = TOK / (16 * NTT);    // wavefronts per head (token groups of 16*NTT tokens)
     static constexpr int H = NH * NG;             // heads of the layer; a workgroup owns NH of them
     static constexpr int C = D * H;
     static constexpr int TPH = (D + 15) / 16;     // 16-row tiles per head
@@ -259,17 +259,19 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
     b = *reinterpret_cast<const half2_t*>(&hi) - off;
 }
 
-// 32 image tokens per workgroup. NTT = 2: one wavefront per head carrying two column tiles of 16 tokens
+// TOK = 32 image tokens per workgroup. NTT = 2: one wavefront per head carrying two column tiles of 16 tokens
 // (A operands shared by both tiles). NTT = 1: two wavefronts per head, one tile each (16 wavefronts per CU
-// instead of 8: more latency hiding for twice the A-operand traffic).
+// instead of 8: more latency hiding for twice the A-operand traffic). TOK = 16 (with NTT = 1): one wavefront per
+// head and half the tokens, for layers whose 32-token tiles would leave most compute units without a workgroup.
 // NG > 1 (layers too wide for one workgroup's LDS): the workgroup owns one head group (NH of the NH*NG
 // heads), takes the per-token codes of `hidden` from the workspace, and stops after A^ V~, which it writes to
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
-template <int D, int NH, int NTT, int NG, int PG>
-__global__ __launch_bounds__(64 * NH * (2 / NTT) * (NG > 1 ? 4 / NH : 1))
-__attribute__((amdgpu_waves_per_eu(1, (NH * (2 / NTT) * (NG > 1 ? 4 / NH : 1) + 3) / 4)))
+template <int D, int NH, int NTT, int NG, int PG, int TOK = 32>
+__global__ __launch_bounds__(64 * NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1))
+__attribute__((amdgpu_waves_per_eu(1, (NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
-    using F = FusedCfg<D, NH, NTT, NG>;
+    using F = FusedCfg<D, NH, NTT, NG, TOK>;
+    static_assert(TOK == 32 || (TOK == 16 && NTT == 1 && NG == 1), "a workgroup owns 32 image tokens, or 16 with one tile per wavefront");
     constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
     constexpr int SUB = F::SUB, TPS = F::TPS;
     constexpr bool LOGP = PG == TAQ_PROB_LOG2, ROWMAX = PG == TAQ_PROB_ROWMAX;  // grid of the probabilities, Eq. (3)
@@ -290,7 +292,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     const int ri = rb / dm.B, b = rb % dm.B;
     const FusedReq rq = tab.req[ri];
     const int N = dm.N, T = dm.T;
-    const int n0 = tile * 32;
+    const int n0 = tile * TOK;
 
     // ---- LDS carve-up
     unsigned char* img = smem;                                  // K~/V~ image blocks of this workgroup's heads
@@ -319,11 +321,11 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     if constexpr (NG == 1) {
         // ---- phase 0: issue every global read up front, oldest first in the order of use (loads return in
         // order): hidden tile, weight scales, this head's to_q weight slice, the K~/V~ image
-        const int tok0 = tid >> 4, part0 = tid & 15;  // 16 threads per token, 4 channels per load (first 512 threads)
+        const int tok0 = tid >> 4, part0 = tid & 15;  // 16 threads per token, 4 channels per load (first 16*TOK threads)
         const int nq0 = n0 + tok0;
         const size_t row0 = (size_t)b * N + (nq0 < N ? nq0 : N - 1);
         uint2 xin[KC];
-        if (tid < 512) {
+        if (tid < 16 * TOK) {
             const uint2* xr = reinterpret_cast<const uint2*>(rq.hidden + row0 * C);
     #pragma unroll
             for (int it = 0; it < KC; ++it) xin[it] = xr[it * 16 + part0];
@@ -338,7 +340,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         // ---- per-token int8 codes of the hidden tile
         float x[KC][4];
         float amax = 0.f;
-        if (tid < 512) {
+        if (tid < 16 * TOK) {
     #pragma unroll
             for (int it = 0; it < KC; ++it) {
                 const __half2* hh = reinterpret_cast<const __half2*>(&xin[it]);
@@ -361,21 +363,21 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         const float sc0 = zero0 ? 1.f : amax / 127.f;
         const float safe0 = zero0 ? 1.f : amax;
         const float cq0 = 127.f * __builtin_amdgcn_rcpf(safe0);
-        if (tid < 512 && part0 == 0) s_h[tok0] = sc0;
+        if (tid < 16 * TOK && part0 == 0) s_h[tok0] = sc0;
     #pragma unroll
         for (int it = 0; it < KC; ++it) {
             if (F::PREFETCH_W) {
     #pragma unroll
                 for (int j = 0; j < TPH; ++j) wreg[j][it] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + wstep * it);
             }
-            if (tid < 512) {
+            if (tid < 16 * TOK) {
                 const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq0, safe0);
                 *reinterpret_cast<unsigned*>(tileq + tok0 * F::TILE_RS + (it * 16 + part0) * 4) = pk;
                 if (dm.dbg.h_code && nq0 < N) *reinterpret_cast<unsigned*>(dm.dbg.h_code + row0 * C + (it * 16 + part0) * 4) = pk;
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (tid < 512 && dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc0;
+        if (tid < 16 * TOK && dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc0;
         // ---- weight scales and the K~/V~ image into LDS
     #pragma unroll
         for (int k = 0; k < SCV; ++k) {
@@ -1106,30 +1108,30 @@ static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hi
     return hipGetLastError();
 }
 
-template <int D, int NH, int NTT, int NG, int PG>
+template <int D, int NH, int NTT, int NG, int PG, int TOK>
 static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
-    using F = FusedCfg<D, NH, NTT, NG>;
+    using F = FusedCfg<D, NH, NTT, NG, TOK>;
     static bool attr_set = false;
     const size_t bytes = NG == 1 ? dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 + 32 * NH * 4  // = fused_lds_bytes
                                  : (size_t)NH * dm.I.head_bytes + 32 * F::TILE_RS + NH * D * 4 + 32 * 4 +
                                        2 * NH * F::TPH * 1024;                                          // = mid_lds_bytes
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int tiles = (dm.N + 31) / 32;
-    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
+    const int tiles = (dm.N + TOK - 1) / TOK;
+    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG, TOK>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 
-template <int D, int NH, int NTT, int NG>
+template <int D, int NH, int NTT, int NG, int TOK = 32>
 static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, int grid, hipStream_t st) {
-    if (grid == TAQ_PROB_LOG2) return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_LOG2>(tab, dm, st);
-    if (grid == TAQ_PROB_ROWMAX) return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_ROWMAX>(tab, dm, st);
-    return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_LINEAR>(tab, dm, st);
+    if (grid == TAQ_PROB_LOG2) return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_LOG2, TOK>(tab, dm, st);
+    if (grid == TAQ_PROB_ROWMAX) return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_ROWMAX, TOK>(tab, dm, st);
+    return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_LINEAR, TOK>(tab, dm, st);
 }
 
 hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, const taq_debug* dbg, hipStream_t st) {
@@ -1159,9 +1161,16 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.ws_omax = nullptr;
     dm.omax_n = 0;
     dm.group_fastest = 0;
-    if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8, TAQ_NTT_40, 1>(tab, dm, s.prob_grid, st);
-    if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8, 2, 1>(tab, dm, s.prob_grid, st);
-    if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10, 2, 1>(tab, dm, s.prob_grid, st);
+    // 32-token tiles that would occupy under half of the 256 compute units: 16-token workgroups instead
+    // (TAQ_FUSED_TOKENS=32 or 16 in the environment forces one variant: for tests and tuning)
+    bool few = ((s.N + 31) / 32) * R * s.B <= 128;
+    if (const char* force = getenv("TAQ_FUSED_TOKENS")) few = atoi(force) == 16 ? true : atoi(force) == 32 ? false : few;
+    if (d == 40 && s.H == 8)
+        return few ? launch_fused_cfg<40, 8, 1, 1, 16>(tab, dm, s.prob_grid, st) : launch_fused_cfg<40, 8, TAQ_NTT_40, 1>(tab, dm, s.prob_grid, st);
+    if (d == 80 && s.H == 8)
+        return few ? launch_fused_cfg<80, 8, 1, 1, 16>(tab, dm, s.prob_grid, st) : launch_fused_cfg<80, 8, 2, 1>(tab, dm, s.prob_grid, st);
+    if (d == 64 && s.H == 10)
+        return few ? launch_fused_cfg<64, 10, 1, 1, 16>(tab, dm, s.prob_grid, st) : launch_fused_cfg<64, 10, 2, 1>(tab, dm, s.prob_grid, st);
     return hipErrorInvalidValue;
 }
 

@@ -418,3 +418,17 @@ def test_rowmax_probability_grid_when_a_trigger_takes_the_whole_row():
         L.Wk = (L.Wk.astype(np.float32) * 4.0).astype(np.float16)
         L.Wv = (L.Wv.astype(np.float32) / scale).astype(np.float16)  # keeps the outputs (~ the trigger's V row) of order 1
         check_layer(L, f"rowmax grid dominant trigger x{scale} C={C}", bits_prob=8, prob_grid="rowmax")
+
+
+@pytest.mark.parametrize("tokens", ["32", "16"])
+@pytest.mark.parametrize("C,H,N,T_,bits_kv", [(640, 8, 45, 77, 8), (640, 10, 70, 50, 4), (640, 8, 130, 33, 4), (320, 8, 150, 77, 8)])
+def test_fused_kernel_both_workgroup_sizes(C, H, N, T_, bits_kv, tokens, monkeypatch):
+    """Single-kernel layers run with 32-token workgroups when that fills the chip and with 16-token workgroups otherwise;
+    both variants are forced here on the same small layers and must give bit-identical outputs."""
+    L = synth.make_layer("tok", seed=C + H + N, B=2, N=N, C=C, H=H, Cc=64, T=T_, bits_kv=bits_kv,
+                         trigger_positions=(1, T_ - 1), trigger_scale=3.0, bias=True)
+    monkeypatch.setenv("TAQ_FUSED_TOKENS", tokens)
+    g = check_layer(L, f"fused C={C} H={H} N={N} workgroup tokens={tokens}")
+    monkeypatch.setenv("TAQ_FUSED_TOKENS", "32" if tokens == "16" else "16")
+    g2 = G.GpuRun(L, taps=False)
+    assert np.array_equal(g.out.view(np.uint16), g2.out.view(np.uint16))
