@@ -47,6 +47,8 @@ def parse():
                    help="run only warmup + timed steps (for rocprofv3), skip the side measurements")
     p.add_argument("--traffic-probe", action="store_true",
                    help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: a device copy of known size, then eager steps")
+    p.add_argument("--summarize-sq", nargs="+", metavar="CSV",
+                   help="rocprofv3 --pmc SQ_* counter CSVs of --profile-only runs -> profiles/fused_block_kernel_cfg2_pmc.json")
     p.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                    help="turn the two counter_collection CSVs of the traffic probe into profiles/traffic.json")
     return p.parse_args()
@@ -183,6 +185,26 @@ def other_configs(dev, use_graph):
 
 
 COPY_BYTES = 256 << 20  # the known-size copy of the traffic probe reads and writes this many bytes
+ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 lane-ops/s
+#   (the chip's 157.3 TFLOP/s fp32 vector figure is this x 2 for an FMA x 2 for packed fp32, which this build may not use)
+
+
+def summarize_sq(csvs):
+    """Mean per launch of every SQ_* counter over the fused kernel's dispatches (rocprofv3 --pmc, one CSV per pass);
+    writes profiles/fused_block_kernel_cfg2_pmc.json, which the ALU-roofline figure of the bench line reads."""
+    import csv
+    acc = {}
+    for path in csvs:
+        for r in csv.DictReader(open(path)):
+            if "fused_block_kernel" in r["Kernel_Name"]:
+                acc.setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+    if not acc:
+        raise SystemExit("no fused_block_kernel dispatches in " + " ".join(csvs))
+    out = {k: sum(v[4:]) / max(1, len(v[4:])) for k, v in sorted(acc.items())}  # skip the first (cold) dispatches
+    out["wavefronts_per_launch"] = out.get("SQ_WAVES", 2048.0)
+    path = os.path.join(ROOT, "profiles", "fused_block_kernel_cfg2_pmc.json")
+    json.dump(out, open(path, "w"), indent=1)
+    print(json.dumps(out))
 
 
 def summarize_pmc(fetch_csv, write_csv):
@@ -215,6 +237,9 @@ def summarize_pmc(fetch_csv, write_csv):
 
 def main():
     a = parse()
+    if a.summarize_sq:
+        summarize_sq(a.summarize_sq)
+        return
     if a.summarize_pmc:
         summarize_pmc(*a.summarize_pmc)
         return
@@ -316,6 +341,20 @@ def main():
     result["roofline"] = {"kernel": "fused_block_kernel<40,8>", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
                           "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
                           "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": t_fused * 1e6}
+    # vector-ALU view of the same kernel: what actually bounds it. Lane-operations per launch = the measured count of
+    # vector instructions (SQ_INSTS_VALU, rocprofv3 --pmc, profiles/) x 64 lanes; transcendentals count once although
+    # they issue at quarter rate, so the true issue-slot use is somewhat higher than this figure.
+    ppath = os.path.join(ROOT, "profiles", "fused_block_kernel_cfg2_pmc.json")
+    if os.path.exists(ppath):
+        try:
+            valu = float(json.load(open(ppath))["SQ_INSTS_VALU"])
+            lane_ops = valu * 64.0
+            result["roofline_alu"] = {"kernel": "fused_block_kernel<40,8>", "bound": "alu",
+                                      "achieved": lane_ops / t_fused / 1e12, "peak": ALU_PEAK_TLANEOPS,
+                                      "unit": "T lane-op/s", "frac": lane_ops / t_fused / 1e12 / ALU_PEAK_TLANEOPS,
+                                      "valu_instructions_per_launch": valu}
+        except Exception:  # noqa: BLE001
+            pass
     # integer matrix work inside the same kernel: to_q + to_out (2*M*C*C each) and K~ Q~^T (2*M*T*C)
     int8_ops = 2.0 * tokens * C * C * 2 + 2.0 * tokens * T_ * C
     result["roofline_mfma_int8"] = {"kernel": "fused_block_kernel<40,8>", "bound": "mfma", "achieved": int8_ops / t_fused / 1e12,
