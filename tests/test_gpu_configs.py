@@ -24,6 +24,19 @@ def test_config2_headline_shape():
     check_layer(synth.config2())
 
 
+@pytest.mark.parametrize("bits_kv,bits_q,bits_prob,prob_grid", [
+    (4, 4, 4, "linear"),    # the 8/4 setting of Table 1
+    (4, 4, 4, "log2"),      # ... with the logarithmic probability grid of the ablation table
+    (8, 8, 8, "rowmax"),    # per-row dynamic probability scale
+])
+def test_config2_headline_shape_other_settings(bits_kv, bits_q, bits_prob, prob_grid):
+    """The headline shape at full size in the other activation settings bench.py times."""
+    import dataclasses
+    L = dataclasses.replace(synth.config2(), bits_kv=bits_kv)
+    check_layer(L, f"config2 kv{bits_kv} q{bits_q} p{bits_prob} {prob_grid}", bits_q=bits_q, bits_prob=bits_prob,
+                prob_grid=prob_grid, w_layout=1)
+
+
 @pytest.mark.parametrize("layer", list(range(16)))
 def test_config3_unet_step_layers_int4(layer):
     # the 16 cross-attention layers of one UNet step: 4096x320 (x5), 1024x640 (x5), 256x1280 (x5), 64x1280
