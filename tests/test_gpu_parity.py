@@ -203,8 +203,12 @@ def test_determinism_and_row_independence():
     assert np.array_equal(c.out.view(np.uint16), a.out[:, 100:170].view(np.uint16))
 
 
-def test_batched_requests_match_single_calls():
-    reqs = synth.config5(R=3, N=160)
+@pytest.mark.parametrize("C,H,N", [(320, 8, 160), (1280, 8, 40), (96, 4, 70), (640, 10, 50)])
+def test_batched_requests_match_single_calls(C, H, N):
+    """One batched call over a pointer table (own weights, context and mask per request) against single calls:
+    single-kernel shapes go out as grouped launches, the others request by request."""
+    reqs = [synth.make_layer(f"req{r}", seed=1000 + r + C, B=1, N=N, C=C, H=H, Cc=64, T=77, bits_kv=8,
+                             n_random_triggers=1 + r, trigger_scale=3.0) for r in range(3)]
     runs = [G.GpuRun(L, taps=False) for L in reqs]
     s = runs[0].shape
     table = []
