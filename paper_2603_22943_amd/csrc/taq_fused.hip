@@ -268,7 +268,7 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
 template <int D, int NH, int NTT, int NG, int PG, int TOK = 32>
 __global__ __launch_bounds__(64 * NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1))
-__attribute__((amdgpu_waves_per_eu(1, (NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1) + 3) / 4)))
+__attribute__((amdgpu_waves_per_eu(1, TOK == 16 ? 4 : (NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
     using F = FusedCfg<D, NH, NTT, NG, TOK>;
     static_assert(TOK == 32 || (TOK == 16 && NTT == 1 && NG == 1), "a workgroup owns 32 image tokens, or 16 with one tile per wavefront");
@@ -297,11 +297,11 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     // ---- LDS carve-up
     unsigned char* img = smem;                                  // K~/V~ image blocks of this workgroup's heads
     const size_t img_bytes = (size_t)NH * dm.I.head_bytes;
-    int8_t* tileq = reinterpret_cast<int8_t*>(smem + img_bytes);                // [32][C+16] hidden codes, later O codes
-    float* wsc = reinterpret_cast<float*>(smem + img_bytes + 32 * F::TILE_RS);  // s_wq | s_wo | bias_o  [3C]
-    float* s_h = wsc + (NG == 1 ? 3 * C : NH * D);               // [32]  (NG > 1: only s_wq of the workgroup's heads)
-    unsigned* omax = reinterpret_cast<unsigned*>(s_h + 32);      // [32][NH]  (NG == 1)
-    int* qacc = reinterpret_cast<int*>(s_h + 32);                // [2][NH*TPH][64][4] to_q accumulators (NG > 1)
+    int8_t* tileq = reinterpret_cast<int8_t*>(smem + img_bytes);                 // [TOK][C+16] hidden codes, later O codes
+    float* wsc = reinterpret_cast<float*>(smem + img_bytes + TOK * F::TILE_RS);  // s_wq | s_wo | bias_o  [3C]
+    float* s_h = wsc + (NG == 1 ? 3 * C : NH * D);               // [TOK]  (NG > 1: only s_wq of the workgroup's heads)
+    unsigned* omax = reinterpret_cast<unsigned*>(s_h + TOK);     // [TOK][NH]  (NG == 1)
+    int* qacc = reinterpret_cast<int*>(s_h + TOK);               // [2][NH*TPH][64][4] to_q accumulators (NG > 1)
 
     const uint8_t* packed = rq.packed;
     const int ntrig = reinterpret_cast<const int*>(packed + dm.L.ntrig)[b];
@@ -600,13 +600,13 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     // wavefront reads it, so only this wavefront waits for it. The last piece may be fetched more than once.
     if constexpr (NG == 1) {
         const unsigned char* gsrc = packed + dm.L.image + (size_t)b * dm.L.image_bytes + (size_t)h * dm.I.head_bytes;
-        const int nchunk = (int)(dm.I.head_bytes >> 10);
+        const int last = (int)dm.I.head_bytes - 1024;  // the block is a multiple of 256 bytes: the last piece overlaps
 #pragma unroll
         for (int k = 0; k < F::IMGC; ++k) {
-            const int c = k < nchunk ? k : nchunk - 1;
+            const int c = k * 1024 < last ? k * 1024 : last;
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(gsrc + (size_t)c * 1024 + lane * 16),
-                (__attribute__((address_space(3))) void*)(imgh + c * 1024), 16, 0, 0);
+                (const __attribute__((address_space(1))) void*)(gsrc + c + lane * 16),
+                (__attribute__((address_space(3))) void*)(imgh + c), 16, 0, 0);
         }
     }
     if constexpr (NG == 1) load_protected();
@@ -1112,7 +1112,7 @@ template <int D, int NH, int NTT, int NG, int PG, int TOK>
 static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     using F = FusedCfg<D, NH, NTT, NG, TOK>;
     static bool attr_set = false;
-    const size_t bytes = NG == 1 ? dm.I.bytes + 32 * F::TILE_RS + 3 * F::C * 4 + 32 * 4 + 32 * NH * 4  // = fused_lds_bytes
+    const size_t bytes = NG == 1 ? dm.I.bytes + TOK * F::TILE_RS + 3 * F::C * 4 + TOK * 4 + TOK * NH * 4  // = fused_lds_bytes
                                  : (size_t)NH * dm.I.head_bytes + 32 * F::TILE_RS + NH * D * 4 + 32 * 4 +
                                        2 * NH * F::TPH * 1024;                                          // = mid_lds_bytes
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;

@@ -49,7 +49,7 @@ struct KvImage {
     size_t bias;    // f32 [96]  0 for unprotected tokens, -inf for protected / padding (same in every head)
     size_t oscale;  // f32       2^-kexp / 255
     size_t vpre;    // f32       2^kexp
-    size_t head_bytes;
+    size_t head_bytes;  // one head's block, a multiple of 256 bytes
     size_t bytes;   // H * head_bytes
 };
 
@@ -68,7 +68,7 @@ static inline KvImage kv_image(const taq_shape& s) {
     I.bias = take(96 * 4);
     I.oscale = take(4);
     I.vpre = take(4);
-    I.head_bytes = align_up(off, 1024);
+    I.head_bytes = align_up(off, 256);  // (at least 1 KiB: the kernels copy it in 1 KiB pieces, the last one overlapping)
     I.bytes = H * I.head_bytes;
     return I;
 }
@@ -83,8 +83,8 @@ static inline size_t weight_pack_bytes(const taq_shape& s) {
 }
 
 // LDS bytes of the fused block kernel: K~/V~ image, int8 token tile, weight scales, per-token scratch.
-static inline size_t fused_lds_bytes(const taq_shape& s) {
-    return kv_image(s).bytes + 32 * ((size_t)s.C + 16) + 3 * (size_t)s.C * 4 + 32 * 4 + 32 * (size_t)s.H * 4;
+static inline size_t fused_lds_bytes(const taq_shape& s, int tok = 32) {
+    return kv_image(s).bytes + tok * ((size_t)s.C + 16) + 3 * (size_t)s.C * 4 + tok * 4 + tok * (size_t)s.H * 4;
 }
 
 // Shapes the fused block kernel is instantiated for: (d, H) = (40, 8), (80, 8), (64, 10), as long as
