@@ -37,6 +37,10 @@
 #include <stddef.h>
 #include <stdint.h>
 
+/* Environment (read at each call, for tests and tuning only): TAQ_FUSED_TOKENS=32 or 16 forces the image-token
+ * tile of the single-kernel path; by default the library picks 16 when 32-token tiles would fill at most half of
+ * the GPU's compute units. Results do not depend on it. */
+
 #ifdef __cplusplus
 extern "C" {
 #endif
