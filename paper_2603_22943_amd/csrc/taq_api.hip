@@ -117,30 +117,32 @@ static int quantize_kv_impl(const void* context, const uint8_t* trigger_mask, co
     const int8_t* w_code = w_code_in;
     const float* s_w = s_w_in;
 
-    TAQ_TRY_HIP(launch_kv_mask_scan(trigger_mask, s.B, s.T, s.bits_kv, ntrig, trig_idx, slot_of, st));
+    // one launch: protected-token list, per-token int8 codes of the context (needed for unprotected tokens only) and,
+    // unless the caller brings them, the 8-bit weight codes (Wk rows then Wv rows)
+    int8_t* wc = reinterpret_cast<int8_t*>(ws + W.w_code);
+    float* sw = reinterpret_cast<float*>(ws + W.s_w);
+    TAQ_TRY_HIP(launch_kv_prep(s.bits_kv != 16 ? static_cast<const __half*>(context) : nullptr, M, x_code, s_x,
+                               w_code ? nullptr : static_cast<const __half*>(Wk),
+                               w_code ? nullptr : static_cast<const __half*>(Wv), s.C, wc, sw, s.Cc, trigger_mask, s.B,
+                               s.T, s.bits_kv, ntrig, trig_idx, slot_of, st));
     if (!w_code) {
-        // 8-bit weight codes, Wk rows then Wv rows
-        int8_t* wc = reinterpret_cast<int8_t*>(ws + W.w_code);
-        float* sw = reinterpret_cast<float*>(ws + W.s_w);
-        TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(Wk), s.C, s.Cc, wc, sw, st));
-        TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(Wv), s.C, s.Cc, wc + (size_t)s.C * s.Cc, sw + s.C, st));
         w_code = wc;
         s_w = sw;
     }
     if (s.bits_kv != 16) {
-        // unprotected tokens: per-token int8 context codes, integer GEMM, float32 dequantisation
-        TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(context), M, s.Cc, x_code, s_x, st));
-        TAQ_TRY_HIP(launch_gemm_i8(x_code, s_x, w_code, s_w, nullptr, M, 2 * s.C, s.Cc, rows_f, nullptr, 2 * s.C, st));
+        // unprotected tokens, one launch per (head, batch element): integer projection, float32 dequantisation, Eq. (2)
+        // codes and scales (zero on protected rows), and the operand-ordered image of the single-kernel paths
+        // (the same launch carries the workgroups that compute the protected rows in fp16)
+        TAQ_TRY_HIP(launch_kv_head(x_code, s_x, w_code, s_w, pk, static_cast<const __half*>(context), s, st));
+    } else {
+        // every row protected: zero scales, no code section, an image without integer rows, all rows in fp16
+        TAQ_TRY_HIP(launch_kv_pack(rows_f, slot_of, s.B, s.T, s.C, s.H, s.bits_kv, pk + L.k_code, pk + L.v_code,
+                                   reinterpret_cast<float*>(pk + L.s_k), reinterpret_cast<float*>(pk + L.s_v), st));
+        TAQ_TRY_HIP(launch_kv_image(pk, s, st));
+        TAQ_TRY_HIP(launch_kv_trigger_rows(static_cast<const __half*>(context), w_code, s_w, ntrig, trig_idx, s.B, s.T,
+                                           s.C, s.Cc, reinterpret_cast<__half*>(pk + L.k16),
+                                           reinterpret_cast<__half*>(pk + L.v16), reinterpret_cast<__half*>(pk + L.v16t), st));
     }
-    // Eq. (2): per-(head, token) codes of unprotected rows; zero codes/scales on protected rows
-    TAQ_TRY_HIP(launch_kv_pack(rows_f, slot_of, s.B, s.T, s.C, s.H, s.bits_kv, pk + L.k_code, pk + L.v_code,
-                               reinterpret_cast<float*>(pk + L.s_k), reinterpret_cast<float*>(pk + L.s_v), st));
-    // protected rows in fp16
-    TAQ_TRY_HIP(launch_kv_trigger_rows(static_cast<const __half*>(context), w_code, s_w, ntrig, trig_idx, s.B, s.T,
-                                       s.C, s.Cc, reinterpret_cast<__half*>(pk + L.k16),
-                                       reinterpret_cast<__half*>(pk + L.v16), reinterpret_cast<__half*>(pk + L.v16t), st));
-    // operand-ordered copy of the integer part for the fused block kernel
-    TAQ_TRY_HIP(launch_kv_image(pk, s, st));
     return TAQ_OK;
 }
 

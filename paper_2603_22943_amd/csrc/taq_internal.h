@@ -197,6 +197,16 @@ hipError_t launch_rowquant_f32(const float* x, int M, int K, int8_t* code, float
 // Per-(row, head) symmetric codes (8 or 4 bit, one per byte) of float32 rows: x [M][C] -> code [M][C], scale [M][H].
 hipError_t launch_headquant_f32(const float* x, int M, int C, int H, int bits, int8_t* code, float* scale, hipStream_t st);
 
+// First launch of taq_quantize_kv: per-row int8 codes of the context rows (context == NULL: skipped) and of the rows of
+// Wk / Wv (NULL: codes given by the caller), plus the protected-token bookkeeping, in one kernel.
+hipError_t launch_kv_prep(const __half* context, int M, int8_t* x_code, float* s_x, const __half* Wk, const __half* Wv,
+                          int C, int8_t* w_code, float* s_w, int K, const uint8_t* mask, int B, int T, int bits,
+                          int* ntrig, int* trig_idx, int* slot_of, hipStream_t st);
+// Second launch of taq_quantize_kv (bits_kv 4 or 8): per (head, batch element) the integer K/V projection, Eq. (2)
+// codes and scales into qkv_packed, and the head's block of the operand-ordered image where the shape has one.
+// The same launch computes the protected fp16 rows (K16, V16, V16T) from the unquantized context rows.
+hipError_t launch_kv_head(const int8_t* x_code, const float* s_x, const int8_t* w_code, const float* s_w, uint8_t* packed,
+                          const __half* context, const taq_shape& s, hipStream_t st);
 // Protected-token bookkeeping of qkv_packed from the mask (all tokens when bits == 16).
 hipError_t launch_kv_mask_scan(const uint8_t* mask, int B, int T, int bits, int* ntrig, int* trig_idx,
                                int* slot_of, hipStream_t st);

@@ -74,6 +74,98 @@ __global__ __launch_bounds__(256) void rowquant_f16_kernel(const __half* __restr
     }
 }
 
+// First launch of taq_quantize_kv: the per-row codes of up to three fp16 matrices that share the row length K (the
+// context rows and, unless cached, the rows of Wk and Wv), and the protected-token list, each part on workgroups of
+// its own: one launch instead of four.
+struct KvPrepJob {
+    const __half* x;   // rows to quantize (NULL: none)
+    int M;             // number of rows
+    int8_t* code;
+    float* scale;
+};
+
+__device__ __forceinline__ void rowquant_f16_row(const __half* __restrict__ x, int row, int K, int8_t* __restrict__ code,
+                                                  float* __restrict__ scale, int lane) {
+    const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)row * K);
+    const int nv = K >> 3;
+    float amax = 0.f;
+    for (int v = lane; v < nv; v += 64) {
+        float f[8];
+        unpack_half8(xr[v], f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
+    }
+    amax = wave_max(amax);
+    const bool zero = amax == 0.f;
+    const float sc = zero ? 1.f : amax / 127.f;
+    const float safe = zero ? 1.f : amax;
+    if (lane == 0) scale[row] = sc;
+    uint2* cr = reinterpret_cast<uint2*>(code + (size_t)row * K);
+    for (int v = lane; v < nv; v += 64) {
+        float f[8];
+        unpack_half8(xr[v], f);
+        int c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c[i] = symq_code(f[i], 127.f, safe);
+        uint2 o;
+        o.x = pack4_i8(c[0], c[1], c[2], c[3]);
+        o.y = pack4_i8(c[4], c[5], c[6], c[7]);
+        cr[v] = o;
+    }
+}
+
+__global__ __launch_bounds__(256) void kv_prep_kernel(KvPrepJob j0, KvPrepJob j1, KvPrepJob j2, int K,
+                                                      const uint8_t* __restrict__ mask, int B, int T, int bits,
+                                                      int* __restrict__ ntrig, int* __restrict__ trig_idx,
+                                                      int* __restrict__ slot_of) {
+    __shared__ int flag[128];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int blk = blockIdx.x;
+    if (blk < B) {  // protected-token list of batch element blk (T <= 96: a direct count is cheaper than a scan)
+        const int t = threadIdx.x;
+        const bool prot = t < T && (bits == 16 || mask[blk * T + t] != 0);
+        if (t < 128) flag[t] = prot ? 1 : 0;
+        __syncthreads();
+        if (t >= 128) return;
+        int before = 0, total = 0;
+        for (int u = 0; u < T; ++u) {
+            before += (u < t) ? flag[u] : 0;
+            total += flag[u];
+        }
+        if (t < T) {
+            slot_of[blk * T + t] = prot ? before : -1;
+            if (prot) trig_idx[blk * T + before] = t;
+            if (t >= total) trig_idx[blk * T + t] = -1;
+        }
+        if (t == 0) ntrig[blk] = total;
+        return;
+    }
+    blk -= B;
+    const KvPrepJob jobs[3] = {j0, j1, j2};
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const int nb = (jobs[k].M + 3) / 4;
+        if (blk < nb) {
+            const int row = blk * 4 + wave;
+            if (jobs[k].x && row < jobs[k].M) rowquant_f16_row(jobs[k].x, row, K, jobs[k].code, jobs[k].scale, lane);
+            return;
+        }
+        blk -= nb;
+    }
+}
+
+hipError_t launch_kv_prep(const __half* context, int M, int8_t* x_code, float* s_x, const __half* Wk, const __half* Wv,
+                          int C, int8_t* w_code, float* s_w, int K, const uint8_t* mask, int B, int T, int bits,
+                          int* ntrig, int* trig_idx, int* slot_of, hipStream_t st) {
+    KvPrepJob j0 = {context, context ? M : 0, x_code, s_x};
+    KvPrepJob j1 = {Wk, Wk ? C : 0, w_code, s_w};
+    KvPrepJob j2 = {Wv, Wv ? C : 0, w_code + (size_t)C * K, s_w + C};
+    const int blocks = B + (j0.M + 3) / 4 + (j1.M + 3) / 4 + (j2.M + 3) / 4;
+    hipLaunchKernelGGL(kv_prep_kernel, dim3(blocks), dim3(256), 0, st, j0, j1, j2, K, mask, B, T, bits, ntrig, trig_idx,
+                       slot_of);
+    return hipGetLastError();
+}
+
 hipError_t launch_rowquant_f16(const __half* x, int M, int K, int8_t* code, float* scale, hipStream_t st) {
     if (M <= 0) return hipSuccess;
     hipLaunchKernelGGL(rowquant_f16_kernel, dim3((M + 3) / 4), dim3(256), 0, st, x, M, K, code, scale);
@@ -252,20 +344,15 @@ hipError_t launch_kv_pack(const float* rows_f, const int* slot_of, int B, int T,
 }
 
 // ---------------------------------------------------------------- protected K/V rows
-// One workgroup per (slot, batch, 64 output channels): y[c] = s_w[c] * sum_k ctx[t][k] * w_code[c][k].
+// One workgroup (512 threads) per (slot, batch, 128 output channels): y[c] = s_w[c] * sum_k ctx[t][k] * w_code[c][k].
 // Four threads share an output channel, each summing every fourth 16-code piece of the row in float32 (four
 // partial sums per thread), combined by two shuffles; one rounding to fp16. Cc % 16 == 0, Cc <= 4096.
-__global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __restrict__ context,
-                                                              const int8_t* __restrict__ w_code,
-                                                              const float* __restrict__ s_w,
-                                                              const int* __restrict__ ntrig,
-                                                              const int* __restrict__ trig_idx, int T, int C,
-                                                              int Cc, __half* __restrict__ k16,
-                                                              __half* __restrict__ v16,
-                                                              __half* __restrict__ v16t) {
-    __shared__ float xs[4096];
-    const int slot = blockIdx.x, b = blockIdx.y;
-    const int c = blockIdx.z * 64 + (threadIdx.x >> 2), part = threadIdx.x & 3;  // output channel in [0, 2C)
+__device__ __forceinline__ void kv_trigger_rows_block(float* xs, int slot, int b, int cblk, const __half* __restrict__ context,
+                                                      const int8_t* __restrict__ w_code, const float* __restrict__ s_w,
+                                                      const int* __restrict__ ntrig, const int* __restrict__ trig_idx,
+                                                      int T, int C, int Cc, __half* __restrict__ k16,
+                                                      __half* __restrict__ v16, __half* __restrict__ v16t) {
+    const int c = cblk * 128 + (threadIdx.x >> 2), part = threadIdx.x & 3;  // output channel in [0, 2C)
     // unused slots of all three copies read as zeros: the padding slots T..95 of the transposed copy ...
     if (slot == T - 1 && c >= C && c < 2 * C && part == 0)
         for (int sp = T; sp < 96; ++sp) v16t[((size_t)b * C + (c - C)) * 96 + sp] = __float2half(0.f);
@@ -282,7 +369,7 @@ __global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __re
     }
     const int t = trig_idx[b * T + slot];
     const __half* xr = context + ((size_t)b * T + t) * Cc;
-    for (int k = threadIdx.x; k < Cc; k += 256) xs[k] = __half2float(xr[k]);
+    for (int k = threadIdx.x; k < Cc; k += 512) xs[k] = __half2float(xr[k]);
     __syncthreads();
     float sum = 0.f;
     if (c < 2 * C) {
@@ -315,11 +402,212 @@ __global__ __launch_bounds__(256) void kv_trigger_rows_kernel(const __half* __re
     }
 }
 
+__global__ __launch_bounds__(512) void kv_trigger_rows_kernel(const __half* __restrict__ context,
+                                                              const int8_t* __restrict__ w_code,
+                                                              const float* __restrict__ s_w,
+                                                              const int* __restrict__ ntrig,
+                                                              const int* __restrict__ trig_idx, int T, int C,
+                                                              int Cc, __half* __restrict__ k16,
+                                                              __half* __restrict__ v16,
+                                                              __half* __restrict__ v16t) {
+    __shared__ float xs[4096];
+    kv_trigger_rows_block(xs, blockIdx.x, blockIdx.y, blockIdx.z, context, w_code, s_w, ntrig, trig_idx, T, C, Cc, k16, v16, v16t);
+}
+
 hipError_t launch_kv_trigger_rows(const __half* context, const int8_t* w_code, const float* s_w,
                                   const int* ntrig, const int* trig_idx, int B, int T, int C, int Cc,
                                   __half* k16, __half* v16, __half* v16t, hipStream_t st) {
-    hipLaunchKernelGGL(kv_trigger_rows_kernel, dim3(T, B, (2 * C + 63) / 64), dim3(256), 0, st, context, w_code, s_w,
+    hipLaunchKernelGGL(kv_trigger_rows_kernel, dim3(T, B, (2 * C + 127) / 128), dim3(512), 0, st, context, w_code, s_w,
                        ntrig, trig_idx, T, C, Cc, k16, v16, v16t);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- K/V projection + Eq. (2) codes + image, per head
+// Second launch of taq_quantize_kv for 4/8-bit rows: a workgroup does, for one head and every text
+// token, the integer projection of the head's K (or V) channels (acc = x_code . w_code over Cc, 16x16x64 int8 MFMA,
+// channels as rows and tokens as columns), the float32 dequantisation float(acc) * (s_x * s_w), the per-(head, token)
+// symmetric quantizer of Eq. (2) (zero codes and scales on protected tokens), and writes the plain code / scale
+// sections of qkv_packed and, where the shape has one, this head's block of the operand-ordered image.
+// One workgroup per (head, batch element, K or V), one wavefront per 16-token column tile. d % 8 == 0, Cc % 16 == 0.
+// The same launch carries the workgroups of the protected fp16 rows (they need only the first launch's results too).
+typedef int kvh_int32x4_t __attribute__((ext_vector_type(4)));
+#ifndef TAQ_NEG_INF
+#define TAQ_NEG_INF (-__builtin_inff())
+#endif
+
+__device__ __forceinline__ float kvh_quad_allmax(float x) {  // over the lanes l, l^16, l^32, l^48
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+template <int TPH>
+__global__ __launch_bounds__(512) void kv_head_kernel(const int8_t* __restrict__ x_code, const float* __restrict__ s_x,
+                                                      const int8_t* __restrict__ w_code, const float* __restrict__ s_w,
+                                                      uint8_t* __restrict__ packed, KvLayout L, KvImage I, int T, int C,
+                                                      int H, int Cc, int bits, int B, const __half* __restrict__ context) {
+    __shared__ float xs[4096];  // protected-row workgroups: the context row in float32
+    __shared__ float sc_l[96];  // scales of the unprotected tokens of this head and side (0: protected / padding)
+    __shared__ unsigned scmax;
+    // workgroups [0, 2*H*B): (head, batch element, K or V); the rest: protected fp16 rows, (slot, batch, 128 channels)
+    const int nhead = 2 * H * B;
+    if ((int)blockIdx.x >= nhead) {
+        const int r = (int)blockIdx.x - nhead, nc = (2 * C + 127) / 128;
+        kv_trigger_rows_block(xs, r % T, (r / T) % B, r / (T * B), context, w_code, s_w,
+                              reinterpret_cast<const int*>(packed + L.ntrig), reinterpret_cast<const int*>(packed + L.trig_idx), T,
+                              C, Cc, reinterpret_cast<__half*>(packed + L.k16), reinterpret_cast<__half*>(packed + L.v16),
+                              reinterpret_cast<__half*>(packed + L.v16t));
+        (void)nc;
+        return;
+    }
+    const int h = (int)blockIdx.x % H, b = ((int)blockIdx.x / H) % B, side = (int)blockIdx.x / (H * B);  // side 0: K, 1: V
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
+    const int d = C / H;
+    const bool has_image = L.image_bytes != 0;
+    const int nsub = has_image ? I.cols_v / 16 : (T + 15) / 16;  // 16-token column tiles to produce (image: padded)
+    if (tid < 96) sc_l[tid] = 0.f;
+    if (tid == 0) scmax = 0u;
+    __syncthreads();
+    const float qmaxf = bits == 4 ? 7.f : 127.f;
+    const int* slot_of = reinterpret_cast<const int*>(packed + L.slot_of) + b * T;
+    uint8_t* codes = packed + (side ? L.v_code : L.k_code);
+    float* scales = reinterpret_cast<float*>(packed + (side ? L.s_v : L.s_k)) + ((size_t)b * H + h) * T;
+    uint8_t* img = packed + L.image + (size_t)b * L.image_bytes + (size_t)h * I.head_bytes;
+    const int st = wave;  // one 16-token column tile per wavefront (at most 6)
+    if (st < nsub) {
+        const int8_t* wrow[TPH];
+#pragma unroll
+        for (int j = 0; j < TPH; ++j) {
+            int c = side * C + h * d + 16 * j + r16;  // rows past the head are computed and dropped; stay inside [0, 2C)
+            c = c < 2 * C ? c : 2 * C - 1;
+            wrow[j] = w_code + (size_t)c * Cc + 16 * q;
+        }
+        const int t = 16 * st + r16, tc = t < T ? t : T - 1;
+        const int8_t* xrow = x_code + ((size_t)b * T + tc) * Cc + 16 * q;
+        kvh_int32x4_t acc[TPH];
+#pragma unroll
+        for (int j = 0; j < TPH; ++j) acc[j] = (kvh_int32x4_t){0, 0, 0, 0};
+        // K steps of 64 codes, KB at a time: all their loads are issued before the first MFMA consumes one
+        constexpr int KB = TPH <= 3 ? 12 : TPH <= 5 ? 6 : 2;  // (TPH + 1) * KB * 4 operand registers in flight
+        for (int k0 = 0; k0 < Cc; k0 += 64 * KB) {
+            kvh_int32x4_t xb[KB], wa[KB][TPH];
+#pragma unroll
+            for (int u = 0; u < KB; ++u) {
+                const bool in = k0 + 64 * u + 16 * q < Cc;  // past the end of the row (its length need not divide)
+                xb[u] = (kvh_int32x4_t){0, 0, 0, 0};
+                if (in) xb[u] = *reinterpret_cast<const kvh_int32x4_t*>(xrow + k0 + 64 * u);
+#pragma unroll
+                for (int j = 0; j < TPH; ++j) {
+                    wa[u][j] = (kvh_int32x4_t){0, 0, 0, 0};
+                    if (in) wa[u][j] = *reinterpret_cast<const kvh_int32x4_t*>(wrow[j] + k0 + 64 * u);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < KB; ++u)
+#pragma unroll
+                for (int j = 0; j < TPH; ++j) acc[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa[u][j], xb[u], acc[j], 0, 0, 0);
+        }
+        // this lane: token t, channels 16*j + 4*q .. +3 of the head
+        const bool tv = t < T;
+        const bool prot = !tv || slot_of[tc] >= 0;
+        const float sx = s_x[(size_t)b * T + tc];
+        float v[TPH][4];
+        float amax = 0.f;
+#pragma unroll
+        for (int j = 0; j < TPH; ++j) {
+            const int cl = 16 * j + 4 * q;
+            const bool valid = cl < d;
+            float4 sw4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (valid) sw4 = *reinterpret_cast<const float4*>(s_w + side * C + h * d + cl);
+            const float swv[4] = {sw4.x, sw4.y, sw4.z, sw4.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float sc = sx * swv[i];
+                v[j][i] = valid ? (float)acc[j][i] * sc : 0.f;
+                amax = fmaxf(amax, fabsf(v[j][i]));
+            }
+        }
+        amax = kvh_quad_allmax(amax);
+        const float sc = prot ? 0.f : (amax == 0.f ? 1.f : amax / qmaxf);
+        const float safe = amax == 0.f ? 1.f : amax;
+        if (tv && q == 0) scales[t] = sc;
+        if (!prot && q == 0) {
+            sc_l[t] = sc;
+            atomicMax(&scmax, __float_as_uint(sc));
+        }
+        const int pos = (t & ~31) + 8 * ((t >> 2) & 3) + 4 * ((t >> 4) & 1) + (t & 3);  // place of token t in a V^T row
+#pragma unroll
+        for (int j = 0; j < TPH; ++j) {
+            const int cl = 16 * j + 4 * q;
+            int c[4] = {0, 0, 0, 0};
+            if (!prot && cl < d) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) c[i] = symq_code(v[j][i], qmaxf, safe);
+            }
+            if (tv && cl < d) {
+                if (bits == 8) {
+                    *reinterpret_cast<unsigned*>(codes + ((size_t)b * T + t) * C + h * d + cl) = pack4_i8(c[0], c[1], c[2], c[3]);
+                } else {
+                    const unsigned short w = (unsigned short)((c[0] & 0xF) | ((c[1] & 0xF) << 4) | ((c[2] & 0xF) << 8) |
+                                                              ((c[3] & 0xF) << 12));
+                    *reinterpret_cast<unsigned short*>(codes + ((size_t)b * T + t) * (C / 2) + (h * d + cl) / 2) = w;
+                }
+            }
+            if (has_image) {
+                if (!side) {  // Kp[t][tile][quarter][4]; zeros past the head and past the last token
+                    if (t < I.rows_k)
+                        *reinterpret_cast<unsigned*>(img + I.kp + (((size_t)t * I.tph + j) * 4 + q) * 4) = pack4_i8(c[0], c[1], c[2], c[3]);
+                } else if (cl < d) {  // Vt[channel][pos], stored with the sign bit flipped
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) img[I.vt + (size_t)(cl + i) * I.cols_v + pos] = (uint8_t)((c[i] & 0xFF) ^ 0x80);
+                }
+            }
+        }
+    }
+    if (!has_image) return;
+    __syncthreads();
+    if (!side) {  // token scales of K and the 0 / -inf token bias
+        if (tid < 96) {
+            reinterpret_cast<float*>(img + I.s_k)[tid] = sc_l[tid];
+            reinterpret_cast<float*>(img + I.bias)[tid] = sc_l[tid] != 0.f ? 0.f : TAQ_NEG_INF;  // an unprotected token's scale is never 0
+        }
+        return;
+    }
+    // per-head power-of-two prescale of V: the largest |s_V * code| goes to [256, 512)
+    int kexp = 0;
+    {
+        const float dmax = __uint_as_float(scmax) * qmaxf;
+        if (dmax > 0.f) {
+            int e;
+            (void)frexpf(dmax, &e);
+            kexp = 9 - e;
+        }
+    }
+    const float vpre = ldexpf(1.0f, kexp);
+    if (tid < 96) reinterpret_cast<float*>(img + I.s_vp)[tid] = sc_l[tid] * vpre;
+    if (tid == 0) {
+        reinterpret_cast<float*>(img + I.vpre)[0] = vpre;
+        reinterpret_cast<float*>(img + I.oscale)[0] = ldexpf(1.0f, -kexp);
+    }
+}
+
+hipError_t launch_kv_head(const int8_t* x_code, const float* s_x, const int8_t* w_code, const float* s_w, uint8_t* packed,
+                          const __half* context, const taq_shape& s, hipStream_t st) {
+    const KvLayout L = kv_layout(s);
+    const KvImage I = kv_image(s);
+    const int tph = (s.C / s.H + 15) / 16;
+    const dim3 grid(2 * s.H * s.B + s.T * s.B * ((2 * s.C + 127) / 128)), block(512);
+#define TAQ_KVH(N)                                                                                                     \
+    case N:                                                                                                            \
+        hipLaunchKernelGGL(kv_head_kernel<N>, grid, block, 0, st, x_code, s_x, w_code, s_w, packed, L, I, s.T, s.C, s.H, \
+                           s.Cc, s.bits_kv, s.B, context);                                                             \
+        break;
+    switch (tph) {
+        TAQ_KVH(1) TAQ_KVH(2) TAQ_KVH(3) TAQ_KVH(4) TAQ_KVH(5) TAQ_KVH(6) TAQ_KVH(7) TAQ_KVH(8) TAQ_KVH(9) TAQ_KVH(10)
+        default: return hipErrorInvalidValue;
+    }
+#undef TAQ_KVH
     return hipGetLastError();
 }
 
