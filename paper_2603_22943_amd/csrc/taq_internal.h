@@ -207,9 +207,6 @@ hipError_t launch_kv_prep(const __half* context, int M, int8_t* x_code, float* s
 // The same launch computes the protected fp16 rows (K16, V16, V16T) from the unquantized context rows.
 hipError_t launch_kv_head(const int8_t* x_code, const float* s_x, const int8_t* w_code, const float* s_w, uint8_t* packed,
                           const __half* context, const taq_shape& s, hipStream_t st);
-// Protected-token bookkeeping of qkv_packed from the mask (all tokens when bits == 16).
-hipError_t launch_kv_mask_scan(const uint8_t* mask, int B, int T, int bits, int* ntrig, int* trig_idx,
-                               int* slot_of, hipStream_t st);
 // Per-(head, token) codes and scales of unprotected K/V rows, written into qkv_packed.
 hipError_t launch_kv_pack(const float* rows_f, const int* slot_of, int B, int T, int C, int H, int bits,
                           uint8_t* k_code, uint8_t* v_code, float* s_k, float* s_v, hipStream_t st);

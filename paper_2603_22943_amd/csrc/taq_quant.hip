@@ -252,34 +252,6 @@ hipError_t launch_headquant_f32(const float* x, int M, int C, int H, int bits, i
     return hipGetLastError();
 }
 
-// ---------------------------------------------------------------- protected-token list
-__global__ __launch_bounds__(128) void kv_mask_scan_kernel(const uint8_t* __restrict__ mask, int T, int bits,
-                                                            int* __restrict__ ntrig, int* __restrict__ trig_idx,
-                                                            int* __restrict__ slot_of) {
-    __shared__ int flag[128];
-    const int b = blockIdx.x, t = threadIdx.x;
-    const bool prot = t < T && (bits == 16 || mask[b * T + t] != 0);
-    flag[t] = prot ? 1 : 0;
-    __syncthreads();
-    int before = 0, total = 0;  // T <= 96: a direct count is cheaper than a scan
-    for (int u = 0; u < T; ++u) {
-        before += (u < t) ? flag[u] : 0;
-        total += flag[u];
-    }
-    if (t < T) {
-        slot_of[b * T + t] = prot ? before : -1;
-        if (prot) trig_idx[b * T + before] = t;
-        if (t >= total) trig_idx[b * T + t] = -1;
-    }
-    if (t == 0) ntrig[b] = total;
-}
-
-hipError_t launch_kv_mask_scan(const uint8_t* mask, int B, int T, int bits, int* ntrig, int* trig_idx,
-                               int* slot_of, hipStream_t st) {
-    hipLaunchKernelGGL(kv_mask_scan_kernel, dim3(B), dim3(128), 0, st, mask, T, bits, ntrig, trig_idx, slot_of);
-    return hipGetLastError();
-}
-
 // ---------------------------------------------------------------- K~/V~ codes, Eq. (2)
 // One wavefront per (batch, token). rows_f holds that token's K channels then V channels;
 // each head's d channels are one quantization row. Protected tokens get zero codes/scales.
