@@ -380,14 +380,10 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
 
 template <int DT>
 static hipError_t launch_core_dt(const CoreArgs& a, int B, hipStream_t st) {
-    static bool attr_set = false;
+    static std::atomic<unsigned long long> lds_set{0};
     const int bytes = CoreLds<DT>::BYTES;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_core_kernel<DT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&attn_core_kernel<DT>), bytes, lds_set);
+    if (e != hipSuccess) return e;
     dim3 grid((a.N + 127) / 128, a.H, B);
     hipLaunchKernelGGL(attn_core_kernel<DT>, grid, dim3(256), bytes, st, a);
     return hipGetLastError();

@@ -1096,13 +1096,9 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
 template <int C, int OT, bool FUSEQ>
 static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     const size_t bytes = 32 * (C + 16) + 32 * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&to_out_tail_kernel<C, OT, FUSEQ>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<unsigned long long> lds_set{0};
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&to_out_tail_kernel<C, OT, FUSEQ>), 160 * 1024, lds_set);
+    if (e != hipSuccess) return e;
     const int tiles = (dm.N + 31) / 32;
     hipLaunchKernelGGL((to_out_tail_kernel<C, OT, FUSEQ>), dim3(tiles * dm.B, C / 16 / OT), dim3(128 * OT), bytes, st, tab, dm);
     return hipGetLastError();
@@ -1111,17 +1107,13 @@ static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hi
 template <int D, int NH, int NTT, int NG, int PG, int TOK>
 static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     using F = FusedCfg<D, NH, NTT, NG, TOK>;
-    static bool attr_set = false;
+    static std::atomic<unsigned long long> lds_set{0};
     const size_t bytes = NG == 1 ? dm.I.bytes + TOK * F::TILE_RS + 3 * F::C * 4 + TOK * 4 + TOK * NH * 4  // = fused_lds_bytes
                                  : (size_t)NH * dm.I.head_bytes + 32 * F::TILE_RS + NH * D * 4 + 32 * 4 +
                                        2 * NH * F::TPH * 1024;                                          // = mid_lds_bytes
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK>), 160 * 1024, lds_set);
+    if (e != hipSuccess) return e;
     const int tiles = (dm.N + TOK - 1) / TOK;
     hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG, TOK>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();

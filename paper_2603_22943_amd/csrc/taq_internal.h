@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "taq.h"
 
 #define TAQ_MAX_T 96        // text tokens the attention core holds in LDS (3 tiles of 32)
@@ -186,6 +188,21 @@ static inline AttnWorkspace attn_workspace(const taq_shape& s) {
     W.s_o = take(M * 4);
     W.total = off;
     return W;
+}
+
+// Kernels that use more than 64 KiB of dynamic LDS need that attribute set once per kernel and device. `done` is the
+// kernel's bit mask of devices that have it (one static per kernel instantiation, the library's only state); setting
+// the attribute twice from two host threads that race here is harmless.
+static inline hipError_t ensure_dynamic_lds(const void* kernel, int bytes, std::atomic<unsigned long long>& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    done.fetch_or(bit, std::memory_order_release);
+    return hipSuccess;
 }
 
 // ---- kernel launchers (each returns a hipError_t from the launch) ----------------
