@@ -50,7 +50,8 @@ __device__ __forceinline__ float byte_to_float(unsigned w, int e) { return (floa
 // ------------------------------------------------------------------------------------------
 // K~/V~ image builder: rearranges the codes of qkv_packed into the order the fused kernel's MFMA
 // operands are read in, and precomputes the per-head power-of-two prescale of V.
-//   per head h:  Kp[t][tile][q][e] = k_code[t][h*d + 16*tile + 4*q + e]         (0 outside d / T)
+//   per head h:  Kp[t][tile][q][e] = k_code[t][h*d + 16*tile + 4*q + e]         (0 outside d / T; heads with a
+//                multiple of 4 tiles use the order [t][tile/4][q][tile%4][e])
 //                Vt[j][32*s + 8*q + 4*a + e] = v_code[t = 32*s + 16*a + 4*q + e][h*d + j] ^ 0x80
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ int code_at(const uint8_t* codes, size_t row, int C, int c, int bits) {
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
         const int cl = 16 * tile + 4 * q + e;
         int v = 0;
         if (t < T && cl < d && slot_of[t] < 0) v = code_at(k_code, (size_t)b * T + t, C, h * d + cl, bits);
-        img[I.kp + i] = (uint8_t)(v & 0xFF);
+        img[I.kp + kp_offset(I.tph, t, tile, q) + e] = (uint8_t)(v & 0xFF);
     }
     for (int i = tid; i < d * I.cols_v; i += nth) {
         const int p = i % I.cols_v, j = i / I.cols_v;
@@ -675,13 +676,16 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 int32x4_t acc[NTT];
 #pragma unroll
                 for (int nt = 0; nt < NTT; ++nt) acc[nt] = (int32x4_t){0, 0, 0, 0};
-                const int8_t* krow = kp + (16 * tt + r16) * (TPH * 16) + 4 * q;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     int32x4_t ka;
+                    if constexpr (TPH % 4 == 0) {  // the lane's 16 bytes of this K step are contiguous
+                        ka = *reinterpret_cast<const int32x4_t*>(kp + kp_offset(TPH, 16 * tt + r16, 4 * ks, q));
+                    } else {
 #pragma unroll
-                    for (int jj = 0; jj < 4; ++jj)
-                        ka[jj] = (4 * ks + jj < TPH) ? *reinterpret_cast<const int*>(krow + 16 * (4 * ks + jj)) : 0;
+                        for (int jj = 0; jj < 4; ++jj)
+                            ka[jj] = (4 * ks + jj < TPH) ? *reinterpret_cast<const int*>(kp + kp_offset(TPH, 16 * tt + r16, 4 * ks + jj, q)) : 0;
+                    }
 #pragma unroll
                     for (int nt = 0; nt < NTT; ++nt) acc[nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ka, qop[nt][ks], acc[nt], 0, 0, 0);
                 }

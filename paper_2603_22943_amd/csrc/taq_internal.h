@@ -44,7 +44,7 @@ struct KvImage {
     int tph;        // 16-channel tiles per head = ceil(d/16)
     int rows_k;     // 16*ceil(T/16) text-token rows of the K part
     int cols_v;     // 32*ceil(T/32) token positions per V^T row
-    size_t kp;      // i8  [rows_k][tph][4 quarter-lanes][4]  K codes in MFMA operand order
+    size_t kp;      // i8  [rows_k][tph][4 quarter-lanes][4]  K codes in MFMA operand order (see kp_offset)
     size_t vt;      // u8  [d][cols_v]   V codes (+128) transposed, tokens in accumulator-register order
     size_t s_k;     // f32 [96]  per-token K scale of this head, 0 on protected / padding tokens
     size_t s_vp;    // f32 [96]  s_V * 2^kexp
@@ -54,6 +54,17 @@ struct KvImage {
     size_t head_bytes;  // one head's block, a multiple of 256 bytes
     size_t bytes;   // H * head_bytes
 };
+
+// Byte offset, within the K part of a head block, of the 4 codes of text token t, 16-channel tile j, quarter q
+// (channels 16*j + 4*q .. +3 of the head). A lane of the score MFMA holds row t, quarter q and needs tiles
+// 4*ks .. 4*ks+3 for K step ks. When the head has a multiple of 4 tiles those 16 bytes are laid out contiguously,
+// [t][ks][q][tile%4][4], so that the lane reads them with one 16-byte LDS load and the 64 lanes of a wavefront hit
+// consecutive 16-byte slots (no bank conflicts; a 64-byte row of [t][tile][q][4] would put 16 rows on 2 bank
+// groups). Otherwise [t][tile][q][4].
+__host__ __device__ static inline size_t kp_offset(int tph, int t, int j, int q) {
+    if ((tph & 3) == 0) return ((((size_t)t * (tph >> 2) + (j >> 2)) * 4 + q) * 4 + (j & 3)) * 4;
+    return (((size_t)t * tph + j) * 4 + q) * 4;
+}
 
 static inline KvImage kv_image(const taq_shape& s) {
     KvImage I;

@@ -529,7 +529,7 @@ __global__ __launch_bounds__(512) void kv_head_kernel(const int8_t* __restrict__
             if (has_image) {
                 if (!side) {  // Kp[t][tile][quarter][4]; zeros past the head and past the last token
                     if (t < I.rows_k)
-                        *reinterpret_cast<unsigned*>(img + I.kp + (((size_t)t * I.tph + j) * 4 + q) * 4) = pack4_i8(c[0], c[1], c[2], c[3]);
+                        *reinterpret_cast<unsigned*>(img + I.kp + kp_offset(I.tph, t, j, q)) = pack4_i8(c[0], c[1], c[2], c[3]);
                 } else if (cl < d) {  // Vt[channel][pos], stored with the sign bit flipped
 #pragma unroll
                     for (int i = 0; i < 4; ++i) img[I.vt + (size_t)(cl + i) * I.cols_v + pos] = (uint8_t)((c[i] & 0xFF) ^ 0x80);
