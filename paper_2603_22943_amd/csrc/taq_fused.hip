@@ -1027,13 +1027,12 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
     const int N = dm.N, n0 = tile * 32;
     int8_t* tileq = reinterpret_cast<int8_t*>(smem);               // [32][C+16]
     float* s_o = reinterpret_cast<float*>(smem + 32 * TILE_RS);    // [32]
-    // weights first (they do not depend on the tile), then the tile
+    // The rows of the tile are requested first: they are needed first (quantizer), and loads return in order; the
+    // weights, needed only after the barrier, travel while the rows are quantized.
     const int cr = 16 * gt + r16;
     const int wrow = dm.w_layout ? (int)dm.w_pack_off + (gt * KC) * 1024 + lane * 16 : cr * C + 16 * q;
     const int wstep = dm.w_layout ? 1024 : 64;
     int32x4_t wa[KC];
-#pragma unroll
-    for (int ks = 0; ks < KC; ++ks) wa[ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow + wstep * ks);
     if constexpr (!FUSEQ) {
         for (int v = tid; v < 32 * (C / 16); v += NT) {
             const int tk = v / (C / 16), col = (v % (C / 16)) * 16;
@@ -1045,6 +1044,8 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
             const int nq = n0 + tid;
             s_o[tid] = dm.ws_so[(size_t)b * N + (nq < N ? nq : N - 1)];
         }
+#pragma unroll
+        for (int ks = 0; ks < KC; ++ks) wa[ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow + wstep * ks);
     } else {
         const int tk = tid >> 5, part = tid & 31;  // token of the tile, piece of its row
         const int nq = n0 + tk;
@@ -1055,6 +1056,10 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
         for (int it = 0; it < CH; ++it) xv[it] = xr[it * 32 + part];
         float amax = 0.f;
         for (int i = part; i < dm.omax_n; i += 32) amax = fmaxf(amax, dm.ws_omax[row * dm.omax_n + i]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < KC; ++ks) wa[ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow + wstep * ks);
+        __builtin_amdgcn_sched_barrier(0);
         amax = row16_allmax(amax);
         {   // the other 16 lanes of this token
             const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
