@@ -29,9 +29,6 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 
 #define TAQ_NEG_INF (-__builtin_inff())
 #define TAQ_MAX_REQ 16
-#ifndef TAQ_NTT_40
-#define TAQ_NTT_40 2  // column tiles of 16 tokens per wavefront in the d = 40 instantiation
-#endif
 
 __device__ __forceinline__ int symq_code_f(float x, float qmaxf, float amax) {
     float t = x * qmaxf;
@@ -177,7 +174,6 @@ struct FusedDims {
     float* ws_of;            // f32 [B*N][C]
     float* ws_omax;          // f32 [B*N][omax_n]  max |A^ V~| over each wavefront's share of a token's row
     int omax_n;              // partial maxima per token (heads x wavefronts per head and token group)
-    int group_fastest;       // head-group variant: 1 = consecutive workgroups differ in head group, 0 = in token tile
     const int8_t* ws_ocode;  // i8  [B*N][C]  per-token codes of A^ V~ when a separate kernel formed them (else NULL)
     const float* ws_so;      // f32 [B*N]     ... and their scales
 };
@@ -279,12 +275,10 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, hl = (tid >> 6) % NH, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
-    // Head-group variant: workgroups are handed to the 8 XCDs round-robin in launch order (x fastest). With
-    // dm.group_fastest the head group is the fastest index, so one XCD's L2 holds one group's weight slice and image
-    // (NG = 8); otherwise the token tile is, and an XCD's L2 holds few tiles of `hidden` and all weights.
-    const int lin = NG > 1 ? (int)(blockIdx.y * gridDim.x + blockIdx.x) : (int)blockIdx.x;
-    const int bx = NG > 1 ? (dm.group_fastest ? lin / NG : lin % (int)gridDim.x) : lin;   // (token tile, batch) index
-    const int by = NG > 1 ? (dm.group_fastest ? lin % NG : lin / (int)gridDim.x) : 0;     // head group
+    // Head-group variant: blockIdx.y is the head group (the order in which workgroups meet the 8 XCDs, head group
+    // fastest or token tile fastest, made no measurable difference at these sizes).
+    const int bx = (int)blockIdx.x;              // (token tile, batch / request) index
+    const int by = NG > 1 ? (int)blockIdx.y : 0;  // head group
     const int h = by * NH + hl;  // head of the layer; hl = head within the workgroup
     const int tbase = (((tid >> 6) / NH) % F::G) * 16 * NTT;  // first tile row of this wavefront's tokens
     const int sub = SUB == 1 ? 0 : (tid >> 6) / (NH * F::G);  // which share of the channel tiles of A^ V~
@@ -1161,13 +1155,12 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.ws_of = nullptr;
     dm.ws_omax = nullptr;
     dm.omax_n = 0;
-    dm.group_fastest = 0;
     // 32-token tiles that would occupy under half of the 256 compute units: 16-token workgroups instead
     // (TAQ_FUSED_TOKENS=32 or 16 in the environment forces one variant: for tests and tuning)
     bool few = ((s.N + 31) / 32) * R * s.B <= 128;
     if (const char* force = getenv("TAQ_FUSED_TOKENS")) few = atoi(force) == 16 ? true : atoi(force) == 32 ? false : few;
     if (d == 40 && s.H == 8)
-        return few ? launch_fused_cfg<40, 8, 1, 1, 16>(tab, dm, s.prob_grid, st) : launch_fused_cfg<40, 8, TAQ_NTT_40, 1>(tab, dm, s.prob_grid, st);
+        return few ? launch_fused_cfg<40, 8, 1, 1, 16>(tab, dm, s.prob_grid, st) : launch_fused_cfg<40, 8, 2, 1>(tab, dm, s.prob_grid, st);
     if (d == 80 && s.H == 8)
         return few ? launch_fused_cfg<80, 8, 1, 1, 16>(tab, dm, s.prob_grid, st) : launch_fused_cfg<80, 8, 2, 1>(tab, dm, s.prob_grid, st);
     if (d == 64 && s.H == 10)
@@ -1208,7 +1201,6 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, float* o_f, 
     dm.ws_of = o_f;
     dm.ws_omax = o_max;
     dm.omax_n = mid_omax_n(s);
-    dm.group_fastest = 0;  // (measured: no difference between the two orders at these sizes)
     if (d == 160 && s.H == 8) return launch_fused_cfg<160, 1, 1, 8>(tab, dm, s.prob_grid, st);
     if (d == 64 && s.H == 20) return launch_fused_cfg<64, 2, 1, 10>(tab, dm, s.prob_grid, st);
     return hipErrorInvalidValue;
