@@ -230,8 +230,15 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
         TAQ_TRY_HIP(launch_gemm_i8(h_code, s_h, Wq, s_wq, nullptr, M, s.C, s.C, q_f, nullptr, s.C, st));
     if (stages & TAQ_STAGE_Q_QUANT)
         TAQ_TRY_HIP(launch_headquant_f32(q_f, M, s.C, s.H, s.bits_q, q_code, s_q, st));
-    if (stages & TAQ_STAGE_ATTN_CORE)
-        TAQ_TRY_HIP(launch_attn_core(q_code, s_q, static_cast<const uint8_t*>(qkv_packed), s, o_f, st));
+    if (stages & TAQ_STAGE_ATTN_CORE) {
+        if (fused_supported(s)) {  // (only reached when profiling by stage) the attention phases of the single kernel, alone
+            FusedReq rq = {static_cast<const __half*>(hidden), static_cast<const uint8_t*>(qkv_packed), Wq, Wo, scales,
+                           static_cast<__half*>(out)};
+            TAQ_TRY_HIP(launch_fused_block(&rq, 1, s, nullptr, st, q_code, s_q, o_f));
+        } else {
+            TAQ_TRY_HIP(launch_attn_core(q_code, s_q, static_cast<const uint8_t*>(qkv_packed), s, o_f, st));
+        }
+    }
     if (stages & TAQ_STAGE_O_QUANT)
         TAQ_TRY_HIP(launch_rowquant_f32(o_f, M, s.C, o_code, s_o, st));
     if (stages & TAQ_STAGE_TO_OUT)

@@ -174,6 +174,8 @@ struct FusedDims {
     float* ws_of;            // f32 [B*N][C]
     float* ws_omax;          // f32 [B*N][omax_n]  max |A^ V~| over each wavefront's share of a token's row
     int omax_n;              // partial maxima per token (heads x wavefronts per head and token group)
+    const int8_t* core_qcode;  // i8  [B*N][C]  Q~ codes (attention-core-only variant)
+    const float* core_sq;      // f32 [B*N][H]  ... and their scales
     const int8_t* ws_ocode;  // i8  [B*N][C]  per-token codes of A^ V~ when a separate kernel formed them (else NULL)
     const float* ws_so;      // f32 [B*N]     ... and their scales
 };
@@ -260,15 +262,18 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // (A operands shared by both tiles). NTT = 1: two wavefronts per head, one tile each (16 wavefronts per CU
 // instead of 8: more latency hiding for twice the A-operand traffic). TOK = 16 (with NTT = 1): one wavefront per
 // head and half the tokens, for layers whose 32-token tiles would leave most compute units without a workgroup.
+// CORE: only the attention core (profiling by stage): Q~ codes and scales come from the workspace instead of the
+// hidden tile and to_q, and the kernel stops after writing A^ V~ as float32.
 // NG > 1 (layers too wide for one workgroup's LDS): the workgroup owns one head group (NH of the NH*NG
 // heads), takes the per-token codes of `hidden` from the workspace, and stops after A^ V~, which it writes to
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
-template <int D, int NH, int NTT, int NG, int PG, int TOK = 32>
+template <int D, int NH, int NTT, int NG, int PG, int TOK = 32, bool CORE = false>
 __global__ __launch_bounds__(64 * NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1))
 __attribute__((amdgpu_waves_per_eu(1, TOK == 16 ? 4 : (NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
     using F = FusedCfg<D, NH, NTT, NG, TOK>;
     static_assert(TOK == 32 || (TOK == 16 && NTT == 1 && NG == 1), "a workgroup owns 32 image tokens, or 16 with one tile per wavefront");
+    static_assert(!CORE || NG == 1, "the attention-core-only variant exists for the single-kernel shapes");
     constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
     constexpr int SUB = F::SUB, TPS = F::TPS;
     constexpr bool LOGP = PG == TAQ_PROB_LOG2, ROWMAX = PG == TAQ_PROB_ROWMAX;  // grid of the probabilities, Eq. (3)
@@ -313,7 +318,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         wrow[j] = dm.w_layout ? (int)dm.w_pack_off + ((h * TPH + j) * KC) * 1024 + lane * 16 : (c < C ? c : C - 1) * C + 16 * q;
     }
     int32x4_t wreg[F::PREFETCH_W ? TPH : 1][F::PREFETCH_W ? KC : 1];
-    if constexpr (NG == 1) {
+    if constexpr (NG == 1 && !CORE) {
         // ---- phase 0: issue every global read up front, oldest first in the order of use (loads return in
         // order): hidden tile, weight scales, this head's to_q weight slice, the K~/V~ image
         const int tok0 = tid >> 4, part0 = tid & 15;  // 16 threads per token, 4 channels per load (first 16*TOK threads)
@@ -509,7 +514,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 
     // ================= to_q for this head: Qf^T[c][n]
     int32x4_t hb[NTT][NG == 1 ? KC : 1];
-    if constexpr (NG == 1) {
+    if constexpr (NG == 1 && !CORE) {
 #pragma unroll
         for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
@@ -517,7 +522,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
     }
     int32x4_t pacc[NTT][TPH];
-    if constexpr (F::PREFETCH_W) {
+    if constexpr (CORE) {
+        // no projection: Q~ comes from the workspace
+    } else if constexpr (F::PREFETCH_W) {
 #pragma unroll
         for (int j = 0; j < TPH; ++j) {
 #pragma unroll
@@ -582,14 +589,16 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     // Everything the Q~ step reads from LDS is fetched now, so that no LDS access sits between the issue of the
     // image copy below and the wait for it (the compiler orders LDS accesses after outstanding direct-to-LDS loads).
     float4 wq4[TPH];
-#pragma unroll
-    for (int j = 0; j < TPH; ++j) {
-        const int cl = 16 * j + 4 * q;
-        wq4[j] = *reinterpret_cast<const float4*>((NG == 1 ? swq + h * D : wsc + hl * D) + (((16 * j + 16 <= D) || cl < D) ? cl : 0));
-    }
     float shv[NTT];
+    if constexpr (!CORE) {
 #pragma unroll
-    for (int nt = 0; nt < NTT; ++nt) shv[nt] = s_h[tbase + 16 * nt + r16];
+        for (int j = 0; j < TPH; ++j) {
+            const int cl = 16 * j + 4 * q;
+            wq4[j] = *reinterpret_cast<const float4*>((NG == 1 ? swq + h * D : wsc + hl * D) + (((16 * j + 16 <= D) || cl < D) ? cl : 0));
+        }
+#pragma unroll
+        for (int nt = 0; nt < NTT; ++nt) shv[nt] = s_h[tbase + 16 * nt + r16];
+    }
     // This head's block of the K~/V~ image: straight into LDS, 1 KiB per wavefront-wide load (LDS address =
     // base + lane * 16), no registers in between; it travels while to_q and Q~ are computed, and only this
     // wavefront reads it, so only this wavefront waits for it. The last piece may be fetched more than once.
@@ -611,6 +620,15 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     float sq2[NTT];
 #pragma unroll
     for (int nt = 0; nt < NTT; ++nt) {
+        if constexpr (CORE) {  // Q~ codes (one per byte) and per-(token, head) scales as a separate kernel formed them
+#pragma unroll
+            for (int j = 0; j < TPH; ++j) {
+                const int cl = 16 * j + 4 * q;
+                qpk[nt][j] = cl < D ? *reinterpret_cast<const unsigned*>(dm.core_qcode + tok[nt] * C + h * D + cl) : 0u;
+            }
+            sq2[nt] = fmaxf(dm.core_sq[tok[nt] * H + h] * dm.sig2, 1e-37f);
+            continue;
+        }
         const float sh = shv[nt];
         float qf[TPH][4];
         float qmax = 0.f;
@@ -645,7 +663,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 
     // the head's image block travelled meanwhile; it is private to this wavefront: wait (vmcnt(0)), no barrier
     __builtin_amdgcn_s_waitcnt(0x0F70);
-    if (F::PREFETCH_W) {  // to_out's weight slice travels while the attention runs
+    if (F::PREFETCH_W && !CORE) {  // to_out's weight slice travels while the attention runs
 #pragma unroll
         for (int j = 0; j < TPH; ++j)
 #pragma unroll
@@ -929,15 +947,15 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             if (nvalid[nt] && valid) {
                 const float4 o4 = make_float4(oacc[nt][k][0], oacc[nt][k][1], oacc[nt][k][2], oacc[nt][k][3]);
                 if (dm.dbg.O) *reinterpret_cast<float4*>(dm.dbg.O + tok[nt] * C + h * D + 16 * jt + 4 * q) = o4;
-                if constexpr (NG > 1) *reinterpret_cast<float4*>(dm.ws_of + tok[nt] * C + h * D + 16 * jt + 4 * q) = o4;
+                if constexpr (NG > 1 || CORE) *reinterpret_cast<float4*>(dm.ws_of + tok[nt] * C + h * D + 16 * jt + 4 * q) = o4;
             }
         }
         omx = quad_allmax(omx);
-        if (NG == 1 && q == 0) omax[(tbase + 16 * nt + r16) * NH + hl] = __float_as_uint(omx);
+        if (NG == 1 && !CORE && q == 0) omax[(tbase + 16 * nt + r16) * NH + hl] = __float_as_uint(omx);
         // head-group variant: this wavefront's share of the token's row maximum, for the kernel that quantizes the row
         if (NG > 1 && q == 0 && nvalid[nt]) dm.ws_omax[tok[nt] * (H * SUB) + h * SUB + sub] = omx;
     }
-    if constexpr (NG > 1) return;  // the per-token quantization of A^ V~ and to_out are separate kernels
+    if constexpr (NG > 1 || CORE) return;  // the per-token quantization of A^ V~ and to_out are separate kernels
     __syncthreads();  // every wavefront is past its reads of the hidden codes
     float so[NTT];
 #pragma unroll
@@ -1107,7 +1125,7 @@ static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hi
     return hipGetLastError();
 }
 
-template <int D, int NH, int NTT, int NG, int PG, int TOK>
+template <int D, int NH, int NTT, int NG, int PG, int TOK, bool CORE>
 static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     using F = FusedCfg<D, NH, NTT, NG, TOK>;
     static std::atomic<unsigned long long> lds_set{0};
@@ -1115,22 +1133,24 @@ static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, 
                                  : (size_t)NH * dm.I.head_bytes + 32 * F::TILE_RS + NH * D * 4 + 32 * 4 +
                                        2 * NH * F::TPH * 1024;                                          // = mid_lds_bytes
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
-    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK>), 160 * 1024, lds_set);
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE>), 160 * 1024, lds_set);
     if (e != hipSuccess) return e;
     const int tiles = (dm.N + TOK - 1) / TOK;
-    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG, TOK>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
+    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 
-template <int D, int NH, int NTT, int NG, int TOK = 32>
+template <int D, int NH, int NTT, int NG, int TOK = 32, bool CORE = false>
 static hipError_t launch_fused_cfg(const FusedTable& tab, const FusedDims& dm, int grid, hipStream_t st) {
-    if (grid == TAQ_PROB_LOG2) return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_LOG2, TOK>(tab, dm, st);
-    if (grid == TAQ_PROB_ROWMAX) return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_ROWMAX, TOK>(tab, dm, st);
-    return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_LINEAR, TOK>(tab, dm, st);
+    if (grid == TAQ_PROB_LOG2) return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_LOG2, TOK, CORE>(tab, dm, st);
+    if (grid == TAQ_PROB_ROWMAX) return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_ROWMAX, TOK, CORE>(tab, dm, st);
+    return launch_fused_grid<D, NH, NTT, NG, TAQ_PROB_LINEAR, TOK, CORE>(tab, dm, st);
 }
 
-hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, const taq_debug* dbg, hipStream_t st) {
+hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, const taq_debug* dbg, hipStream_t st,
+                              const int8_t* core_qcode, const float* core_sq, float* core_of) {
     if (R < 1 || R > TAQ_MAX_REQ || !fused_supported(s)) return hipErrorInvalidValue;
+    if (core_qcode && (R != 1 || !core_sq || !core_of)) return hipErrorInvalidValue;
     FusedTable tab;
     for (int r = 0; r < TAQ_MAX_REQ; ++r) tab.req[r] = reqs[r < R ? r : 0];
     FusedDims dm;
@@ -1152,9 +1172,19 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.I = kv_image(s);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
     dm.dbg = (dbg && R == 1) ? *dbg : none;
-    dm.ws_of = nullptr;
+    dm.ws_of = core_of;
     dm.ws_omax = nullptr;
     dm.omax_n = 0;
+    dm.core_qcode = core_qcode;
+    dm.core_sq = core_sq;
+    dm.ws_ocode = nullptr;
+    dm.ws_so = nullptr;
+    if (core_qcode) {  // the attention core alone, from Q~ codes and scales in the workspace to float32 A^ V~
+        if (d == 40 && s.H == 8) return launch_fused_cfg<40, 8, 2, 1, 32, true>(tab, dm, s.prob_grid, st);
+        if (d == 80 && s.H == 8) return launch_fused_cfg<80, 8, 2, 1, 32, true>(tab, dm, s.prob_grid, st);
+        if (d == 64 && s.H == 10) return launch_fused_cfg<64, 10, 2, 1, 32, true>(tab, dm, s.prob_grid, st);
+        return hipErrorInvalidValue;
+    }
     // 32-token tiles that would occupy under half of the 256 compute units: 16-token workgroups instead
     // (TAQ_FUSED_TOKENS=32 or 16 in the environment forces one variant: for tests and tuning)
     bool few = ((s.N + 31) / 32) * R * s.B <= 128;
@@ -1201,6 +1231,10 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, float* o_f, 
     dm.ws_of = o_f;
     dm.ws_omax = o_max;
     dm.omax_n = mid_omax_n(s);
+    dm.core_qcode = nullptr;
+    dm.core_sq = nullptr;
+    dm.ws_ocode = nullptr;
+    dm.ws_so = nullptr;
     if (d == 160 && s.H == 8) return launch_fused_cfg<160, 1, 1, 8>(tab, dm, s.prob_grid, st);
     if (d == 64 && s.H == 20) return launch_fused_cfg<64, 2, 1, 10>(tab, dm, s.prob_grid, st);
     return hipErrorInvalidValue;

@@ -266,8 +266,10 @@ struct FusedReq {
     const float* scales;
     __half* out;
 };
-// Whole block in one kernel (shapes of fused_supported only). dbg may be NULL.
-hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, const taq_debug* dbg, hipStream_t st);
+// Whole block in one kernel (shapes of fused_supported only). dbg may be NULL. With core_qcode != NULL (R == 1) the
+// kernel runs the attention core alone: Q~ codes i8 [B*N][C] and scales f32 [B*N][H] in, float32 A^ V~ [B*N][C] out.
+hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, const taq_debug* dbg, hipStream_t st,
+                              const int8_t* core_qcode = nullptr, const float* core_sq = nullptr, float* core_of = nullptr);
 // Head-group path (shapes of mid_supported), two kernels: (1) per-token codes of `hidden`, to_q, Q~ and the attention
 // per head group, writing float32 A^ V~ [B*N][C] and partial row maxima [B*N][<= 40] to the workspace; (2) per-token
 // codes of A^ V~ and to_out (with o_code != NULL the codes come from the row quantizer kernel instead). Taps in `dbg`
