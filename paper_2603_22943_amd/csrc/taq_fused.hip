@@ -317,6 +317,12 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         const int c = h * D + 16 * j + r16;
         wrow[j] = dm.w_layout ? (int)dm.w_pack_off + ((h * TPH + j) * KC) * 1024 + lane * 16 : (c < C ? c : C - 1) * C + 16 * q;
     }
+    // Weight rows past the head (the upper lanes of a partly filled last tile) are not fetched: their products are
+    // dropped anyway, and at d = 40 they are a sixth of the bytes every CU pulls through its L2.
+    auto load_w = [&](const int8_t* base, int j, int off) -> int32x4_t {
+        if ((D % 16 == 0) || 16 * j + 16 <= D || r16 < D - 16 * j) return *reinterpret_cast<const int32x4_t*>(base + wrow[j] + off);
+        return (int32x4_t){0, 0, 0, 0};
+    };
     int32x4_t wreg[F::PREFETCH_W ? TPH : 1][F::PREFETCH_W ? KC : 1];
     if constexpr (NG == 1 && !CORE) {
         // ---- phase 0: issue every global read up front, oldest first in the order of use (loads return in
@@ -368,7 +374,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         for (int it = 0; it < KC; ++it) {
             if (F::PREFETCH_W) {
     #pragma unroll
-                for (int j = 0; j < TPH; ++j) wreg[j][it] = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + wstep * it);
+                for (int j = 0; j < TPH; ++j) wreg[j][it] = load_w(rq.wq, j, wstep * it);
             }
             if (tid < 16 * TOK) {
                 const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq0, safe0);
@@ -542,7 +548,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
             for (int ks = 0; ks < KC; ++ks) {
-                const int32x4_t wa = *reinterpret_cast<const int32x4_t*>(rq.wq + wrow[j] + wstep * ks);
+                const int32x4_t wa = load_w(rq.wq, j, wstep * ks);
 #pragma unroll
                 for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
             }
@@ -667,7 +673,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
         for (int j = 0; j < TPH; ++j)
 #pragma unroll
-            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + wstep * ks);
+            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = load_w(rq.wo, j, wstep * ks);
     }
 
 
@@ -991,7 +997,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < KC; ++ks) {
-            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : *reinterpret_cast<const int32x4_t*>(rq.wo + wrow[j] + wstep * ks);
+            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : load_w(rq.wo, j, wstep * ks);
 #pragma unroll
             for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
         }
