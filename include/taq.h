@@ -16,13 +16,15 @@
  *   - rows: K/V per (head, text token); Q per (image token, head); hidden states and
  *     the attention output per image token; weights per output channel (8 bit);
  *   - Q_a on probabilities is the fixed grid code = rint(pmax*A), A^ = code/pmax, pmax = 2^b - 1 (255 or 15);
+ *     shape->prob_grid selects a power-of-two grid or the row's own range instead;
  *   - to_q, to_out and the K/V projections of unprotected tokens are W8A8 integer
  *     contractions; protected K/V rows are computed from the unquantized fp16 context
  *     row (with the 8-bit weight codes) and stored as fp16.
  *
  * General rules
  *   - Every data pointer is DEVICE memory owned by the caller, 16-byte aligned, unless
- *     said otherwise. The library allocates nothing and keeps no state between calls.
+ *     said otherwise. The library allocates nothing and keeps no state between calls
+ *     (apart from remembering, per kernel and device, that a launch attribute was set).
  *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and return without waiting; the caller synchronises.
  *   - Return value: TAQ_OK (0) or a negative taq_status. On error nothing is launched.
