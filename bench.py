@@ -37,8 +37,8 @@ INT8_PEAK_TOPS = 5000.0  # dense int8 MFMA, published
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=512)
-    p.add_argument("--warmup", type=int, default=32)
+    p.add_argument("--steps", type=int, default=4096)   # 4096 steps of ~16 us: the timed region lasts ~65 ms
+    p.add_argument("--warmup", type=int, default=256)  # enough for the clocks to settle
     p.add_argument("--ring", type=int, default=16, help="distinct buffer sets cycled through")
     p.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     p.add_argument("--no-cpu-baseline", action="store_true")
