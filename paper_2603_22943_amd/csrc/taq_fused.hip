@@ -269,10 +269,10 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
 template <int D, int NH, int NTT, int NG, int PG, int TOK = 32, bool CORE = false>
 __global__ __launch_bounds__(64 * NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1))
-__attribute__((amdgpu_waves_per_eu(1, TOK == 16 ? 4 : (NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1) + 3) / 4)))
+__attribute__((amdgpu_waves_per_eu(1, TOK == 16 ? (NG > 1 ? 1 : 4) : (NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
     using F = FusedCfg<D, NH, NTT, NG, TOK>;
-    static_assert(TOK == 32 || (TOK == 16 && NTT == 1 && NG == 1), "a workgroup owns 32 image tokens, or 16 with one tile per wavefront");
+    static_assert(TOK == 32 || (TOK == 16 && NTT == 1), "a workgroup owns 32 image tokens, or 16 with one tile per wavefront");
     static_assert(!CORE || NG == 1, "the attention-core-only variant exists for the single-kernel shapes");
     constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
     constexpr int SUB = F::SUB, TPS = F::TPS;
@@ -301,7 +301,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     float* wsc = reinterpret_cast<float*>(smem + img_bytes + TOK * F::TILE_RS);  // s_wq | s_wo | bias_o  [3C]
     float* s_h = wsc + (NG == 1 ? 3 * C : NH * D);               // [TOK]  (NG > 1: only s_wq of the workgroup's heads)
     unsigned* omax = reinterpret_cast<unsigned*>(s_h + TOK);     // [TOK][NH]  (NG == 1)
-    int* qacc = reinterpret_cast<int*>(s_h + TOK);               // [2][NH*TPH][64][4] to_q accumulators (NG > 1)
+    int* qacc = reinterpret_cast<int*>(s_h + TOK);               // [K ranges][TOK/16][NH*TPH][64][4] partial to_q sums (NG > 1)
 
     const uint8_t* packed = rq.packed;
     const int ntrig = reinterpret_cast<const int*>(packed + dm.L.ntrig)[b];
@@ -394,13 +394,15 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     // ---- head-group variant, phase 0: every global read of the first two phases is issued up front, oldest first in
     // the order of use: the hidden tile, this wavefront's share of the to_q weights, the K~/V~ image blocks
     constexpr int TW = NH * TPH;                       // weight tiles (16 output channels) of this workgroup
-    constexpr int TJ = NG > 1 ? TW / 2 : 1;            // ... per wavefront: two tile groups x
-    constexpr int KW = NG > 1 ? KC / 4 : 1;            // ... four K ranges of KW steps
+    constexpr int KP = NG > 1 ? NT / 128 : 1;          // the wavefronts split to_q into two tile groups x KP K ranges
+    constexpr int N2 = TOK / 16;                       // token groups of 16, all covered by every wavefront's share
+    constexpr int TJ = NG > 1 ? TW / 2 : 1;            // weight tiles per tile group
+    constexpr int KW = NG > 1 ? KC / KP : 1;           // K steps per K range
     constexpr int IMV = NG > 1 ? (NH * F::IMGC * 64 + NT - 1) / NT : 1;
     int32x4_t wpre[TJ][KW];
     int32x4_t imv[IMV];
     if constexpr (NG > 1) {
-        static_assert(NG == 1 || (TW % 2 == 0 && KC % 4 == 0 && C % 128 == 0 && NT == 512), "head-group split");
+        static_assert(NG == 1 || (TW % 2 == 0 && KC % KP == 0 && C % 128 == 0 && NT == 16 * TOK), "head-group split");
         constexpr int CH = C / 128;  // 16-byte pieces of a hidden row per thread (16 threads per token)
         const int wv = tid >> 6, js = wv & 1, kp = wv >> 1;
         const int tok0 = tid >> 4, part0 = tid & 15;
@@ -414,7 +416,6 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         }
         float4 swv = make_float4(0.f, 0.f, 0.f, 0.f);  // s_wq of this workgroup's heads: NH*D floats
         if (tid < NH * D / 4) swv = reinterpret_cast<const float4*>(rq.scales + (size_t)by * NH * D)[tid];
-        for (int i = tid; i < 2 * TW * 64; i += NT) reinterpret_cast<uint4*>(qacc)[i] = make_uint4(0, 0, 0, 0);
         // ---- per-token int8 codes of the hidden tile (every head group of a token tile computes the same codes)
         float amax = 0.f;
 #pragma unroll
@@ -554,30 +555,29 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             }
         }
     } else {
-        // Head-group variant: the eight wavefronts split the workgroup's to_q by weight tile group (js) and K range
-        // (kp), each for all 32 tokens; the int32 partial sums meet in LDS (integer adds: exact in any order), and
-        // every wavefront then picks up the finished accumulators of its own (head, token group).
+        // Head-group variant: the wavefronts split the workgroup's to_q by weight tile group (js) and K range (kp),
+        // each for all of the workgroup's tokens; every wavefront leaves its int32 partial sums in a slot of its own
+        // in LDS, and then adds up the KP partial sums of its own (head, token group): integer adds, exact in any order.
         const int wv = tid >> 6, js = wv & 1, kp = wv >> 1;
         load_protected();  // needed only after the second barrier: they travel during the MFMAs
-        int32x4_t hb2[2][KW];
+        int32x4_t hb2[N2][KW];
 #pragma unroll
-        for (int n2 = 0; n2 < 2; ++n2)
+        for (int n2 = 0; n2 < N2; ++n2)
 #pragma unroll
             for (int kk = 0; kk < KW; ++kk)
                 hb2[n2][kk] = *reinterpret_cast<const int32x4_t*>(tileq + (16 * n2 + r16) * F::TILE_RS + 64 * (kp * KW + kk) + 16 * q);
 #pragma unroll
         for (int jj = 0; jj < TJ; ++jj) {
-            int32x4_t a2[2] = {(int32x4_t){0, 0, 0, 0}, (int32x4_t){0, 0, 0, 0}};
+            int32x4_t a2[N2];
+#pragma unroll
+            for (int n2 = 0; n2 < N2; ++n2) a2[n2] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
             for (int kk = 0; kk < KW; ++kk)
 #pragma unroll
-                for (int n2 = 0; n2 < 2; ++n2) a2[n2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wpre[jj][kk], hb2[n2][kk], a2[n2], 0, 0, 0);
+                for (int n2 = 0; n2 < N2; ++n2) a2[n2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wpre[jj][kk], hb2[n2][kk], a2[n2], 0, 0, 0);
 #pragma unroll
-            for (int n2 = 0; n2 < 2; ++n2) {
-                int* dst = qacc + ((n2 * TW + js * TJ + jj) * 64 + lane) * 4;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) __hip_atomic_fetch_add(dst + i, a2[n2][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
+            for (int n2 = 0; n2 < N2; ++n2)
+                *reinterpret_cast<int32x4_t*>(qacc + (((kp * N2 + n2) * TW + js * TJ + jj) * 64 + lane) * 4) = a2[n2];
         }
         {   // the K~/V~ image blocks (read into registers in phase 0) go to LDS
             const int img16 = (int)((NH * dm.I.head_bytes) >> 4);
@@ -589,8 +589,12 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         }
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < TPH; ++j)
+        for (int j = 0; j < TPH; ++j) {
             pacc[0][j] = *reinterpret_cast<const int32x4_t*>(qacc + (((tbase >> 4) * TW + hl * TPH + j) * 64 + lane) * 4);
+#pragma unroll
+            for (int p = 1; p < KP; ++p)
+                pacc[0][j] += *reinterpret_cast<const int32x4_t*>(qacc + (((p * N2 + (tbase >> 4)) * TW + hl * TPH + j) * 64 + lane) * 4);
+        }
     }
     // Everything the Q~ step reads from LDS is fetched now, so that no LDS access sits between the issue of the
     // image copy below and the wait for it (the compiler orders LDS accesses after outstanding direct-to-LDS loads).
@@ -1136,8 +1140,8 @@ static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, 
     using F = FusedCfg<D, NH, NTT, NG, TOK>;
     static std::atomic<unsigned long long> lds_set{0};
     const size_t bytes = NG == 1 ? dm.I.bytes + TOK * F::TILE_RS + 3 * F::C * 4 + TOK * 4 + TOK * NH * 4  // = fused_lds_bytes
-                                 : (size_t)NH * dm.I.head_bytes + 32 * F::TILE_RS + NH * D * 4 + 32 * 4 +
-                                       2 * NH * F::TPH * 1024;                                          // = mid_lds_bytes
+                                 : (size_t)NH * dm.I.head_bytes + TOK * F::TILE_RS + NH * D * 4 + TOK * 4 +
+                                       (F::NT / 128) * (TOK / 16) * NH * F::TPH * 1024;  // = mid_lds_bytes at TOK = 32
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE>), 160 * 1024, lds_set);
     if (e != hipSuccess) return e;
@@ -1241,8 +1245,14 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, float* o_f, 
     dm.core_sq = nullptr;
     dm.ws_ocode = nullptr;
     dm.ws_so = nullptr;
-    if (d == 160 && s.H == 8) return launch_fused_cfg<160, 1, 1, 8>(tab, dm, s.prob_grid, st);
-    if (d == 64 && s.H == 20) return launch_fused_cfg<64, 2, 1, 10>(tab, dm, s.prob_grid, st);
+    // 32-token tiles that would leave compute units without a workgroup: 16-token workgroups of four wavefronts instead
+    // (TAQ_FUSED_TOKENS=32 or 16 in the environment forces one variant: for tests and tuning)
+    bool few = ((s.N + 31) / 32) * s.B * (d == 160 ? 8 : 10) <= 256;
+    if (const char* force = getenv("TAQ_FUSED_TOKENS")) few = atoi(force) == 16 ? true : atoi(force) == 32 ? false : few;
+    if (d == 160 && s.H == 8)
+        return few ? launch_fused_cfg<160, 1, 1, 8, 16>(tab, dm, s.prob_grid, st) : launch_fused_cfg<160, 1, 1, 8>(tab, dm, s.prob_grid, st);
+    if (d == 64 && s.H == 20)
+        return few ? launch_fused_cfg<64, 2, 1, 10, 16>(tab, dm, s.prob_grid, st) : launch_fused_cfg<64, 2, 1, 10>(tab, dm, s.prob_grid, st);
     return hipErrorInvalidValue;
 }
 

@@ -115,7 +115,8 @@ static inline bool fused_supported(const taq_shape& s) {
 static inline size_t mid_lds_bytes(const taq_shape& s) {
     const int d = s.C / s.H;
     const size_t nh = d == 160 ? 1 : 2;
-    return nh * kv_image(s).head_bytes + 32 * ((size_t)s.C + 16) + nh * d * 4 + 32 * 4 + 2 * nh * (size_t)((d + 15) / 16) * 1024;
+    // image blocks | 32 token rows of codes | s_wq of the heads | s_h | partial to_q sums [4 K ranges][2 token groups][tiles][1 KiB]
+    return nh * kv_image(s).head_bytes + 32 * ((size_t)s.C + 16) + nh * d * 4 + 32 * 4 + 8 * nh * (size_t)((d + 15) / 16) * 1024;
 }
 static inline bool mid_supported(const taq_shape& s) {
     if (s.bits_kv != 4 && s.bits_kv != 8) return false;

@@ -425,10 +425,11 @@ def test_rowmax_probability_grid_when_a_trigger_takes_the_whole_row():
 
 
 @pytest.mark.parametrize("tokens", ["32", "16"])
-@pytest.mark.parametrize("C,H,N,T_,bits_kv", [(640, 8, 45, 77, 8), (640, 10, 70, 50, 4), (640, 8, 130, 33, 4), (320, 8, 150, 77, 8)])
+@pytest.mark.parametrize("C,H,N,T_,bits_kv", [(640, 8, 45, 77, 8), (640, 10, 70, 50, 4), (640, 8, 130, 33, 4), (320, 8, 150, 77, 8),
+                                              (1280, 8, 45, 77, 8), (1280, 8, 70, 40, 4), (1280, 20, 90, 77, 4), (1280, 20, 33, 96, 8)])
 def test_fused_kernel_both_workgroup_sizes(C, H, N, T_, bits_kv, tokens, monkeypatch):
-    """Single-kernel layers run with 32-token workgroups when that fills the chip and with 16-token workgroups otherwise;
-    both variants are forced here on the same small layers and must give bit-identical outputs."""
+    """Single-kernel and head-group layers run with 32-token workgroups when that fills the chip and with 16-token
+    workgroups otherwise; both variants are forced here on the same small layers and must give bit-identical outputs."""
     L = synth.make_layer("tok", seed=C + H + N, B=2, N=N, C=C, H=H, Cc=64, T=T_, bits_kv=bits_kv,
                          trigger_positions=(1, T_ - 1), trigger_scale=3.0, bias=True)
     monkeypatch.setenv("TAQ_FUSED_TOKENS", tokens)
