@@ -193,7 +193,9 @@ struct FusedCfg {
     // of A^ V~, and all eight wavefronts of the workgroup split to_q by weight tile and K range.
     static constexpr int SUB = NG > 1 ? 4 / NH : 1;
     static constexpr int TPS = (TPH + SUB - 1) / SUB;  // channel tiles of A^ V~ per wavefront
-    static constexpr int NT = 64 * NH * G * SUB;  // threads
+    static constexpr int ROLES = NH * G * SUB;    // wavefronts with a (head, token group, channel share) of the attention
+    static constexpr int NT = NG > 1 ? 512 : 64 * ROLES;  // threads (head-group variant: always eight wavefronts for the
+                                                          // hidden codes and to_q; those without a role stop after to_q)
     static constexpr int TILE_RS = C + 16;        // bytes per token row of the int8 tile
     // bytes of one head's image block at T = 96, in 1 KiB pieces (one direct-to-LDS load each)
     static constexpr int IMG_HEAD_MAX = 96 * TPH * 16 + D * 96 + 3 * 96 * 4 + 32;
@@ -268,8 +270,8 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // heads), takes the per-token codes of `hidden` from the workspace, and stops after A^ V~, which it writes to
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
 template <int D, int NH, int NTT, int NG, int PG, int TOK = 32, bool CORE = false>
-__global__ __launch_bounds__(64 * NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1))
-__attribute__((amdgpu_waves_per_eu(1, TOK == 16 ? (NG > 1 ? 1 : 4) : (NH * (TOK / (16 * NTT)) * (NG > 1 ? 4 / NH : 1) + 3) / 4)))
+__global__ __launch_bounds__(NG > 1 ? 512 : 64 * NH * (TOK / (16 * NTT)))
+__attribute__((amdgpu_waves_per_eu(1, NG > 1 ? 2 : TOK == 16 ? 4 : (NH * (TOK / (16 * NTT)) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
     using F = FusedCfg<D, NH, NTT, NG, TOK>;
     static_assert(TOK == 32 || (TOK == 16 && NTT == 1), "a workgroup owns 32 image tokens, or 16 with one tile per wavefront");
@@ -402,17 +404,18 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     int32x4_t wpre[TJ][KW];
     int32x4_t imv[IMV];
     if constexpr (NG > 1) {
-        static_assert(NG == 1 || (TW % 2 == 0 && KC % KP == 0 && C % 128 == 0 && NT == 16 * TOK), "head-group split");
-        constexpr int CH = C / 128;  // 16-byte pieces of a hidden row per thread (16 threads per token)
+        constexpr int TPT = NT / TOK;        // threads per token: 16 or 32
+        constexpr int CH = C / (8 * TPT);    // 16-byte pieces of a hidden row per thread
+        static_assert(NG == 1 || (TW % 2 == 0 && KC % KP == 0 && C % (8 * TPT) == 0 && (TPT == 16 || TPT == 32)), "head-group split");
         const int wv = tid >> 6, js = wv & 1, kp = wv >> 1;
-        const int tok0 = tid >> 4, part0 = tid & 15;
+        const int tok0 = tid / TPT, part0 = tid % TPT;
         const int nq0 = n0 + tok0;
         const size_t row0 = (size_t)b * N + (nq0 < N ? nq0 : N - 1);
         uint4 xin[CH];
         {
             const uint4* xr = reinterpret_cast<const uint4*>(rq.hidden + row0 * C);
 #pragma unroll
-            for (int it = 0; it < CH; ++it) xin[it] = xr[it * 16 + part0];
+            for (int it = 0; it < CH; ++it) xin[it] = xr[it * TPT + part0];
         }
         float4 swv = make_float4(0.f, 0.f, 0.f, 0.f);  // s_wq of this workgroup's heads: NH*D floats
         if (tid < NH * D / 4) swv = reinterpret_cast<const float4*>(rq.scales + (size_t)by * NH * D)[tid];
@@ -432,6 +435,10 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         // unit's queue is full, so the requests are spread under the ALU work.
         __builtin_amdgcn_sched_barrier(0);
         amax = row16_allmax(amax);
+        if constexpr (TPT == 32) {  // the other 16 lanes of this token
+            const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
+            amax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        }
         const bool zero0 = amax == 0.f;
         const float sc0 = zero0 ? 1.f : amax / 127.f;
         const float safe0 = zero0 ? 1.f : amax;
@@ -467,8 +474,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             uint2 pk;
             pk.x = quant4_i8(p0.x, p0.y, p1.x, p1.y, cq0, safe0);
             pk.y = quant4_i8(p2.x, p2.y, p3.x, p3.y, cq0, safe0);
-            *reinterpret_cast<uint2*>(tileq + tok0 * F::TILE_RS + (it * 16 + part0) * 8) = pk;
-            if (tap && dm.dbg.h_code) *reinterpret_cast<uint2*>(dm.dbg.h_code + row0 * C + (it * 16 + part0) * 8) = pk;
+            *reinterpret_cast<uint2*>(tileq + tok0 * F::TILE_RS + (it * TPT + part0) * 8) = pk;
+            if (tap && dm.dbg.h_code) *reinterpret_cast<uint2*>(dm.dbg.h_code + row0 * C + (it * TPT + part0) * 8) = pk;
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -559,7 +566,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         // each for all of the workgroup's tokens; every wavefront leaves its int32 partial sums in a slot of its own
         // in LDS, and then adds up the KP partial sums of its own (head, token group): integer adds, exact in any order.
         const int wv = tid >> 6, js = wv & 1, kp = wv >> 1;
-        load_protected();  // needed only after the second barrier: they travel during the MFMAs
+        if (sub < SUB) load_protected();  // needed only after the second barrier: they travel during the MFMAs
         int32x4_t hb2[N2][KW];
 #pragma unroll
         for (int n2 = 0; n2 < N2; ++n2)
@@ -588,6 +595,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             }
         }
         __syncthreads();
+        if (sub >= SUB) return;  // 16-token variant: only ROLES of the eight wavefronts carry on (no barrier follows)
 #pragma unroll
         for (int j = 0; j < TPH; ++j) {
             pacc[0][j] = *reinterpret_cast<const int32x4_t*>(qacc + (((tbase >> 4) * TW + hl * TPH + j) * 64 + lane) * 4);
