@@ -201,6 +201,11 @@ struct FusedCfg {
     static constexpr int IMG_HEAD_MAX = 96 * TPH * 16 + D * 96 + 3 * 96 * 4 + 32;
     static constexpr int IMGC = (IMG_HEAD_MAX + 1023) / 1024;
     static constexpr bool PREFETCH_W = TPH * KC <= 16 && NTT == 2 && NG == 1;  // a head's whole weight slice in registers
+    // Otherwise (one token tile per wavefront: registers to spare) a ring of RING weight loads stays in flight ahead of
+    // the projection MFMAs; left to itself the compiler keeps one to ten loads ahead and the loop waits on latency.
+    static constexpr int NF = TPH * KC;  // weight loads (16 rows x 64 bytes) of one projection per wavefront
+    static constexpr int RING_MAX = NH <= 8 ? 32 : 12;  // two wavefronts per SIMD (256 registers each), or three (168)
+    static constexpr int RING = (!PREFETCH_W && NG == 1 && NTT == 1) ? (NF < RING_MAX ? NF : RING_MAX) : 0;
 };
 
 // Symmetric 8-bit codes of four values of one row, packed into a dword (low byte first).
@@ -271,7 +276,7 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
 template <int D, int NH, int NTT, int NG, int PG, int TOK = 32, bool CORE = false>
 __global__ __launch_bounds__(NG > 1 ? 512 : 64 * NH * (TOK / (16 * NTT)))
-__attribute__((amdgpu_waves_per_eu(1, NG > 1 ? 2 : TOK == 16 ? 4 : (NH * (TOK / (16 * NTT)) + 3) / 4)))
+__attribute__((amdgpu_waves_per_eu(1, NG > 1 ? 2 : (NH * (TOK / (16 * NTT)) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
     using F = FusedCfg<D, NH, NTT, NG, TOK>;
     static_assert(TOK == 32 || (TOK == 16 && NTT == 1), "a workgroup owns 32 image tokens, or 16 with one tile per wavefront");
@@ -326,6 +331,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         return (int32x4_t){0, 0, 0, 0};
     };
     int32x4_t wreg[F::PREFETCH_W ? TPH : 1][F::PREFETCH_W ? KC : 1];
+    constexpr int RING = CORE ? 0 : F::RING, NF = F::NF;
+    constexpr int RPS = RING ? (RING + KC - 1) / KC : 0;  // ring loads issued per step of the hidden quantizer
+    int32x4_t wring[RING ? RING : 1];
     if constexpr (NG == 1 && !CORE) {
         // ---- phase 0: issue every global read up front, oldest first in the order of use (loads return in
         // order): hidden tile, weight scales, this head's to_q weight slice, the K~/V~ image
@@ -377,6 +385,10 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             if (F::PREFETCH_W) {
     #pragma unroll
                 for (int j = 0; j < TPH; ++j) wreg[j][it] = load_w(rq.wq, j, wstep * it);
+            }
+            if constexpr (RING > 0) {  // the first RING loads of to_q, in the order the MFMAs use them
+    #pragma unroll
+                for (int f = it * RPS; f < (it + 1) * RPS && f < RING; ++f) wring[f] = load_w(rq.wq, f / KC, wstep * (f % KC));
             }
             if (tid < 16 * TOK) {
                 const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq0, safe0);
@@ -556,9 +568,14 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
             for (int ks = 0; ks < KC; ++ks) {
-                const int32x4_t wa = load_w(rq.wq, j, wstep * ks);
+                const int f = j * KC + ks;
+                const int32x4_t wa = RING ? wring[RING ? f % RING : 0] : load_w(rq.wq, j, wstep * ks);
 #pragma unroll
                 for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
+                if constexpr (RING > 0) {  // the slot is free again: the load RING places ahead takes it
+                    if (f + RING < NF) wring[f % RING] = load_w(rq.wq, (f + RING) / KC, wstep * ((f + RING) % KC));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
     } else {
@@ -686,6 +703,10 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         for (int j = 0; j < TPH; ++j)
 #pragma unroll
             for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = load_w(rq.wo, j, wstep * ks);
+    }
+    if constexpr (RING > 0) {  // ... or its first RING loads
+#pragma unroll
+        for (int f = 0; f < RING; ++f) wring[f] = load_w(rq.wo, f / KC, wstep * (f % KC));
     }
 
 
@@ -1009,9 +1030,14 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < KC; ++ks) {
-            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : load_w(rq.wo, j, wstep * ks);
+            const int f = j * KC + ks;
+            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : RING ? wring[RING ? f % RING : 0] : load_w(rq.wo, j, wstep * ks);
 #pragma unroll
             for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
+            if constexpr (RING > 0) {
+                if (f + RING < NF) wring[f % RING] = load_w(rq.wo, (f + RING) / KC, wstep * ((f + RING) % KC));
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
 #pragma unroll
