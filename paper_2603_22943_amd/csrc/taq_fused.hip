@@ -201,11 +201,13 @@ struct FusedCfg {
     static constexpr int IMG_HEAD_MAX = 96 * TPH * 16 + D * 96 + 3 * 96 * 4 + 32;
     static constexpr int IMGC = (IMG_HEAD_MAX + 1023) / 1024;
     static constexpr bool PREFETCH_W = TPH * KC <= 16 && NTT == 2 && NG == 1;  // a head's whole weight slice in registers
-    // Otherwise (one token tile per wavefront: registers to spare) a ring of RING weight loads stays in flight ahead of
-    // the projection MFMAs; left to itself the compiler keeps one to ten loads ahead and the loop waits on latency.
+    // Otherwise a ring of RING weight loads stays in flight ahead of the projection MFMAs (K step outermost, so that
+    // only one step's B operands are live); left to itself the compiler keeps one to ten loads ahead and the loop
+    // waits on latency.
     static constexpr int NF = TPH * KC;  // weight loads (16 rows x 64 bytes) of one projection per wavefront
-    static constexpr int RING_MAX = NH <= 8 ? 32 : 12;  // two wavefronts per SIMD (256 registers each), or three (168)
-    static constexpr int RING = (!PREFETCH_W && NG == 1 && NTT == 1) ? (NF < RING_MAX ? NF : RING_MAX) : 0;
+    // two wavefronts per SIMD (256 registers each), or three at ten heads (168)
+    static constexpr int RING_MAX = NH <= 8 ? (NTT == 1 ? 32 : 24) : (NTT == 1 ? 12 : 8);
+    static constexpr int RING = (!PREFETCH_W && NG == 1) ? (NF < RING_MAX ? NF : RING_MAX) : 0;
 };
 
 // Symmetric 8-bit codes of four values of one row, packed into a dword (low byte first).
@@ -388,7 +390,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             }
             if constexpr (RING > 0) {  // the first RING loads of to_q, in the order the MFMAs use them
     #pragma unroll
-                for (int f = it * RPS; f < (it + 1) * RPS && f < RING; ++f) wring[f] = load_w(rq.wq, f / KC, wstep * (f % KC));
+                for (int f = it * RPS; f < (it + 1) * RPS && f < RING; ++f) wring[f] = load_w(rq.wq, f % TPH, wstep * (f / TPH));
             }
             if (tid < 16 * TOK) {
                 const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq0, safe0);
@@ -539,8 +541,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     };
 
     // ================= to_q for this head: Qf^T[c][n]
-    int32x4_t hb[NTT][NG == 1 ? KC : 1];
-    if constexpr (NG == 1 && !CORE) {
+    int32x4_t hb[NTT][NG == 1 && RING == 0 ? KC : 1];
+    if constexpr (NG == 1 && !CORE && RING == 0) {
 #pragma unroll
         for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
@@ -561,6 +563,28 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 for (int nt = 0; nt < NTT; ++nt)
                     pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wreg[j][ks], hb[nt][ks], pacc[nt][j], 0, 0, 0);
         }
+    } else if constexpr (NG == 1 && RING > 0) {
+#pragma unroll
+        for (int j = 0; j < TPH; ++j)
+#pragma unroll
+            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KC; ++ks) {
+            int32x4_t hbk[NTT];
+#pragma unroll
+            for (int nt = 0; nt < NTT; ++nt)
+                hbk[nt] = *reinterpret_cast<const int32x4_t*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
+#pragma unroll
+            for (int j = 0; j < TPH; ++j) {
+                const int f = ks * TPH + j;
+                const int32x4_t wa = wring[f % RING];
+#pragma unroll
+                for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hbk[nt], pacc[nt][j], 0, 0, 0);
+                // the slot is free again: the load RING places ahead takes it
+                if (f + RING < NF) wring[f % RING] = load_w(rq.wq, (f + RING) % TPH, wstep * ((f + RING) / TPH));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
     } else if constexpr (NG == 1) {
 #pragma unroll
         for (int j = 0; j < TPH; ++j) {
@@ -568,14 +592,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
             for (int ks = 0; ks < KC; ++ks) {
-                const int f = j * KC + ks;
-                const int32x4_t wa = RING ? wring[RING ? f % RING : 0] : load_w(rq.wq, j, wstep * ks);
+                const int32x4_t wa = load_w(rq.wq, j, wstep * ks);
 #pragma unroll
                 for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
-                if constexpr (RING > 0) {  // the slot is free again: the load RING places ahead takes it
-                    if (f + RING < NF) wring[f % RING] = load_w(rq.wq, (f + RING) / KC, wstep * ((f + RING) % KC));
-                    __builtin_amdgcn_sched_barrier(0);
-                }
             }
         }
     } else {
@@ -704,9 +723,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
             for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = load_w(rq.wo, j, wstep * ks);
     }
-    if constexpr (RING > 0) {  // ... or its first RING loads
+    if constexpr (RING > 0 && NTT == 1) {  // ... or its first RING loads
 #pragma unroll
-        for (int f = 0; f < RING; ++f) wring[f] = load_w(rq.wo, f / KC, wstep * (f % KC));
+        for (int f = 0; f < RING; ++f) wring[f] = load_w(rq.wo, f % TPH, wstep * (f / TPH));
     }
 
 
@@ -969,6 +988,10 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         }
     }
 
+    if constexpr (RING > 0 && NTT == 2) {  // two token tiles per wavefront: the attention needs the registers; the first
+#pragma unroll                         // RING loads of to_out travel while A^ V~ is quantized
+        for (int f = 0; f < RING; ++f) wring[f] = load_w(rq.wo, f % TPH, wstep * (f / TPH));
+    }
     // ================= per-token int8 codes of O over all heads
     const float osc = reinterpret_cast<const float*>(imgh + dm.I.oscale)[0] * (1.0f / dm.pmax);
 #pragma unroll
@@ -1019,24 +1042,42 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     __syncthreads();
 
     // ================= to_out: Y^T[c][n] for this head's D output channels
+    if constexpr (RING > 0) {
 #pragma unroll
-    for (int nt = 0; nt < NTT; ++nt)
+        for (int j = 0; j < TPH; ++j)
 #pragma unroll
-        for (int ks = 0; ks < KC; ++ks)
-            hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
-#pragma unroll
-    for (int j = 0; j < TPH; ++j) {
-#pragma unroll
-        for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
+            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < KC; ++ks) {
-            const int f = j * KC + ks;
-            const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : RING ? wring[RING ? f % RING : 0] : load_w(rq.wo, j, wstep * ks);
+            int32x4_t hbk[NTT];
 #pragma unroll
-            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
-            if constexpr (RING > 0) {
-                if (f + RING < NF) wring[f % RING] = load_w(rq.wo, (f + RING) / KC, wstep * ((f + RING) % KC));
+            for (int nt = 0; nt < NTT; ++nt)
+                hbk[nt] = *reinterpret_cast<const int32x4_t*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
+#pragma unroll
+            for (int j = 0; j < TPH; ++j) {
+                const int f = ks * TPH + j;
+                const int32x4_t wa = wring[f % RING];
+#pragma unroll
+                for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hbk[nt], pacc[nt][j], 0, 0, 0);
+                if (f + RING < NF) wring[f % RING] = load_w(rq.wo, (f + RING) % TPH, wstep * ((f + RING) / TPH));
                 __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int nt = 0; nt < NTT; ++nt)
+#pragma unroll
+            for (int ks = 0; ks < KC; ++ks)
+                hb[nt][ks] = *reinterpret_cast<const int32x4_t*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + 64 * ks + 16 * q);
+#pragma unroll
+        for (int j = 0; j < TPH; ++j) {
+#pragma unroll
+            for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < KC; ++ks) {
+                const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : load_w(rq.wo, j, wstep * ks);
+#pragma unroll
+                for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
             }
         }
     }
