@@ -402,6 +402,9 @@ hipError_t launch_kv_trigger_rows(const __half* context, const int8_t* w_code, c
 // sections of qkv_packed and, where the shape has one, this head's block of the operand-ordered image.
 // One workgroup per (head, batch element, K or V), one wavefront per 16-token column tile. d % 8 == 0, Cc % 16 == 0.
 // The same launch carries the workgroups of the protected fp16 rows (they need only the first launch's results too).
+// WLDS: the head's weight slice (16*TPH rows x Cc codes, Cc % 64 == 0) is fetched once per workgroup, straight into LDS
+// in MFMA operand order (one KiB per 16 rows x 64 codes, LDS address = base + lane * 16), and every wavefront reads its
+// A operands from there; otherwise each of the up to six wavefronts fetches the slice itself.
 typedef int kvh_int32x4_t __attribute__((ext_vector_type(4)));
 #ifndef TAQ_NEG_INF
 #define TAQ_NEG_INF (-__builtin_inff())
@@ -414,7 +417,74 @@ __device__ __forceinline__ float kvh_quad_allmax(float x) {  // over the lanes l
     return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
+// Epilogue of one wavefront's 16-token column tile: float32 dequantisation of the integer sums, Eq. (2) quantizer per
+// (head, token), plain code / scale sections and the head's image block. This lane: token 16*st + r16, channels
+// 16*j + 4*q .. +3 of the head.
 template <int TPH>
+__device__ __forceinline__ void kvh_finish(const kvh_int32x4_t (&acc)[TPH], int st, int h, int b, int side, int d, int r16, int q,
+                                           int T, int C, int H, int bits, float qmaxf, const float* __restrict__ s_x,
+                                           const float* __restrict__ s_w, const int* __restrict__ slot_of, uint8_t* codes,
+                                           float* scales, uint8_t* img, const KvImage& I, bool has_image, float* sc_l,
+                                           unsigned* scmax) {
+    const int t = 16 * st + r16, tc = t < T ? t : T - 1;
+    const bool tv = t < T;
+    const bool prot = !tv || slot_of[tc] >= 0;
+    const float sx = s_x[(size_t)b * T + tc];
+    float v[TPH][4];
+    float amax = 0.f;
+#pragma unroll
+    for (int j = 0; j < TPH; ++j) {
+        const int cl = 16 * j + 4 * q;
+        const bool valid = cl < d;
+        float4 sw4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (valid) sw4 = *reinterpret_cast<const float4*>(s_w + side * C + h * d + cl);
+        const float swv[4] = {sw4.x, sw4.y, sw4.z, sw4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float sc = sx * swv[i];
+            v[j][i] = valid ? (float)acc[j][i] * sc : 0.f;
+            amax = fmaxf(amax, fabsf(v[j][i]));
+        }
+    }
+    amax = kvh_quad_allmax(amax);
+    const float sc = prot ? 0.f : (amax == 0.f ? 1.f : amax / qmaxf);
+    const float safe = amax == 0.f ? 1.f : amax;
+    if (tv && q == 0) scales[t] = sc;
+    if (!prot && q == 0) {
+        sc_l[t] = sc;
+        atomicMax(scmax, __float_as_uint(sc));
+    }
+    const int pos = (t & ~31) + 8 * ((t >> 2) & 3) + 4 * ((t >> 4) & 1) + (t & 3);  // place of token t in a V^T row
+#pragma unroll
+    for (int j = 0; j < TPH; ++j) {
+        const int cl = 16 * j + 4 * q;
+        int c[4] = {0, 0, 0, 0};
+        if (!prot && cl < d) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) c[i] = symq_code(v[j][i], qmaxf, safe);
+        }
+        if (tv && cl < d) {
+            if (bits == 8) {
+                *reinterpret_cast<unsigned*>(codes + ((size_t)b * T + t) * C + h * d + cl) = pack4_i8(c[0], c[1], c[2], c[3]);
+            } else {
+                const unsigned short w = (unsigned short)((c[0] & 0xF) | ((c[1] & 0xF) << 4) | ((c[2] & 0xF) << 8) |
+                                                          ((c[3] & 0xF) << 12));
+                *reinterpret_cast<unsigned short*>(codes + ((size_t)b * T + t) * (C / 2) + (h * d + cl) / 2) = w;
+            }
+        }
+        if (has_image) {
+            if (!side) {  // Kp[t][tile][quarter][4]; zeros past the head and past the last token
+                if (t < I.rows_k)
+                    *reinterpret_cast<unsigned*>(img + I.kp + kp_offset(I.tph, t, j, q)) = pack4_i8(c[0], c[1], c[2], c[3]);
+            } else if (cl < d) {  // Vt[channel][pos], stored with the sign bit flipped
+#pragma unroll
+                for (int i = 0; i < 4; ++i) img[I.vt + (size_t)(cl + i) * I.cols_v + pos] = (uint8_t)((c[i] & 0xFF) ^ 0x80);
+            }
+        }
+    }
+}
+
+template <int TPH, bool WLDS>
 __global__ __launch_bounds__(512) void kv_head_kernel(const int8_t* __restrict__ x_code, const float* __restrict__ s_x,
                                                       const int8_t* __restrict__ w_code, const float* __restrict__ s_w,
                                                       uint8_t* __restrict__ packed, KvLayout L, KvImage I, int T, int C,
@@ -422,6 +492,7 @@ __global__ __launch_bounds__(512) void kv_head_kernel(const int8_t* __restrict__
     __shared__ float xs[4096];  // protected-row workgroups: the context row in float32
     __shared__ float sc_l[96];  // scales of the unprotected tokens of this head and side (0: protected / padding)
     __shared__ unsigned scmax;
+    extern __shared__ __align__(16) unsigned char kvh_w[];  // WLDS: [TPH][Cc/64][64 lanes][16 bytes]
     // workgroups [0, 2*H*B): (head, batch element, K or V); the rest: protected fp16 rows, (slot, batch, 128 channels)
     const int nhead = 2 * H * B;
     if ((int)blockIdx.x >= nhead) {
@@ -440,13 +511,68 @@ __global__ __launch_bounds__(512) void kv_head_kernel(const int8_t* __restrict__
     const int nsub = has_image ? I.cols_v / 16 : (T + 15) / 16;  // 16-token column tiles to produce (image: padded)
     if (tid < 96) sc_l[tid] = 0.f;
     if (tid == 0) scmax = 0u;
-    __syncthreads();
+    const int ksteps = Cc / 64;  // used by WLDS only (there Cc % 64 == 0)
+    if constexpr (WLDS) {
+        // all eight wavefronts: piece f = j * ksteps + ks of the slice (rows 16*j .. 16*j+15, codes 64*ks .. 64*ks+63)
+        for (int f = wave; f < TPH * ksteps; f += 8) {
+            const int j = f / ksteps, ks = f - j * ksteps;
+            int c = side * C + h * d + 16 * j + r16;  // rows past the head are computed and dropped; stay inside [0, 2C)
+            c = c < 2 * C ? c : 2 * C - 1;
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(w_code + (size_t)c * Cc + 64 * ks + 16 * q),
+                (__attribute__((address_space(3))) void*)(kvh_w + (size_t)f * 1024), 16, 0, 0);
+        }
+    }
     const float qmaxf = bits == 4 ? 7.f : 127.f;
     const int* slot_of = reinterpret_cast<const int*>(packed + L.slot_of) + b * T;
     uint8_t* codes = packed + (side ? L.v_code : L.k_code);
     float* scales = reinterpret_cast<float*>(packed + (side ? L.s_v : L.s_k)) + ((size_t)b * H + h) * T;
     uint8_t* img = packed + L.image + (size_t)b * L.image_bytes + (size_t)h * I.head_bytes;
     const int st = wave;  // one 16-token column tile per wavefront (at most 6)
+    if constexpr (WLDS) {
+        // the token codes of the first K steps travel with the weight slice; then everybody waits for the slice
+        const int t = 16 * st + r16, tc = t < T ? t : T - 1;
+        const int8_t* xrow = x_code + ((size_t)b * T + tc) * Cc + 16 * q;
+        constexpr int XB = 16;  // K steps of token codes in flight per wavefront
+        kvh_int32x4_t xb[XB];
+        kvh_int32x4_t acc[TPH];
+#pragma unroll
+        for (int j = 0; j < TPH; ++j) acc[j] = (kvh_int32x4_t){0, 0, 0, 0};
+        if (st < nsub) {
+#pragma unroll
+            for (int u = 0; u < XB; ++u) {
+                xb[u] = (kvh_int32x4_t){0, 0, 0, 0};
+                if (u < ksteps) xb[u] = *reinterpret_cast<const kvh_int32x4_t*>(xrow + 64 * u);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's pieces of the slice are in LDS
+        __syncthreads();                     // ... and so are everybody else's; sc_l and scmax are cleared
+        if (st < nsub) {
+            for (int k0 = 0; k0 < ksteps; k0 += XB) {
+                if (k0 > 0) {
+#pragma unroll
+                    for (int u = 0; u < XB; ++u) {
+                        xb[u] = (kvh_int32x4_t){0, 0, 0, 0};
+                        if (k0 + u < ksteps) xb[u] = *reinterpret_cast<const kvh_int32x4_t*>(xrow + 64 * (k0 + u));
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < XB; ++u) {
+                    if (k0 + u < ksteps) {
+#pragma unroll
+                        for (int j = 0; j < TPH; ++j) {
+                            const kvh_int32x4_t wa =
+                                *reinterpret_cast<const kvh_int32x4_t*>(kvh_w + (size_t)(j * ksteps + k0 + u) * 1024 + lane * 16);
+                            acc[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, xb[u], acc[j], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+            kvh_finish<TPH>(acc, st, h, b, side, d, r16, q, T, C, H, bits, qmaxf, s_x, s_w, slot_of, codes, scales, img, I, has_image,
+                            sc_l, &scmax);
+        }
+    } else {
+    __syncthreads();
     if (st < nsub) {
         const int8_t* wrow[TPH];
 #pragma unroll
@@ -480,62 +606,9 @@ __global__ __launch_bounds__(512) void kv_head_kernel(const int8_t* __restrict__
 #pragma unroll
                 for (int j = 0; j < TPH; ++j) acc[j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa[u][j], xb[u], acc[j], 0, 0, 0);
         }
-        // this lane: token t, channels 16*j + 4*q .. +3 of the head
-        const bool tv = t < T;
-        const bool prot = !tv || slot_of[tc] >= 0;
-        const float sx = s_x[(size_t)b * T + tc];
-        float v[TPH][4];
-        float amax = 0.f;
-#pragma unroll
-        for (int j = 0; j < TPH; ++j) {
-            const int cl = 16 * j + 4 * q;
-            const bool valid = cl < d;
-            float4 sw4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (valid) sw4 = *reinterpret_cast<const float4*>(s_w + side * C + h * d + cl);
-            const float swv[4] = {sw4.x, sw4.y, sw4.z, sw4.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float sc = sx * swv[i];
-                v[j][i] = valid ? (float)acc[j][i] * sc : 0.f;
-                amax = fmaxf(amax, fabsf(v[j][i]));
-            }
-        }
-        amax = kvh_quad_allmax(amax);
-        const float sc = prot ? 0.f : (amax == 0.f ? 1.f : amax / qmaxf);
-        const float safe = amax == 0.f ? 1.f : amax;
-        if (tv && q == 0) scales[t] = sc;
-        if (!prot && q == 0) {
-            sc_l[t] = sc;
-            atomicMax(&scmax, __float_as_uint(sc));
-        }
-        const int pos = (t & ~31) + 8 * ((t >> 2) & 3) + 4 * ((t >> 4) & 1) + (t & 3);  // place of token t in a V^T row
-#pragma unroll
-        for (int j = 0; j < TPH; ++j) {
-            const int cl = 16 * j + 4 * q;
-            int c[4] = {0, 0, 0, 0};
-            if (!prot && cl < d) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) c[i] = symq_code(v[j][i], qmaxf, safe);
-            }
-            if (tv && cl < d) {
-                if (bits == 8) {
-                    *reinterpret_cast<unsigned*>(codes + ((size_t)b * T + t) * C + h * d + cl) = pack4_i8(c[0], c[1], c[2], c[3]);
-                } else {
-                    const unsigned short w = (unsigned short)((c[0] & 0xF) | ((c[1] & 0xF) << 4) | ((c[2] & 0xF) << 8) |
-                                                              ((c[3] & 0xF) << 12));
-                    *reinterpret_cast<unsigned short*>(codes + ((size_t)b * T + t) * (C / 2) + (h * d + cl) / 2) = w;
-                }
-            }
-            if (has_image) {
-                if (!side) {  // Kp[t][tile][quarter][4]; zeros past the head and past the last token
-                    if (t < I.rows_k)
-                        *reinterpret_cast<unsigned*>(img + I.kp + kp_offset(I.tph, t, j, q)) = pack4_i8(c[0], c[1], c[2], c[3]);
-                } else if (cl < d) {  // Vt[channel][pos], stored with the sign bit flipped
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) img[I.vt + (size_t)(cl + i) * I.cols_v + pos] = (uint8_t)((c[i] & 0xFF) ^ 0x80);
-                }
-            }
-        }
+        kvh_finish<TPH>(acc, st, h, b, side, d, r16, q, T, C, H, bits, qmaxf, s_x, s_w, slot_of, codes, scales, img, I, has_image,
+                        sc_l, &scmax);
+    }
     }
     if (!has_image) return;
     __syncthreads();
@@ -564,23 +637,38 @@ __global__ __launch_bounds__(512) void kv_head_kernel(const int8_t* __restrict__
     }
 }
 
-hipError_t launch_kv_head(const int8_t* x_code, const float* s_x, const int8_t* w_code, const float* s_w, uint8_t* packed,
-                          const __half* context, const taq_shape& s, hipStream_t st) {
+template <int TPH, bool WLDS>
+static hipError_t launch_kv_head_cfg(const int8_t* x_code, const float* s_x, const int8_t* w_code, const float* s_w,
+                                     uint8_t* packed, const __half* context, const taq_shape& s, size_t lds, hipStream_t st) {
     const KvLayout L = kv_layout(s);
     const KvImage I = kv_image(s);
-    const int tph = (s.C / s.H + 15) / 16;
+    if (WLDS) {
+        static std::atomic<unsigned long long> lds_set{0};
+        const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&kv_head_kernel<TPH, WLDS>), 140 * 1024, lds_set);
+        if (e != hipSuccess) return e;
+    }
     const dim3 grid(2 * s.H * s.B + s.T * s.B * ((2 * s.C + 127) / 128)), block(512);
-#define TAQ_KVH(N)                                                                                                     \
-    case N:                                                                                                            \
-        hipLaunchKernelGGL(kv_head_kernel<N>, grid, block, 0, st, x_code, s_x, w_code, s_w, packed, L, I, s.T, s.C, s.H, \
-                           s.Cc, s.bits_kv, s.B, context);                                                             \
-        break;
+    hipLaunchKernelGGL((kv_head_kernel<TPH, WLDS>), grid, block, lds, st, x_code, s_x, w_code, s_w, packed, L, I, s.T, s.C, s.H,
+                       s.Cc, s.bits_kv, s.B, context);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_head(const int8_t* x_code, const float* s_x, const int8_t* w_code, const float* s_w, uint8_t* packed,
+                          const __half* context, const taq_shape& s, hipStream_t st) {
+    const int tph = (s.C / s.H + 15) / 16;
+    // weight slice of a head in LDS (one KiB per 16 rows x 64 codes) when the row length allows whole K steps and the
+    // slice fits beside the 17 KiB of static LDS
+    const size_t slice = (size_t)tph * (s.Cc / 64) * 1024;
+    const bool wlds = s.Cc % 64 == 0 && slice <= 140 * 1024;
+#define TAQ_KVH(N)                                                                                                       \
+    case N:                                                                                                              \
+        return wlds ? launch_kv_head_cfg<N, true>(x_code, s_x, w_code, s_w, packed, context, s, slice, st)               \
+                    : launch_kv_head_cfg<N, false>(x_code, s_x, w_code, s_w, packed, context, s, 0, st);
     switch (tph) {
         TAQ_KVH(1) TAQ_KVH(2) TAQ_KVH(3) TAQ_KVH(4) TAQ_KVH(5) TAQ_KVH(6) TAQ_KVH(7) TAQ_KVH(8) TAQ_KVH(9) TAQ_KVH(10)
         default: return hipErrorInvalidValue;
     }
 #undef TAQ_KVH
-    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- expansion for tests
