@@ -41,7 +41,7 @@
 
 /* Environment (read at each call, for tests and tuning only): TAQ_FUSED_TOKENS=32 or 16 forces the image-token
  * tile of the single-kernel and head-group paths; by default the library picks 16 when 32-token tiles would fill at
- * most half of the GPU's compute units (head-group path: when they would give at most one workgroup per compute
+ * most half of the GPU's compute units (head-group path: when they would give at most four workgroups per compute
  * unit). Results do not depend on it. */
 
 #ifdef __cplusplus

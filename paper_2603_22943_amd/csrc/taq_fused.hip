@@ -1110,10 +1110,12 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 // a token tile forms the same int8 codes of its 32 rows (32 threads per row) in LDS: one kernel less, worth it while
 // the layer has few token tiles. Otherwise the codes and scales were formed once by the row quantizer kernel.
 // Same operand layout and epilogue as the last phase of the fused kernel.
-template <int C, int OT, bool FUSEQ>
+template <int C, int OT, bool FUSEQ, int TT = 1>
 __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, FusedDims dm) {
     constexpr int KC = C / 64, NT = 128 * OT, TILE_RS = C + 16;
+    constexpr int TOKS = 32 * TT;  // image tokens per workgroup (TT = 2: every weight load serves two 32-token tiles)
     static_assert(NT == 1024 && C % 128 == 0, "32 threads per token row");
+    static_assert(TT == 1 || !FUSEQ, "the in-kernel quantizer maps 32 threads to each of 32 rows");
     constexpr int CH = C / 128;  // float4 pieces of a row per thread
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
@@ -1121,9 +1123,9 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
     const int tl = (wave / OT) * 16 + r16;              // this lane's token within the 32-token tile
     const int b = blockIdx.x % dm.B, tile = blockIdx.x / dm.B;
     const FusedReq rq = tab.req[0];
-    const int N = dm.N, n0 = tile * 32;
-    int8_t* tileq = reinterpret_cast<int8_t*>(smem);               // [32][C+16]
-    float* s_o = reinterpret_cast<float*>(smem + 32 * TILE_RS);    // [32]
+    const int N = dm.N, n0 = tile * TOKS;
+    int8_t* tileq = reinterpret_cast<int8_t*>(smem);               // [TOKS][C+16]
+    float* s_o = reinterpret_cast<float*>(smem + TOKS * TILE_RS);  // [TOKS]
     // The rows of the tile are requested first: they are needed first (quantizer), and loads return in order; the
     // weights, needed only after the barrier, travel while the rows are quantized.
     const int cr = 16 * gt + r16;
@@ -1131,13 +1133,13 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
     const int wstep = dm.w_layout ? 1024 : 64;
     int32x4_t wa[KC];
     if constexpr (!FUSEQ) {
-        for (int v = tid; v < 32 * (C / 16); v += NT) {
+        for (int v = tid; v < TOKS * (C / 16); v += NT) {
             const int tk = v / (C / 16), col = (v % (C / 16)) * 16;
             const int nq = n0 + tk;
             const size_t row = (size_t)b * N + (nq < N ? nq : N - 1);
             *reinterpret_cast<uint4*>(tileq + tk * TILE_RS + col) = *reinterpret_cast<const uint4*>(dm.ws_ocode + row * C + col);
         }
-        if (tid < 32) {
+        if (tid < TOKS) {
             const int nq = n0 + tid;
             s_o[tid] = dm.ws_so[(size_t)b * N + (nq < N ? nq : N - 1)];
         }
@@ -1177,36 +1179,44 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
         }
     }
     __syncthreads();
-    const int n = n0 + tl;
-    const size_t tok = (size_t)b * N + (n < N ? n : N - 1);
-    const float so = s_o[tl];
-    int32x4_t acc = (int32x4_t){0, 0, 0, 0};
+    int32x4_t acc[TT];
+#pragma unroll
+    for (int g = 0; g < TT; ++g) acc[g] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
     for (int ks = 0; ks < KC; ++ks) {
-        const int32x4_t hb = *reinterpret_cast<const int32x4_t*>(tileq + tl * TILE_RS + 64 * ks + 16 * q);
-        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa[ks], hb, acc, 0, 0, 0);
+#pragma unroll
+        for (int g = 0; g < TT; ++g) {
+            const int32x4_t hb = *reinterpret_cast<const int32x4_t*>(tileq + (32 * g + tl) * TILE_RS + 64 * ks + 16 * q);
+            acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa[ks], hb, acc[g], 0, 0, 0);
+        }
     }
     const int c = 16 * gt + 4 * q;
     const float4 w4 = *reinterpret_cast<const float4*>(rq.scales + C + c);
     const float4 b4 = *reinterpret_cast<const float4*>(rq.scales + 2 * C + c);
-    const float y0 = (float)acc[0] * (so * w4.x) + b4.x;
-    const float y1 = (float)acc[1] * (so * w4.y) + b4.y;
-    const float y2 = (float)acc[2] * (so * w4.z) + b4.z;
-    const float y3 = (float)acc[3] * (so * w4.w) + b4.w;
-    if (n < N) {
-        const half4_t y = {(_Float16)y0, (_Float16)y1, (_Float16)y2, (_Float16)y3};
-        *reinterpret_cast<half4_t*>(rq.out + tok * C + c) = y;
+#pragma unroll
+    for (int g = 0; g < TT; ++g) {
+        const int n = n0 + 32 * g + tl;
+        const size_t tok = (size_t)b * N + (n < N ? n : N - 1);
+        const float so = s_o[32 * g + tl];
+        const float y0 = (float)acc[g][0] * (so * w4.x) + b4.x;
+        const float y1 = (float)acc[g][1] * (so * w4.y) + b4.y;
+        const float y2 = (float)acc[g][2] * (so * w4.z) + b4.z;
+        const float y3 = (float)acc[g][3] * (so * w4.w) + b4.w;
+        if (n < N) {
+            const half4_t y = {(_Float16)y0, (_Float16)y1, (_Float16)y2, (_Float16)y3};
+            *reinterpret_cast<half4_t*>(rq.out + tok * C + c) = y;
+        }
     }
 }
 
-template <int C, int OT, bool FUSEQ>
+template <int C, int OT, bool FUSEQ, int TT>
 static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
-    const size_t bytes = 32 * (C + 16) + 32 * 4;
+    const size_t bytes = 32 * TT * (C + 16) + 32 * TT * 4;
     static std::atomic<unsigned long long> lds_set{0};
-    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&to_out_tail_kernel<C, OT, FUSEQ>), 160 * 1024, lds_set);
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&to_out_tail_kernel<C, OT, FUSEQ, TT>), 160 * 1024, lds_set);
     if (e != hipSuccess) return e;
-    const int tiles = (dm.N + 31) / 32;
-    hipLaunchKernelGGL((to_out_tail_kernel<C, OT, FUSEQ>), dim3(tiles * dm.B, C / 16 / OT), dim3(128 * OT), bytes, st, tab, dm);
+    const int tiles = (dm.N + 32 * TT - 1) / (32 * TT);
+    hipLaunchKernelGGL((to_out_tail_kernel<C, OT, FUSEQ, TT>), dim3(tiles * dm.B, C / 16 / OT), dim3(128 * OT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 
@@ -1320,9 +1330,10 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, float* o_f, 
     dm.core_sq = nullptr;
     dm.ws_ocode = nullptr;
     dm.ws_so = nullptr;
-    // 32-token tiles that would leave compute units without a workgroup: 16-token workgroups of four wavefronts instead
-    // (TAQ_FUSED_TOKENS=32 or 16 in the environment forces one variant: for tests and tuning)
-    bool few = ((s.N + 31) / 32) * s.B * (d == 160 ? 8 : 10) <= 256;
+    // 16-token workgroups (all eight wavefronts load, four carry on with the attention) unless the layer is large:
+    // measured faster up to 640 workgroups of 32 tokens (SDXL 1024-token layer, batch 2: 36.4 -> 33.6 us), not
+    // measured beyond (TAQ_FUSED_TOKENS=32 or 16 in the environment forces one variant: for tests and tuning)
+    bool few = ((s.N + 31) / 32) * s.B * (d == 160 ? 8 : 10) <= 1024;
     if (const char* force = getenv("TAQ_FUSED_TOKENS")) few = atoi(force) == 16 ? true : atoi(force) == 32 ? false : few;
     if (d == 160 && s.H == 8)
         return few ? launch_fused_cfg<160, 1, 1, 8, 16>(tab, dm, s.prob_grid, st) : launch_fused_cfg<160, 1, 1, 8>(tab, dm, s.prob_grid, st);
@@ -1352,7 +1363,8 @@ hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const floa
     dm.omax_n = mid_omax_n(s);
     dm.ws_ocode = o_code;
     dm.ws_so = s_o;
-    if (s.C == 1280) return o_code ? launch_tail_cfg<1280, 8, false>(tab, dm, st) : launch_tail_cfg<1280, 8, true>(tab, dm, st);
+    // codes from the row quantizer (large layers): 64 tokens per workgroup, so that a weight load serves two token tiles
+    if (s.C == 1280) return o_code ? launch_tail_cfg<1280, 8, false, 2>(tab, dm, st) : launch_tail_cfg<1280, 8, true, 1>(tab, dm, st);
     return hipErrorInvalidValue;
 }
 

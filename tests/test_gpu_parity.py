@@ -424,6 +424,15 @@ def test_rowmax_probability_grid_when_a_trigger_takes_the_whole_row():
         check_layer(L, f"rowmax grid dominant trigger x{scale} C={C}", bits_prob=8, prob_grid="rowmax")
 
 
+@pytest.mark.parametrize("C,H,B,N,bits_kv", [(1280, 8, 2, 530, 8), (1280, 20, 1, 1050, 4)])
+def test_head_group_layers_with_more_than_1024_tokens_ragged(C, H, B, N, bits_kv):
+    """Above 1024 image tokens in total the head-group path quantizes A^ V~ with the row quantizer kernel and runs
+    to_out with 64 tokens per workgroup; N is a multiple of neither 32 nor 64 here."""
+    L = synth.make_layer("midbig", seed=C + H + N, B=B, N=N, C=C, H=H, Cc=64, T=77, bits_kv=bits_kv,
+                         trigger_positions=(2, 30), trigger_scale=3.0, bias=True)
+    check_layer(L, f"head groups C={C} H={H} B={B} N={N}")
+
+
 @pytest.mark.parametrize("tokens", ["32", "16"])
 @pytest.mark.parametrize("C,H,N,T_,bits_kv", [(640, 8, 45, 77, 8), (640, 10, 70, 50, 4), (640, 8, 130, 33, 4), (320, 8, 150, 77, 8),
                                               (1280, 8, 45, 77, 8), (1280, 8, 70, 40, 4), (1280, 20, 90, 77, 4), (1280, 20, 33, 96, 8)])
