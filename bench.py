@@ -45,6 +45,8 @@ def parse():
     p.add_argument("--cpu-seconds", type=float, default=12.0, help="lower bound of oracle time to spend")
     p.add_argument("--profile-only", action="store_true",
                    help="run only warmup + timed steps (for rocprofv3), skip the side measurements")
+    p.add_argument("--profile-config3", action="store_true",
+                   help="run only the 16-layer UNet step of configs[2] (for rocprofv3)")
     p.add_argument("--traffic-probe", action="store_true",
                    help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: a device copy of known size, then eager steps")
     p.add_argument("--summarize-sq", nargs="+", metavar="CSV",
@@ -134,29 +136,47 @@ def cpu_baseline(L, min_seconds):
                       f"float64 numpy, os.cpu_count()={os.cpu_count()}"}
 
 
+def prep_layer(L, dev, bits_q=8, bits_prob=8, prob_grid=T.TAQ_PROB_LINEAR):
+    """Device buffers of one synthetic layer, weight codes formed and packed, K~/V~ quantized once."""
+    to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    s = T.make_shape(B=L.B, N=L.N, C=L.C, H=L.H, T=L.T, Cc=L.Cc, bits_kv=L.bits_kv, bits_q=bits_q,
+                     bits_prob=bits_prob, w_layout=1 if L.C % 64 == 0 else 0, prob_grid=prob_grid)
+    wq, swq = T.taq_quantize_weight(to(L.Wq))
+    wo, swo = T.taq_quantize_weight(to(L.Wo))
+    if s.w_layout:
+        wq, wo = T.taq_pack_weight(wq, s), T.taq_pack_weight(wo, s)
+    d = dict(s=s, wq=wq, wo=wo, scales=torch.cat([swq, swo, to(L.bias_o)]).contiguous(), mask=to(L.mask),
+             ctx=to(L.context), Wk=to(L.Wk), Wv=to(L.Wv), hidden=to(L.hidden), bits_kv=L.bits_kv,
+             out=torch.empty((L.B, L.N, L.C), dtype=torch.float16, device=dev),
+             ws=torch.empty(T.taq_workspace_bytes(s), dtype=torch.uint8, device=dev),
+             packed=torch.empty(T.taq_kv_packed_bytes(s), dtype=torch.uint8, device=dev))
+    T.taq_quantize_kv(d["ctx"], d["mask"], d["Wk"], d["Wv"], L.bits_kv, s, d["packed"], d["ws"])
+    return d
+
+
+def attn_call(d):
+    return lambda: T.taq_cross_attn(d["hidden"], d["packed"], d["wq"], d["wo"], d["scales"], d["mask"], d["s"],
+                                    d["out"], d["ws"])
+
+
+def profile_config3(dev, use_graph, reps):
+    """For rocprofv3: the 16 cross-attention layers of one UNet step (configs[2]) replayed `reps` times from one HIP
+    graph, after one taq_quantize_kv per layer. Prints the measured time per 16-layer step."""
+    layers = [prep_layer(L, dev) for L in synth.config3()]
+    for d in layers:  # once more, so that the trace holds a second sample of the per-prompt kernels
+        T.taq_quantize_kv(d["ctx"], d["mask"], d["Wk"], d["Wv"], d["bits_kv"], d["s"], d["packed"], d["ws"])
+    r = Runner([attn_call(d) for d in layers], use_graph=use_graph)
+    r.run(2 * len(layers))
+    us = r.time_events(reps * len(layers)) * len(layers) * 1e6
+    print(json.dumps({"workload": "configs[2]: 16 cross-attention layers of one SD1.5 UNet step, batch 2, int4 K/V",
+                      "us_per_16_layer_step": round(us, 2), "replays": reps,
+                      "launch": "hip-graph" if r.graph is not None else "eager"}), flush=True)
+
+
 def other_configs(dev, use_graph):
     """Device time per taq_cross_attn call (and per taq_quantize_kv) for configs 1, 3, 4, 5."""
-    to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
     out = {}
-
-    def prep(L, bits_q=8, bits_prob=8, prob_grid=T.TAQ_PROB_LINEAR):
-        s = T.make_shape(B=L.B, N=L.N, C=L.C, H=L.H, T=L.T, Cc=L.Cc, bits_kv=L.bits_kv, bits_q=bits_q,
-                         bits_prob=bits_prob, w_layout=1 if L.C % 64 == 0 else 0, prob_grid=prob_grid)
-        wq, swq = T.taq_quantize_weight(to(L.Wq))
-        wo, swo = T.taq_quantize_weight(to(L.Wo))
-        if s.w_layout:
-            wq, wo = T.taq_pack_weight(wq, s), T.taq_pack_weight(wo, s)
-        d = dict(s=s, wq=wq, wo=wo, scales=torch.cat([swq, swo, to(L.bias_o)]).contiguous(), mask=to(L.mask),
-                 ctx=to(L.context), Wk=to(L.Wk), Wv=to(L.Wv), hidden=to(L.hidden),
-                 out=torch.empty((L.B, L.N, L.C), dtype=torch.float16, device=dev),
-                 ws=torch.empty(T.taq_workspace_bytes(s), dtype=torch.uint8, device=dev),
-                 packed=torch.empty(T.taq_kv_packed_bytes(s), dtype=torch.uint8, device=dev))
-        T.taq_quantize_kv(d["ctx"], d["mask"], d["Wk"], d["Wv"], L.bits_kv, s, d["packed"], d["ws"])
-        return d
-
-    def attn_call(d):
-        return lambda: T.taq_cross_attn(d["hidden"], d["packed"], d["wq"], d["wo"], d["scales"], d["mask"], d["s"],
-                                        d["out"], d["ws"])
+    prep = lambda L, **kw: prep_layer(L, dev, **kw)
 
     def timed(calls, reps=40):
         r = Runner(calls, use_graph=use_graph)
@@ -251,6 +271,9 @@ def main():
     T.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if a.profile_config3:
+        profile_config3(dev, not a.no_graph, reps=50)
+        return
     L = synth.config2()
     s = T.make_shape(B=L.B, N=L.N, C=L.C, H=L.H, T=L.T, Cc=L.Cc, bits_kv=L.bits_kv, w_layout=1)
     to = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
