@@ -54,7 +54,8 @@ typedef enum taq_status {
     TAQ_ERR_UNSUPPORTED_BITS = -2, /* a bit width outside what this build implements        */
     TAQ_ERR_BAD_SHAPE = -3,        /* shape outside the supported set listed above          */
     TAQ_ERR_MISALIGNED = -4,       /* a pointer is not 16-byte aligned                      */
-    TAQ_ERR_HIP = -5               /* the HIP runtime reported an error at launch           */
+    TAQ_ERR_HIP = -5,              /* the HIP runtime reported an error at launch           */
+    TAQ_ERR_SCRATCH_TOO_SMALL = -6 /* taq_cross_attn_static: shape needs more scratch than the library's array */
 } taq_status;
 
 /* Problem description shared by all calls. */
@@ -184,6 +185,21 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
                       const int8_t* Wo, const float* scales, const uint8_t* trigger_mask,
                       const taq_shape* shape, void* out, void* workspace, void* hip_stream,
                       const taq_debug* dbg);
+
+/* taq_cross_attn for callers that cannot hand over (or allocate) a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation. Same arguments minus `workspace`;
+ * the scratch memory is a fixed array of TAQ_STATIC_SCRATCH_BYTES inside the library, one copy per
+ * GPU, held until the process ends. The call allocates and frees nothing.
+ *   - A shape whose kernels need more scratch than the array holds is rejected with
+ *     TAQ_ERR_SCRATCH_TOO_SMALL and nothing is launched (shapes that run as one kernel need none
+ *     and are never rejected for size; the others need about 11 * B * N * C bytes).
+ *   - All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different
+ *     streams, several host threads) race; serialise them or use taq_cross_attn with own workspaces.
+ *   - Results are bit-identical to taq_cross_attn. */
+#define TAQ_STATIC_SCRATCH_BYTES (16u << 20)
+int taq_cross_attn_static(const void* hidden, const void* qkv_packed, const int8_t* Wq, const int8_t* Wo,
+                          const float* scales, const uint8_t* trigger_mask, const taq_shape* shape,
+                          void* out, void* hip_stream);
 
 /* R independent requests of one shape, each with its own weights, K~/V~ and hidden
  * states (e.g. R personalised checkpoints served together). `table` is HOST memory,

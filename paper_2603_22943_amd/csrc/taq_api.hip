@@ -48,6 +48,8 @@ const char* taq_status_string(int status) {
         case TAQ_ERR_BAD_SHAPE: return "TAQ_ERR_BAD_SHAPE: shape outside the supported set";
         case TAQ_ERR_MISALIGNED: return "TAQ_ERR_MISALIGNED: pointer not 16-byte aligned";
         case TAQ_ERR_HIP: return "TAQ_ERR_HIP: HIP runtime error at launch";
+        case TAQ_ERR_SCRATCH_TOO_SMALL:
+            return "TAQ_ERR_SCRATCH_TOO_SMALL: the shape needs more scratch than the library's static array holds";
         default: return "unknown taq_status";
     }
 }
@@ -262,6 +264,40 @@ int taq_cross_attn(const void* hidden, const void* qkv_packed, const int8_t* Wq,
                    void* workspace, void* hip_stream) {
     return taq_cross_attn_ex(hidden, qkv_packed, Wq, Wo, scales, trigger_mask, shape, out, workspace, hip_stream,
                              nullptr);
+}
+
+// Scratch of taq_cross_attn_static: a fixed array in device memory, one copy per GPU, each at its own address. In host
+// code the array's name is only a stand-in for the symbol; the address kernels can use is looked up once per device
+// (with that device current) and kept in scratch_ptr. `used`: no kernel names the array, it must still be emitted.
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[TAQ_STATIC_SCRATCH_BYTES];
+static std::atomic<void*> scratch_ptr[64];
+
+static int static_scratch(void** p) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return TAQ_ERR_HIP;
+    void* q = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!q) {  // two host threads that race here look up the same address
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return TAQ_ERR_HIP;
+        scratch_ptr[dev].store(q, std::memory_order_release);
+    }
+    *p = q;
+    return TAQ_OK;
+}
+
+int taq_cross_attn_static(const void* hidden, const void* qkv_packed, const int8_t* Wq, const int8_t* Wo,
+                          const float* scales, const uint8_t* trigger_mask, const taq_shape* shape, void* out,
+                          void* hip_stream) {
+    int rc = check_shape(shape, true);
+    if (rc != TAQ_OK) return rc;
+    // the single-kernel shapes never touch the workspace; every other path uses the layout of attn_workspace
+    const size_t need = fused_supported(*shape) ? 0 : attn_workspace(*shape).total;
+    if (need > (size_t)TAQ_STATIC_SCRATCH_BYTES) return TAQ_ERR_SCRATCH_TOO_SMALL;
+    if (!hidden || !qkv_packed || !Wq || !Wo || !scales || !out) return TAQ_ERR_INVALID_ARG;
+    void* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != TAQ_OK) return rc;
+    // nothing in the workspace has to start at zero: every kernel writes what a later one reads
+    return taq_cross_attn_ex(hidden, qkv_packed, Wq, Wo, scales, trigger_mask, shape, out, ws, hip_stream, nullptr);
 }
 
 int taq_cross_attn_batched(int R, const taq_request* table, const taq_shape* shape, void* workspace,

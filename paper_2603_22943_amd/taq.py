@@ -22,6 +22,8 @@ TAQ_ERR_UNSUPPORTED_BITS = -2
 TAQ_ERR_BAD_SHAPE = -3
 TAQ_ERR_MISALIGNED = -4
 TAQ_ERR_HIP = -5
+TAQ_ERR_SCRATCH_TOO_SMALL = -6
+TAQ_STATIC_SCRATCH_BYTES = 16 << 20
 
 TAQ_PROB_LINEAR = 0
 TAQ_PROB_LOG2 = 1
@@ -38,7 +40,7 @@ EXPORTS = [
     "taq_kv_packed_bytes", "taq_workspace_bytes", "taq_quantize_weight", "taq_weight_bytes", "taq_pack_weight",
     "taq_quantize_kv",
     "taq_quantize_kv_w8",
-    "taq_cross_attn", "taq_cross_attn_ex", "taq_cross_attn_batched", "taq_unpack_kv",
+    "taq_cross_attn", "taq_cross_attn_ex", "taq_cross_attn_static", "taq_cross_attn_batched", "taq_unpack_kv",
     "taq_status_string",
 ]
 
@@ -93,6 +95,7 @@ def load() -> ctypes.CDLL:
     lib.taq_quantize_kv_w8.argtypes = [vp, vp, vp, vp, ci, shp, vp, vp, vp]
     lib.taq_cross_attn.argtypes = [vp, vp, vp, vp, vp, vp, shp, vp, vp, vp]
     lib.taq_cross_attn_ex.argtypes = [vp, vp, vp, vp, vp, vp, shp, vp, vp, vp, ctypes.POINTER(taq_debug)]
+    lib.taq_cross_attn_static.argtypes = [vp, vp, vp, vp, vp, vp, shp, vp, vp]
     lib.taq_cross_attn_batched.argtypes = [ci, ctypes.POINTER(taq_request), shp, vp, vp]
     lib.taq_unpack_kv.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, vp]
     for name in EXPORTS:
@@ -216,6 +219,17 @@ def taq_cross_attn(hidden: torch.Tensor, qkv_packed: torch.Tensor, Wq: torch.Ten
                                    _ptr(trigger_mask), ctypes.byref(shape), _ptr(out), _ptr(workspace),
                                    _stream(stream), ctypes.byref(debug))
     _check(rc, "taq_cross_attn")
+    return out
+
+
+def taq_cross_attn_static(hidden: torch.Tensor, qkv_packed: torch.Tensor, Wq: torch.Tensor, Wo: torch.Tensor,
+                          scales: torch.Tensor, trigger_mask: Optional[torch.Tensor], shape: taq_shape,
+                          out: torch.Tensor, stream=None) -> torch.Tensor:
+    """taq_cross_attn on the library's static scratch array: no workspace argument, nothing allocated (the
+    caller passes `out`)."""
+    _check(load().taq_cross_attn_static(_ptr(hidden), _ptr(qkv_packed), _ptr(Wq), _ptr(Wo), _ptr(scales),
+                                        _ptr(trigger_mask), ctypes.byref(shape), _ptr(out), _stream(stream)),
+           "taq_cross_attn_static")
     return out
 
 

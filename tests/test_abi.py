@@ -35,7 +35,7 @@ def test_struct_sizes_match_header_layout():
 
 def test_status_strings():
     assert T.taq_status_string(0) == "TAQ_OK"
-    for code in (-1, -2, -3, -4, -5):
+    for code in (-1, -2, -3, -4, -5, -6):
         assert T.taq_status_string(code).startswith("TAQ_ERR_")
     assert "unknown" in T.taq_status_string(-99)
 
@@ -102,6 +102,11 @@ def test_entry_points_reject_null_misaligned_and_inconsistent_arguments_without_
     assert lib.taq_cross_attn(FAKE, FAKE, FAKE, ODD, FAKE, None, sp, FAKE, FAKE, None) == T.TAQ_ERR_MISALIGNED
     s0 = T.make_shape(B=1, N=0, C=320, H=8, T=77, Cc=768)
     assert lib.taq_cross_attn(FAKE, FAKE, FAKE, FAKE, FAKE, None, ctypes.byref(s0), FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG
+    # taq_cross_attn_static: the size limit is checked on the host, before anything touches the GPU
+    assert lib.taq_cross_attn_static(FAKE, FAKE, FAKE, FAKE, FAKE, None, sp, None, None) == T.TAQ_ERR_INVALID_ARG
+    big = T.make_shape(B=2, N=4096, C=1280, H=8, T=77, Cc=768)   # head-group path: ~11*B*N*C bytes of scratch
+    assert lib.taq_cross_attn_static(FAKE, FAKE, FAKE, FAKE, FAKE, None, ctypes.byref(big), FAKE, None) == T.TAQ_ERR_SCRATCH_TOO_SMALL
+    assert T.taq_workspace_bytes(big) > T.TAQ_STATIC_SCRATCH_BYTES
     # taq_quantize_weight
     assert lib.taq_quantize_weight(FAKE, 0, 64, FAKE, FAKE, None) == T.TAQ_ERR_INVALID_ARG
     assert lib.taq_quantize_weight(FAKE, 8, 60, FAKE, FAKE, None) == T.TAQ_ERR_BAD_SHAPE
