@@ -39,11 +39,6 @@
 #include <stddef.h>
 #include <stdint.h>
 
-/* Environment (read at each call, for tests and tuning only): TAQ_FUSED_TOKENS=32 or 16 forces the image-token
- * tile of the single-kernel and head-group paths; by default the library picks 16 when 32-token tiles would fill at
- * most half of the GPU's compute units (head-group path: when they would give at most four workgroups per compute
- * unit). Results do not depend on it. */
-
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -79,6 +74,10 @@ typedef struct taq_shape {
                                 TAQ_PROB_ROWMAX (2) : the affine quantizer with the row's own range:
                                                       amax = largest unprotected A of the (token, head) row,
                                                       code = rint(pmax*A/amax), A^ = code*amax/pmax     */
+    int tok_tile;            /* image tokens per workgroup of the single-kernel and head-group paths: 0 = the library
+                                picks (16 when 32-token tiles would fill at most half of the GPU's compute units;
+                                head-group path: when they would give at most four workgroups per compute unit);
+                                32 or 16 forces one (tests and tuning). Results do not depend on it.              */
 } taq_shape;
 
 enum { TAQ_PROB_LINEAR = 0, TAQ_PROB_LOG2 = 1, TAQ_PROB_ROWMAX = 2 };

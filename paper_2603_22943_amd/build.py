@@ -20,7 +20,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtaq.so")
-SOURCES = ["taq_api.hip", "taq_quant.hip", "taq_gemm.hip", "taq_attn.hip", "taq_fused.hip"]
+SOURCES = ["taq_fused_d40.hip", "taq_fused_d80.hip", "taq_fused_d64.hip", "taq_fused_mid160.hip", "taq_fused_mid64.hip",
+           "taq_fused.hip", "taq_api.hip", "taq_quant.hip", "taq_gemm.hip", "taq_attn.hip"]
 
 
 def hipcc_path() -> str:
@@ -31,23 +32,35 @@ def hipcc_path() -> str:
 
 
 def build_lib(verbose: bool = True) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [
-        hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    """Compile every source to an object (in parallel: one hipcc per file) and link libtaq.so."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    flags = [
+        "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
         "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-honor-nans",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wno-unused-function",
         "-I", os.path.join(os.path.dirname(HERE), "include"),
-        "-o", LIB,
-    ] + os.environ.get("TAQ_EXTRA_HIPCC_FLAGS", "").split() + srcs
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
-    if verbose and out.strip():
-        print(out, flush=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
+    ] + os.environ.get("TAQ_EXTRA_HIPCC_FLAGS", "").split()
+    hipcc = hipcc_path()
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+        if verbose and out.strip():
+            print(out, flush=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + out)
+
+    objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    jobs = [[hipcc] + flags + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1)) as pool:
+        list(pool.map(run, jobs))
+    run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
     return LIB
 
 

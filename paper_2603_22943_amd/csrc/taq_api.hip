@@ -23,6 +23,7 @@ int check_shape(const taq_shape* s, bool need_n) {
     if (s->C % 32 != 0 || s->Cc % 32 != 0 || s->Cc > 4096) return TAQ_ERR_BAD_SHAPE;
     if (!(s->softmax_scale >= 0.f)) return TAQ_ERR_INVALID_ARG;
     if (s->w_layout != 0 && s->w_layout != 1) return TAQ_ERR_INVALID_ARG;
+    if (s->tok_tile != 0 && s->tok_tile != 16 && s->tok_tile != 32) return TAQ_ERR_INVALID_ARG;
     if (s->prob_grid != TAQ_PROB_LINEAR && s->prob_grid != TAQ_PROB_LOG2 && s->prob_grid != TAQ_PROB_ROWMAX)
         return TAQ_ERR_INVALID_ARG;
     // index arithmetic inside the kernels is 32-bit for token counts

@@ -55,7 +55,8 @@ class taq_shape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("N", ctypes.c_int), ("C", ctypes.c_int), ("H", ctypes.c_int),
                 ("T", ctypes.c_int), ("Cc", ctypes.c_int), ("bits_kv", ctypes.c_int),
                 ("bits_prob", ctypes.c_int), ("bits_q", ctypes.c_int), ("bits_proj", ctypes.c_int),
-                ("softmax_scale", ctypes.c_float), ("w_layout", ctypes.c_int), ("prob_grid", ctypes.c_int)]
+                ("softmax_scale", ctypes.c_float), ("w_layout", ctypes.c_int), ("prob_grid", ctypes.c_int),
+                ("tok_tile", ctypes.c_int)]
 
 
 class taq_debug(ctypes.Structure):
@@ -106,8 +107,9 @@ def load() -> ctypes.CDLL:
 
 def make_shape(B: int, N: int, C: int, H: int, T: int, Cc: int, bits_kv: int = 8, bits_prob: int = 8,
                bits_q: int = 8, bits_proj: int = 8, softmax_scale: float = 0.0, w_layout: int = 0,
-               prob_grid: int = 0) -> taq_shape:
-    return taq_shape(B, N, C, H, T, Cc, bits_kv, bits_prob, bits_q, bits_proj, softmax_scale, w_layout, prob_grid)
+               prob_grid: int = 0, tok_tile: int = 0) -> taq_shape:
+    return taq_shape(B, N, C, H, T, Cc, bits_kv, bits_prob, bits_q, bits_proj, softmax_scale, w_layout, prob_grid,
+                     tok_tile)
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:

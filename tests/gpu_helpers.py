@@ -11,10 +11,10 @@ from paper_2603_22943_amd import taq as T
 DEV = "cuda:0"
 
 
-def shape_of(L, bits_kv=None, N=None, w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear"):
+def shape_of(L, bits_kv=None, N=None, w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear", tok_tile=0):
     return T.make_shape(B=L.B, N=L.N if N is None else N, C=L.C, H=L.H, T=L.T, Cc=L.Cc,
                         bits_kv=L.bits_kv if bits_kv is None else bits_kv, bits_q=bits_q, bits_prob=bits_prob,
-                        w_layout=w_layout, prob_grid={"linear": T.TAQ_PROB_LINEAR, "log2": T.TAQ_PROB_LOG2,
+                        w_layout=w_layout, tok_tile=tok_tile, prob_grid={"linear": T.TAQ_PROB_LINEAR, "log2": T.TAQ_PROB_LOG2,
                                                        "rowmax": T.TAQ_PROB_ROWMAX}[prob_grid])
 
 
@@ -28,9 +28,9 @@ def dev(a, dtype=None):
 class GpuRun:
     """Everything the HIP path produces for one layer (tensors brought back as numpy)."""
 
-    def __init__(self, L, taps=True, hidden=None, w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear"):
+    def __init__(self, L, taps=True, hidden=None, w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear", tok_tile=0):
         self.L = L
-        self.shape = s = shape_of(L, w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid)
+        self.shape = s = shape_of(L, w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid, tok_tile=tok_tile)
         ctx, mask = dev(L.context), dev(L.mask)
         Wq, Wk, Wv, Wo = dev(L.Wq), dev(L.Wk), dev(L.Wv), dev(L.Wo)
         self.wq_code, self.s_wq = T.taq_quantize_weight(Wq)
@@ -50,7 +50,7 @@ class GpuRun:
         self.hidden_d = dev(L.hidden if hidden is None else hidden)
         if hidden is not None:
             self.shape = s = shape_of(L, N=hidden.shape[1], w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob,
-                                      prob_grid=prob_grid)
+                                      prob_grid=prob_grid, tok_tile=tok_tile)
         if taps:
             dbg, t = T.make_debug(s, DEV)
             self.ws.fill_(0xFF)

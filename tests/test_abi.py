@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert ctypes.sizeof(T.taq_shape) == 13 * 4
+    assert ctypes.sizeof(T.taq_shape) == 14 * 4
     assert ctypes.sizeof(T.taq_request) == 7 * 8
     assert ctypes.sizeof(T.taq_debug) == 7 * 8 + 8
 
@@ -72,6 +72,7 @@ def test_size_queries_are_host_only_and_consistent():
     (dict(Cc=100), T.TAQ_ERR_BAD_SHAPE),
     (dict(B=0), T.TAQ_ERR_INVALID_ARG),
     (dict(softmax_scale=-1.0), T.TAQ_ERR_INVALID_ARG),
+    (dict(tok_tile=8), T.TAQ_ERR_INVALID_ARG),
 ])
 def test_bad_shapes_are_rejected(kw, expect):
     base = dict(B=2, N=64, C=320, H=8, T=77, Cc=768)

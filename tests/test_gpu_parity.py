@@ -27,10 +27,10 @@ OUT_MAX_ABS = 2e-2
 OUT_REL_L2 = 5e-3
 
 
-def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear"):
+def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear", tok_tile=0):
     print(f"[case] {label or L.name}: B={L.B} N={L.N} C={L.C} H={L.H} T={L.T} Cc={L.Cc} bits_kv={L.bits_kv} "
           f"bits_q={bits_q} bits_prob={bits_prob} grid={prob_grid} ntrig={L.mask.sum(axis=1).tolist()} w_layout={w_layout}", flush=True)
-    g = G.GpuRun(L, w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid)
+    g = G.GpuRun(L, w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid, tok_tile=tok_tile)
     ref_out, aux = G.oracle_run(L, bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid)
     kv = aux["kv"]
     pmax = float((1 << bits_prob) - 1)
@@ -433,16 +433,15 @@ def test_head_group_layers_with_more_than_1024_tokens_ragged(C, H, B, N, bits_kv
     check_layer(L, f"head groups C={C} H={H} B={B} N={N}")
 
 
-@pytest.mark.parametrize("tokens", ["32", "16"])
+@pytest.mark.parametrize("tokens", [32, 16])
 @pytest.mark.parametrize("C,H,N,T_,bits_kv", [(640, 8, 45, 77, 8), (640, 10, 70, 50, 4), (640, 8, 130, 33, 4), (320, 8, 150, 77, 8),
                                               (1280, 8, 45, 77, 8), (1280, 8, 70, 40, 4), (1280, 20, 90, 77, 4), (1280, 20, 33, 96, 8)])
-def test_fused_kernel_both_workgroup_sizes(C, H, N, T_, bits_kv, tokens, monkeypatch):
+def test_fused_kernel_both_workgroup_sizes(C, H, N, T_, bits_kv, tokens):
     """Single-kernel and head-group layers run with 32-token workgroups when that fills the chip and with 16-token
-    workgroups otherwise; both variants are forced here on the same small layers and must give bit-identical outputs."""
+    workgroups otherwise; both variants are forced here (shape.tok_tile) on the same small layers and must give
+    bit-identical outputs."""
     L = synth.make_layer("tok", seed=C + H + N, B=2, N=N, C=C, H=H, Cc=64, T=T_, bits_kv=bits_kv,
                          trigger_positions=(1, T_ - 1), trigger_scale=3.0, bias=True)
-    monkeypatch.setenv("TAQ_FUSED_TOKENS", tokens)
-    g = check_layer(L, f"fused C={C} H={H} N={N} workgroup tokens={tokens}")
-    monkeypatch.setenv("TAQ_FUSED_TOKENS", "32" if tokens == "16" else "16")
-    g2 = G.GpuRun(L, taps=False)
+    g = check_layer(L, f"fused C={C} H={H} N={N} workgroup tokens={tokens}", tok_tile=tokens)
+    g2 = G.GpuRun(L, taps=False, tok_tile=48 - tokens)
     assert np.array_equal(g.out.view(np.uint16), g2.out.view(np.uint16))
