@@ -49,7 +49,10 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
     for (int t = tid; t < 96; t += nth) {
         const bool isint = t < T && slot_of[t] < 0;
         reinterpret_cast<float*>(img + I.s_k)[t] = isint ? s_k[t] : 0.f;
-        reinterpret_cast<float*>(img + I.s_vp)[t] = isint ? s_v[t] * vpre_s : 0.f;
+        const float sp = isint ? s_v[t] * vpre_s : 0.f;  // s' = s_V * 2^kexp as two fp16 numbers, high part and remainder
+        const __half sph = __float2half_rn(sp);
+        reinterpret_cast<__half*>(img + I.s_vp)[t] = sph;
+        reinterpret_cast<__half*>(img + I.s_vp)[96 + t] = __float2half_rn(sp - __half2float(sph));
         reinterpret_cast<float*>(img + I.bias)[t] = isint ? 0.f : TAQ_NEG_INF;
     }
     const int rowb = I.tph * 16;  // bytes per (head, token) row of Kp

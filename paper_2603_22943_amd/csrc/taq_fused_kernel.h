@@ -109,21 +109,23 @@ struct FusedCfg {
 // Symmetric 8-bit codes of four values of one row, packed into a dword (low byte first).
 //   exact definition: code = rint((x * qmax) / amax) with IEEE float32 multiply and divide (qmax = 127, or 7 for
 //   4-bit Q~; the bounds below are stated for 127 and only shrink for 7).
-//   fast path: q0 = x * c with c = 127 * rcp(amax) (rcp within 1 ulp). q0 lies within 4 * 2^-24 * 127 = 3.0e-5
-//   of the exact ratio and the defined quotient within 2 * 2^-24 * 127 = 1.5e-5, so both round to the same
-//   integer unless q0 is within 4.6e-5 of a half-integer; those (rare) lanes redo the four values by the
-//   definition. Rounding uses the 1.5 * 2^23 trick: the low mantissa byte of q0 + magic is the code's byte.
+//   fast path: with c = qmax * rcp(amax) (rcp within 1 ulp, the product rounded once: c is within 1.5 * 2^-23 of
+//   qmax / amax, relatively), m = fma(x, c, 1.5 * 2^23) is the EXACT product x * c rounded half-to-even to an integer
+//   (plus the magic constant, whose low mantissa byte is then the code's byte), and e = fma(x, c, -(m - magic)) is the
+//   distance of that exact product from the integer. x * c lies within 1.5 * 2^-23 * 127 = 2.3e-5 of the exact ratio
+//   and the defined quotient within 2 * 2^-24 * 127 = 1.5e-5, so both round to the same integer unless x * c is
+//   within 3.8e-5 of a half-integer; lanes with |e| > 0.49995 redo their four values by the definition.
 __device__ __forceinline__ unsigned quant4_i8(float x0, float x1, float x2, float x3, float c, float amax,
                                               float qmaxf = 127.f) {
     const float magic = 12582912.0f;
-    const float q0 = x0 * c, q1 = x1 * c, q2 = x2 * c, q3 = x3 * c;
-    const float m0 = q0 + magic, m1 = q1 + magic, m2 = q2 + magic, m3 = q3 + magic;
-    const float d0 = fabsf(q0 - (m0 - magic)), d1 = fabsf(q1 - (m1 - magic));
-    const float d2 = fabsf(q2 - (m2 - magic)), d3 = fabsf(q3 - (m3 - magic));
+    const float m0 = __builtin_fmaf(x0, c, magic), m1 = __builtin_fmaf(x1, c, magic);
+    const float m2 = __builtin_fmaf(x2, c, magic), m3 = __builtin_fmaf(x3, c, magic);
+    const float e0 = __builtin_fmaf(x0, c, magic - m0), e1 = __builtin_fmaf(x1, c, magic - m1);
+    const float e2 = __builtin_fmaf(x2, c, magic - m2), e3 = __builtin_fmaf(x3, c, magic - m3);
     const unsigned lo = __builtin_amdgcn_perm(__float_as_uint(m1), __float_as_uint(m0), 0x0c0c0400u);
     const unsigned hi = __builtin_amdgcn_perm(__float_as_uint(m3), __float_as_uint(m2), 0x0c0c0400u);
     unsigned pk = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-    if (fmaxf(fmaxf(d0, d1), fmaxf(d2, d3)) > 0.49995f)
+    if (fmaxf(fmaxf(fabsf(e0), fabsf(e1)), fmaxf(fabsf(e2), fabsf(e3))) > 0.49995f)
         pk = pack4(symq_code_f(x0, qmaxf, amax), symq_code_f(x1, qmaxf, amax), symq_code_f(x2, qmaxf, amax),
                    symq_code_f(x3, qmaxf, amax));
     return pk;
@@ -232,6 +234,40 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     constexpr int RING = CORE ? 0 : F::RING, NF = F::NF;
     constexpr int RPS = RING ? (RING + KC - 1) / KC : 0;  // ring loads issued per step of the hidden quantizer
     int32x4_t wring[RING ? RING : 1];
+    const float* swq = wsc;
+    const float* swo = wsc + C;
+    const float* bo = wsc + 2 * C;
+    unsigned char* imgh = img + (size_t)hl * dm.I.head_bytes;  // this head's block of the K~/V~ image
+    const float* img_sk = reinterpret_cast<const float*>(imgh + dm.I.s_k);
+    const float* img_bias = reinterpret_cast<const float*>(imgh + dm.I.bias);
+    const __half* k16 = reinterpret_cast<const __half*>(packed + dm.L.k16) + (size_t)b * T * C;
+    const __half* v16t = reinterpret_cast<const __half*>(packed + dm.L.v16t) + (size_t)b * C * 96;
+
+    // protected (trigger) rows of this head, first tile of 16: fp16 K rows and transposed V rows straight from
+    // global memory into MFMA operand registers (slots past the protected tokens hold zeros; K channels past the
+    // head are not read: they would belong to the next head, or lie past the last row of the last head, and a
+    // non-finite bit pattern there would survive the multiplication with a zero Q~ code)
+    uint2 k16r[FS][2], v16r[TPS];
+    auto load_protected = [&]() {
+        if (nfp > 0) {
+            const int slot = r16 < T ? r16 : T - 1;
+            const __half* kr = k16 + (size_t)slot * C + h * D + 4 * q;
+#pragma unroll
+            for (int s = 0; s < FS; ++s)
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+                    k16r[s][jj] = (2 * s + jj < TPH && 16 * (2 * s + jj) + 4 * q < D)
+                                      ? *reinterpret_cast<const uint2*>(kr + 16 * (2 * s + jj)) : make_uint2(0, 0);
+#pragma unroll
+            for (int k = 0; k < TPS; ++k) {
+                const int jt = sub + SUB * k;  // this wavefront's k-th channel tile of A^ V~ (may lie past the head: clamped)
+                int c = h * D + 16 * jt + r16;
+                c = c < C ? c : C - 1;
+                v16r[k] = *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 4 * q);
+            }
+        }
+    };
+
     if constexpr (NG == 1 && !CORE) {
         // ---- phase 0: issue every global read up front, oldest first in the order of use (loads return in
         // order): hidden tile, weight scales, this head's to_q weight slice, the K~/V~ image
@@ -296,7 +332,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             __builtin_amdgcn_sched_barrier(0);
         }
         if (tid < 16 * TOK && dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc0;
-        // ---- weight scales and the K~/V~ image into LDS
+        // ---- weight scales into LDS
     #pragma unroll
         for (int k = 0; k < SCV; ++k) {
             const int i = tid + k * NT;
@@ -391,16 +427,6 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
     __syncthreads();
 
-    const float* swq = wsc;
-    const float* swo = wsc + C;
-    const float* bo = wsc + 2 * C;
-    unsigned char* imgh = img + (size_t)hl * dm.I.head_bytes;  // this head's block of the K~/V~ image
-    const float* img_sk = reinterpret_cast<const float*>(imgh + dm.I.s_k);
-    const float* img_svp = reinterpret_cast<const float*>(imgh + dm.I.s_vp);
-    const float* img_bias = reinterpret_cast<const float*>(imgh + dm.I.bias);
-    const __half* k16 = reinterpret_cast<const __half*>(packed + dm.L.k16) + (size_t)b * T * C;
-    const __half* v16t = reinterpret_cast<const __half*>(packed + dm.L.v16t) + (size_t)b * C * 96;
-
     // this lane's two image tokens: tile rows r16 and 16 + r16
     bool nvalid[NTT];
     size_t tok[NTT];
@@ -410,31 +436,6 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         nvalid[nt] = n < N;
         tok[nt] = (size_t)b * N + (n < N ? n : N - 1);
     }
-
-    // protected (trigger) rows of this head, first tile of 16: fp16 K rows and transposed V rows straight from
-    // global memory into MFMA operand registers (slots past the protected tokens hold zeros; K channels past the
-    // head are not read: they would belong to the next head, or lie past the last row of the last head, and a
-    // non-finite bit pattern there would survive the multiplication with a zero Q~ code)
-    uint2 k16r[FS][2], v16r[TPS];
-    auto load_protected = [&]() {
-        if (nfp > 0) {
-            const int slot = r16 < T ? r16 : T - 1;
-            const __half* kr = k16 + (size_t)slot * C + h * D + 4 * q;
-#pragma unroll
-            for (int s = 0; s < FS; ++s)
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj)
-                    k16r[s][jj] = (2 * s + jj < TPH && 16 * (2 * s + jj) + 4 * q < D)
-                                      ? *reinterpret_cast<const uint2*>(kr + 16 * (2 * s + jj)) : make_uint2(0, 0);
-#pragma unroll
-            for (int k = 0; k < TPS; ++k) {
-                const int jt = sub + SUB * k;  // this wavefront's k-th channel tile of A^ V~ (may lie past the head: clamped)
-                int c = h * D + 16 * jt + r16;
-                c = c < C ? c : C - 1;
-                v16r[k] = *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 4 * q);
-            }
-        }
-    };
 
     // ================= to_q for this head: Qf^T[c][n]
     int32x4_t hb[NTT][NG == 1 && RING == 0 ? KC : 1];
@@ -613,20 +614,13 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 
     // the head's image block travelled meanwhile; it is private to this wavefront: wait (vmcnt(0)), no barrier
     __builtin_amdgcn_s_waitcnt(0x0F70);
-    if (F::PREFETCH_W && !CORE) {  // to_out's weight slice travels while the attention runs
-#pragma unroll
-        for (int j = 0; j < TPH; ++j)
-#pragma unroll
-            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = load_w(rq.wo, j, wstep * ks);
-    }
     if constexpr (RING > 0 && NTT == 1) {  // ... or its first RING loads
 #pragma unroll
         for (int f = 0; f < RING; ++f) wring[f] = load_w(rq.wo, f % TPH, wstep * (f / TPH));
     }
 
-
     // ================= scores: x[t][n] = (K~ Q~^T)[t][n] * s_K[t]   (times sQ * sigma * log2 e later)
-    float S[NTT][6][4], Sf[NTT][6][4];
+    float S[NTT][6][4];
     {
         int32x4_t qop[NTT][KS];  // B operand: dword jj of step ks = codes of tile 4*ks + jj
 #pragma unroll
@@ -666,72 +660,82 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 }
             }
         }
-        // protected rows: fp16 K rows straight from global memory (a handful of rows)
-        if (nfp > 0) {
-            half8_t qh[NTT][FS];  // Q~ codes as fp16: step s covers tiles 2s, 2s+1
-#pragma unroll
-            for (int nt = 0; nt < NTT; ++nt)
-#pragma unroll
-                for (int s = 0; s < FS; ++s) {
-                    half2_t c0 = {(_Float16)0.f, (_Float16)0.f}, c1 = c0, c2 = c0, c3 = c0;
-                    biased4_to_half(qpk[nt][2 * s] ^ 0x80808080u, c0, c1);
-                    if (2 * s + 1 < TPH) biased4_to_half(qpk[nt][2 * s + 1 < TPH ? 2 * s + 1 : 0] ^ 0x80808080u, c2, c3);
-                    qh[nt][s] = (half8_t){c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
-                }
-#pragma unroll
-            for (int ft = 0; ft < 6; ++ft) {
-                if (ft < nfp) {
-                    floatx4_t facc[NTT];
-#pragma unroll
-                    for (int nt = 0; nt < NTT; ++nt) facc[nt] = (floatx4_t){0.f, 0.f, 0.f, 0.f};
-                    int slot = 16 * ft + r16;
-                    slot = slot < T ? slot : T - 1;
-                    const __half* kr = k16 + (size_t)slot * C + h * D + 4 * q;
-#pragma unroll
-                    for (int s = 0; s < FS; ++s) {
-                        half8_t ka;
-#pragma unroll
-                        for (int jj = 0; jj < 2; ++jj) {
-                            const int j = 2 * s + jj;
-                            uint2 w = make_uint2(0, 0);
-                            if (ft == 0) w = k16r[s][jj];
-                            else if (j < TPH && 16 * j + 4 * q < D) w = *reinterpret_cast<const uint2*>(kr + 16 * j);
-                            const half4_t hv = *reinterpret_cast<const half4_t*>(&w);
-                            ka[4 * jj + 0] = hv[0];
-                            ka[4 * jj + 1] = hv[1];
-                            ka[4 * jj + 2] = hv[2];
-                            ka[4 * jj + 3] = hv[3];
-                        }
-#pragma unroll
-                        for (int nt = 0; nt < NTT; ++nt) facc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qh[nt][s], facc[nt], 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const bool live = 16 * ft + 4 * q + i < ntrig;
-#pragma unroll
-                        for (int nt = 0; nt < NTT; ++nt) Sf[nt][ft][i] = live ? facc[nt][i] : TAQ_NEG_INF;
-                    }
-                }
-            }
-        }
     }
+    // protected rows: fp16 K rows (the first 16 from registers, further ones straight from global memory: a handful of
+    // rows). Their scores are formed twice by a run-time loop over tiles of 16 protected tokens, once for the row
+    // maximum and once more for the exponentials, which go straight into the MFMAs against the fp16 V rows: only
+    // one tile of protected scores is ever held in registers.
+    half8_t qh[NTT][FS];  // Q~ codes as fp16: step s covers tiles 2s, 2s+1
+    if (nfp > 0) {
+#pragma unroll
+        for (int nt = 0; nt < NTT; ++nt)
+#pragma unroll
+            for (int s = 0; s < FS; ++s) {
+                half2_t c0 = {(_Float16)0.f, (_Float16)0.f}, c1 = c0, c2 = c0, c3 = c0;
+                biased4_to_half(qpk[nt][2 * s] ^ 0x80808080u, c0, c1);
+                if (2 * s + 1 < TPH) biased4_to_half(qpk[nt][2 * s + 1 < TPH ? 2 * s + 1 : 0] ^ 0x80808080u, c2, c3);
+                qh[nt][s] = (half8_t){c0[0], c0[1], c1[0], c1[1], c2[0], c2[1], c3[0], c3[1]};
+            }
+    }
+    // scores of protected tile ft (tokens of slots 16*ft .. 16*ft+15) for this lane's image tokens; -inf past ntrig
+    auto protected_scores = [&](int ft, floatx4_t (&facc)[NTT]) {
+#pragma unroll
+        for (int nt = 0; nt < NTT; ++nt) facc[nt] = (floatx4_t){0.f, 0.f, 0.f, 0.f};
+        int slot = 16 * ft + r16;
+        slot = slot < T ? slot : T - 1;
+        const __half* kr = k16 + (size_t)slot * C + h * D + 4 * q;
+#pragma unroll
+        for (int s = 0; s < FS; ++s) {
+            half8_t ka;
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const int j = 2 * s + jj;
+                uint2 w = k16r[s][jj];
+                if (ft > 0) w = (j < TPH && 16 * j + 4 * q < D) ? *reinterpret_cast<const uint2*>(kr + 16 * j) : make_uint2(0, 0);
+                const half4_t hv = *reinterpret_cast<const half4_t*>(&w);
+                ka[4 * jj + 0] = hv[0];
+                ka[4 * jj + 1] = hv[1];
+                ka[4 * jj + 2] = hv[2];
+                ka[4 * jj + 3] = hv[3];
+            }
+#pragma unroll
+            for (int nt = 0; nt < NTT; ++nt) facc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qh[nt][s], facc[nt], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool live = 16 * ft + 4 * q + i < ntrig;
+#pragma unroll
+            for (int nt = 0; nt < NTT; ++nt) facc[nt][i] = live ? facc[nt][i] : TAQ_NEG_INF;
+        }
+    };
 
     // ================= softmax over the text tokens; Eq. (3); weights of O^T = V~^T A^^T
     float kq[NTT];   // code = rint(E * kq): pmax / Z per image token (row-range grid: pmax / largest unprotected E)
     float kqp[NTT];  // protected columns: weight = E * kqp = pmax * A
     float lz[NTT];   // log2 Z (log2 grid only)
     float rz[NTT], fz[NTT];  // row-range grid only: Z / range and range / Z, which move between the two units
+    float mxs[NTT];  // row maximum of the raw scores
 #pragma unroll
     for (int nt = 0; nt < NTT; ++nt) {
         float mx = TAQ_NEG_INF;
 #pragma unroll
         for (int tt = 0; tt < 6; ++tt)
             if (tt < dm.nt16) mx = fmaxf(mx, fmaxf(fmaxf(S[nt][tt][0], S[nt][tt][1]), fmaxf(S[nt][tt][2], S[nt][tt][3])));
+        mxs[nt] = mx;
+    }
+    for (int ft = 0; ft < nfp; ++ft) {  // first pass over the protected tiles: their share of the row maximum
+        floatx4_t facc[NTT];
+        protected_scores(ft, facc);
 #pragma unroll
-        for (int ft = 0; ft < 6; ++ft)
-            if (ft < nfp) mx = fmaxf(mx, fmaxf(fmaxf(Sf[nt][ft][0], Sf[nt][ft][1]), fmaxf(Sf[nt][ft][2], Sf[nt][ft][3])));
-        mx = quad_allmax(mx);
+        for (int nt = 0; nt < NTT; ++nt)
+            mxs[nt] = fmaxf(mxs[nt], fmaxf(fmaxf(facc[nt][0], facc[nt][1]), fmaxf(facc[nt][2], facc[nt][3])));
+    }
+    float Zs[NTT], eus[NTT], offs[NTT];
+#pragma unroll
+    for (int nt = 0; nt < NTT; ++nt) {
+        const float mx = quad_allmax(mxs[nt]);
         const float sc = sq2[nt], off = -mx * sc;
+        offs[nt] = off;
         float Z = 0.f, eu = 0.f;
 #pragma unroll
         for (int tt = 0; tt < 6; ++tt)
@@ -745,32 +749,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                     S[nt][tt][i] = LOGP ? arg : ex;  // the log2 grid rounds the exponent itself
                 }
             }
-#pragma unroll
-        for (int ft = 0; ft < 6; ++ft)
-            if (ft < nfp) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    Sf[nt][ft][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(Sf[nt][ft][i], sc, off));
-                    Z += Sf[nt][ft][i];
-                }
-            }
-        Z = quad_allsum(Z);
-        kqp[nt] = dm.pmax * __builtin_amdgcn_rcpf(Z);
-        kq[nt] = kqp[nt];
-        lz[nt] = LOGP ? __builtin_amdgcn_logf(Z) : 0.f;  // log2 Z >= 0: the largest term of Z is 1
-        rz[nt] = 1.f;
-        fz[nt] = 1.f;
-        if constexpr (ROWMAX) {
-            // codes = rint(pmax * E / range), A^ = code * (range / Z) / pmax. Unprotected columns that together weigh
-            // less than 2^-40 of the row (or none at all) are dropped: their codes would scale a vanishing range.
-            eu = quad_allmax(eu);
-            if (eu > Z * 9.094947e-13f) {
-                const float re = __builtin_amdgcn_rcpf(eu);
-                kq[nt] = dm.pmax * re;
-                rz[nt] = Z * re;
-                fz[nt] = eu * __builtin_amdgcn_rcpf(Z);
-            }
-        }
+        Zs[nt] = Z;
+        eus[nt] = eu;
     }
 
     // oacc[nt][k]: channel tile jt = sub + SUB*k of this head (NG == 1: SUB = 1, every tile; head-group variant: every
@@ -780,48 +760,81 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
         for (int k = 0; k < TPS; ++k) oacc[nt][k] = (floatx4_t){0.f, 0.f, 0.f, 0.f};
-    if (nfp > 0) {
-        // protected columns keep A (Eq. 3): 255*A as fp16 high + low parts against the fp16 V row
-#pragma unroll
-        for (int ft = 0; ft < 6; ++ft) {
-            if (ft < nfp) {
-                half4_t phi[NTT], plo[NTT];
-#pragma unroll
-                for (int nt = 0; nt < NTT; ++nt)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        // high part = fp16(Sf*kq), low part = fp16(Sf*kq - high), each one mixed-precision FMA
-                        const _Float16 xh = (_Float16)__builtin_fmaf(Sf[nt][ft][i], kqp[nt], 0.0f);
-                        phi[nt][i] = xh;
-                        plo[nt][i] = (_Float16)__builtin_fmaf(Sf[nt][ft][i], kqp[nt], -(float)xh);
-                    }
-#pragma unroll
-                for (int k = 0; k < TPS; ++k) {
-                    const int jt = sub + SUB * k;
-                    if (SUB > 1 && jt >= TPH) continue;
-                    int c = h * D + 16 * jt + r16;
-                    c = c < C ? c : C - 1;
-                    const uint2 w = ft == 0 ? v16r[k] : *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 16 * ft + 4 * q);
-                    const half4_t va = *reinterpret_cast<const half4_t*>(&w);  // slots past ntrig hold zeros
-#pragma unroll
-                    for (int nt = 0; nt < NTT; ++nt) {
-                        oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, phi[nt], oacc[nt][k], 0, 0, 0);
-                        oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, plo[nt], oacc[nt][k], 0, 0, 0);
-                    }
-                }
-            }
-        }
-        const float vpre = reinterpret_cast<const float*>(imgh + dm.I.vpre)[0];
+    // protected columns keep A (Eq. 3). Second pass over the protected tiles: E = exp2(score - max), not yet divided
+    // by Z, as fp16 high + low parts against the fp16 V rows; the accumulators are brought to the unit of the
+    // unprotected columns' weights (pmax * A * 2^kexp) once Z is known.
+    for (int ft = 0; ft < nfp; ++ft) {
+        floatx4_t facc[NTT];
+        protected_scores(ft, facc);
+        half4_t phi[NTT], plo[NTT];
 #pragma unroll
         for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float ex = __builtin_amdgcn_exp2f(__builtin_fmaf(facc[nt][i], sq2[nt], offs[nt]));
+                Zs[nt] += ex;
+                const _Float16 xh = (_Float16)ex;
+                phi[nt][i] = xh;
+                plo[nt][i] = (_Float16)(ex - (float)xh);
+            }
+#pragma unroll
+        for (int k = 0; k < TPS; ++k) {
+            const int jt = sub + SUB * k;
+            if (SUB > 1 && jt >= TPH) continue;
+            int c = h * D + 16 * jt + r16;
+            c = c < C ? c : C - 1;
+            uint2 w = v16r[k];
+            if (ft > 0) w = *reinterpret_cast<const uint2*>(v16t + (size_t)c * 96 + 16 * ft + 4 * q);
+            const half4_t va = *reinterpret_cast<const half4_t*>(&w);  // slots past ntrig hold zeros
+#pragma unroll
+            for (int nt = 0; nt < NTT; ++nt) {
+                oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, phi[nt], oacc[nt][k], 0, 0, 0);
+                oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, plo[nt], oacc[nt][k], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int nt = 0; nt < NTT; ++nt) {
+        const float Z = quad_allsum(Zs[nt]);
+        kqp[nt] = dm.pmax * __builtin_amdgcn_rcpf(Z);
+        kq[nt] = kqp[nt];
+        lz[nt] = LOGP ? __builtin_amdgcn_logf(Z) : 0.f;  // log2 Z >= 0: the largest term of Z is 1
+        rz[nt] = 1.f;
+        fz[nt] = 1.f;
+        if constexpr (ROWMAX) {
+            // codes = rint(pmax * E / range), A^ = code * (range / Z) / pmax. Unprotected columns that together weigh
+            // less than 2^-40 of the row (or none at all) are dropped: their codes would scale a vanishing range.
+            const float eu = quad_allmax(eus[nt]);
+            if (eu > Z * 9.094947e-13f) {
+                const float re = __builtin_amdgcn_rcpf(eu);
+                kq[nt] = dm.pmax * re;
+                rz[nt] = Z * re;
+                fz[nt] = eu * __builtin_amdgcn_rcpf(Z);
+            }
+        }
+    }
+    if (nfp > 0) {
+        const float vpre = reinterpret_cast<const float*>(imgh + dm.I.vpre)[0];
+#pragma unroll
+        for (int nt = 0; nt < NTT; ++nt) {
+            const float f = kqp[nt] * (ROWMAX ? vpre * rz[nt] : vpre);
+#pragma unroll
             for (int k = 0; k < TPS; ++k)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) oacc[nt][k][i] *= ROWMAX ? vpre * rz[nt] : vpre;
+                for (int i = 0; i < 4; ++i) oacc[nt][k][i] *= f;
+        }
     }
-    // unprotected columns: weight = code * (s_V * 2^kexp), split into fp16 high + low parts; V codes exact in fp16
+    // unprotected columns: weight = code * s', s' = s_V * 2^kexp, as fp16 high + low parts (V codes are exact in fp16).
+    // s' comes from the image already split, s' = sh + sl (two fp16 numbers, |sl| <= 2^-11 |sh|). The code c (an integer
+    // below 256) is exact in fp16; in packed fp16 arithmetic, two columns per instruction:
+    //   wh = fl(c * sh),  r = fma(c, sh, -wh)  (the rounding error of wh: exact, it needs at most 8 bits),
+    //   wl = fma(c, sl, r)                      => wh + wl = c * s' to about 2^-22, relatively.
+    // The code itself is formed with one FMA: P * kq + (1.5 * 2^23 + 0x6400) rounds P * kq half-to-even to an integer
+    // and leaves 0x6400 + code in the low half of the result: the bit pattern of the fp16 number 1024 + code.
     {
         const uint8_t* vt = imgh + dm.I.vt;
+        const _Float16* img_sv = reinterpret_cast<const _Float16*>(imgh + dm.I.s_vp);  // [96] high parts | [96] low parts
+        const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             if (2 * s < dm.nt16) {
@@ -829,29 +842,35 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 half8_t phi[NTT], plo[NTT];
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
-                    const float4 sv = *reinterpret_cast<const float4*>(img_svp + 16 * (2 * s + a) + 4 * q);
-                    const float svv[4] = {sv.x, sv.y, sv.z, sv.w};
                     if (a == 0 || second) {
+                        const uint2 h4 = *reinterpret_cast<const uint2*>(img_sv + 16 * (2 * s + a) + 4 * q);
+                        const uint2 l4 = *reinterpret_cast<const uint2*>(img_sv + 96 + 16 * (2 * s + a) + 4 * q);
+                        const half2_t sh[2] = {*reinterpret_cast<const half2_t*>(&h4.x), *reinterpret_cast<const half2_t*>(&h4.y)};
+                        const half2_t sl[2] = {*reinterpret_cast<const half2_t*>(&l4.x), *reinterpret_cast<const half2_t*>(&l4.y)};
 #pragma unroll
                         for (int nt = 0; nt < NTT; ++nt)
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                _Float16 wh, wl;
+                            for (int i2 = 0; i2 < 2; ++i2) {
+                                half2_t c;
                                 if constexpr (LOGP) {
-                                    // -code = clip(rint(log2 A)) = clip(rint(arg - log2 Z)); weight 2^(8 - code) * s_V, exact
-                                    const float c = fminf(fmaxf(__builtin_rintf(S[nt][2 * s + a][i] - lz[nt]), -dm.plast), 0.f);
-                                    const float w = ldexpf(svv[i], 8 + (int)c);
-                                    wh = (_Float16)w;
-                                    wl = (_Float16)__builtin_fmaf((float)wh, -1.0f, w);  // w - hi, exact
+                                    // -code = clip(rint(log2 A)) = clip(rint(arg - log2 Z)); weight 2^(8 - code) * s': exact
+                                    // scalings of sh and sl (a weight below fp16's range is below 2^-30 of the largest)
+                                    const float c0 = __builtin_amdgcn_fmed3f(__builtin_rintf(S[nt][2 * s + a][2 * i2] - lz[nt]), -dm.plast, 0.f);
+                                    const float c1 = __builtin_amdgcn_fmed3f(__builtin_rintf(S[nt][2 * s + a][2 * i2 + 1] - lz[nt]), -dm.plast, 0.f);
+                                    const auto pw = __builtin_amdgcn_cvt_pkrtz(ldexpf(256.0f, (int)c0), ldexpf(256.0f, (int)c1));
+                                    c = (half2_t){(_Float16)pw[0], (_Float16)pw[1]};
                                 } else {
-                                    // Eq. (3): weight = code * s_V; high part = fp16(code*s_V), low part = fp16(code*s_V - high),
-                                    // each a single mixed-precision FMA on the exact product
-                                    const float c = __builtin_rintf(S[nt][2 * s + a][i] * kq[nt]);
-                                    wh = (_Float16)__builtin_fmaf(c, svv[i], 0.0f);
-                                    wl = (_Float16)__builtin_fmaf(c, svv[i], -(float)wh);
+                                    const float m0 = __builtin_fmaf(S[nt][2 * s + a][2 * i2], kq[nt], 12608512.0f);
+                                    const float m1 = __builtin_fmaf(S[nt][2 * s + a][2 * i2 + 1], kq[nt], 12608512.0f);
+                                    const unsigned u = __builtin_amdgcn_perm(__float_as_uint(m1), __float_as_uint(m0), 0x05040100u);
+                                    c = *reinterpret_cast<const half2_t*>(&u) - k1024;
                                 }
-                                phi[nt][4 * a + i] = wh;
-                                plo[nt][4 * a + i] = wl;
+                                const half2_t wh = c * sh[i2];
+                                const half2_t wl = __builtin_elementwise_fma(c, sl[i2], __builtin_elementwise_fma(c, sh[i2], -wh));
+                                phi[nt][4 * a + 2 * i2] = wh[0];
+                                phi[nt][4 * a + 2 * i2 + 1] = wh[1];
+                                plo[nt][4 * a + 2 * i2] = wl[0];
+                                plo[nt][4 * a + 2 * i2 + 1] = wl[1];
                             }
                     } else {
 #pragma unroll
@@ -884,6 +903,12 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         }
     }
 
+    if (F::PREFETCH_W && !CORE) {  // to_out's weight slice travels while A^ V~ is quantized (two barriers away from its use)
+#pragma unroll
+        for (int j = 0; j < TPH; ++j)
+#pragma unroll
+            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = load_w(rq.wo, j, wstep * ks);
+    }
     if constexpr (RING > 0 && NTT == 2) {  // two token tiles per wavefront: the attention needs the registers; the first
 #pragma unroll                         // RING loads of to_out travel while A^ V~ is quantized
         for (int f = 0; f < RING; ++f) wring[f] = load_w(rq.wo, f % TPH, wstep * (f / TPH));

@@ -47,7 +47,7 @@ struct KvImage {
     size_t kp;      // i8  [rows_k][tph][4 quarter-lanes][4]  K codes in MFMA operand order (see kp_offset)
     size_t vt;      // u8  [d][cols_v]   V codes (+128) transposed, tokens in accumulator-register order
     size_t s_k;     // f32 [96]  per-token K scale of this head, 0 on protected / padding tokens
-    size_t s_vp;    // f32 [96]  s_V * 2^kexp
+    size_t s_vp;    // f16 [2][96]  s_V * 2^kexp as an fp16 high part [0][t] and the fp16 remainder [1][t]
     size_t bias;    // f32 [96]  0 for unprotected tokens, -inf for protected / padding (same in every head)
     size_t oscale;  // f32       2^-kexp / 255
     size_t vpre;    // f32       2^kexp

@@ -630,7 +630,12 @@ __global__ __launch_bounds__(512) void kv_head_kernel(const int8_t* __restrict__
         }
     }
     const float vpre = ldexpf(1.0f, kexp);
-    if (tid < 96) reinterpret_cast<float*>(img + I.s_vp)[tid] = sc_l[tid] * vpre;
+    if (tid < 96) {  // s' = s_V * 2^kexp as two fp16 numbers, high part and remainder
+        const float sp = sc_l[tid] * vpre;
+        const __half hi = __float2half_rn(sp);
+        reinterpret_cast<__half*>(img + I.s_vp)[tid] = hi;
+        reinterpret_cast<__half*>(img + I.s_vp)[96 + tid] = __float2half_rn(sp - __half2float(hi));
+    }
     if (tid == 0) {
         reinterpret_cast<float*>(img + I.vpre)[0] = vpre;
         reinterpret_cast<float*>(img + I.oscale)[0] = ldexpf(1.0f, -kexp);
