@@ -9,7 +9,7 @@ namespace taq {
 // operands are read in, and precomputes the per-head power-of-two prescale of V.
 //   per head h:  Kp[t][tile][q][e] = k_code[t][h*d + 16*tile + 4*q + e]         (0 outside d / T; heads with a
 //                multiple of 4 tiles use the order [t][tile/4][q][tile%4][e])
-//                Vt[j][32*s + 8*q + 4*a + e] = v_code[t = 32*s + 16*a + 4*q + e][h*d + j] ^ 0x80
+//                Vt[j][vt_pos(t)] = v_code[t][h*d + j] ^ 0x80   (vt_pos: 32*s + 8*q + 4*a + e for t = 32*s + 16*a + 4*q + e)
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ int code_at(const uint8_t* codes, size_t row, int C, int c, int bits) {
     if (bits == 8) return (int8_t)codes[row * C + c];
@@ -46,13 +46,13 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
         }
     }
     __syncthreads();
-    for (int t = tid; t < 96; t += nth) {
+    for (int t = tid; t < I.ntok; t += nth) {
         const bool isint = t < T && slot_of[t] < 0;
         reinterpret_cast<float*>(img + I.s_k)[t] = isint ? s_k[t] : 0.f;
         const float sp = isint ? s_v[t] * vpre_s : 0.f;  // s' = s_V * 2^kexp as two fp16 numbers, high part and remainder
         const __half sph = __float2half_rn(sp);
         reinterpret_cast<__half*>(img + I.s_vp)[t] = sph;
-        reinterpret_cast<__half*>(img + I.s_vp)[96 + t] = __float2half_rn(sp - __half2float(sph));
+        reinterpret_cast<__half*>(img + I.s_vp)[I.ntok + t] = __float2half_rn(sp - __half2float(sph));
         reinterpret_cast<float*>(img + I.bias)[t] = isint ? 0.f : TAQ_NEG_INF;
     }
     const int rowb = I.tph * 16;  // bytes per (head, token) row of Kp
@@ -64,14 +64,12 @@ __global__ __launch_bounds__(256) void kv_image_kernel(uint8_t* __restrict__ pac
         img[I.kp + kp_offset(I.tph, t, tile, q) + e] = (uint8_t)(v & 0xFF);
     }
     for (int i = tid; i < d * I.cols_v; i += nth) {
-        const int p = i % I.cols_v, j = i / I.cols_v;
-        const int s = p >> 5, q = (p >> 3) & 3, a = (p >> 2) & 1, e = p & 3;
-        const int t = 32 * s + 16 * a + 4 * q + e;
+        const int t = i % I.cols_v, j = i / I.cols_v;  // token t of channel j goes to position vt_pos(t)
         int v = 0;
         if (t < T && slot_of[t] < 0) v = code_at(v_code, (size_t)b * T + t, C, h * d + j, bits);
         // stored with the sign bit flipped (code + 128 as an unsigned byte): 0x6400 | byte is then the
         // fp16 number 1024 + 128 + code, one packed subtraction away from the code itself
-        img[I.vt + i] = (uint8_t)((v & 0xFF) ^ 0x80);
+        img[I.vt + (size_t)j * I.cols_v + vt_pos(t, I.nt16)] = (uint8_t)((v & 0xFF) ^ 0x80);
     }
 }
 

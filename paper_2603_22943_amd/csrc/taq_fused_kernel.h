@@ -174,7 +174,9 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // NG > 1 (layers too wide for one workgroup's LDS): the workgroup owns one head group (NH of the NH*NG
 // heads), takes the per-token codes of `hidden` from the workspace, and stops after A^ V~, which it writes to
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
-template <int D, int NH, int NTT, int NG, int PG, int TOK = 32, bool CORE = false>
+// NT16 > 0: the number of 16-token score tiles, ceil(T / 16), is this compile-time constant (5 for the 77 text tokens
+// of every configured workload: no run-time guards around the tiles); NT16 = 0: any T up to 96, guards at run time.
+template <int D, int NH, int NTT, int NG, int PG, int TOK = 32, bool CORE = false, int NT16 = 0>
 __global__ __launch_bounds__(NG > 1 ? 512 : 64 * NH * (TOK / (16 * NTT)))
 __attribute__((amdgpu_waves_per_eu(1, NG > 1 ? 2 : (NH * (TOK / (16 * NTT)) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
@@ -184,6 +186,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
     constexpr int SUB = F::SUB, TPS = F::TPS;
     constexpr bool LOGP = PG == TAQ_PROB_LOG2, ROWMAX = PG == TAQ_PROB_ROWMAX;  // grid of the probabilities, Eq. (3)
+    constexpr int MT16 = NT16 ? NT16 : 6;  // score tiles the code is unrolled for
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, hl = (tid >> 6) % NH, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
@@ -199,6 +202,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     const int ri = rb / dm.B, b = rb % dm.B;
     const FusedReq rq = tab.req[ri];
     const int N = dm.N, T = dm.T;
+    const int nt16 = NT16 ? NT16 : dm.nt16;
     const int n0 = tile * TOK;
 
     // ---- LDS carve-up
@@ -558,10 +562,12 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         const int last = (int)dm.I.head_bytes - 1024;  // the block is a multiple of 256 bytes: the last piece overlaps
 #pragma unroll
         for (int k = 0; k < F::IMGC; ++k) {
-            const int c = k * 1024 < last ? k * 1024 : last;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(gsrc + c + lane * 16),
-                (__attribute__((address_space(3))) void*)(imgh + c), 16, 0, 0);
+            if (k == 0 || k * 1024 < last + 1024) {  // (pieces past the block's end at this T are not fetched)
+                const int c = k * 1024 < last ? k * 1024 : last;
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(gsrc + c + lane * 16),
+                    (__attribute__((address_space(3))) void*)(imgh + c), 16, 0, 0);
+            }
         }
     }
     if constexpr (NG == 1) load_protected();
@@ -620,7 +626,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 
     // ================= scores: x[t][n] = (K~ Q~^T)[t][n] * s_K[t]   (times sQ * sigma * log2 e later)
-    float S[NTT][6][4];
+    float S[NTT][MT16][4];
     {
         int32x4_t qop[NTT][KS];  // B operand: dword jj of step ks = codes of tile 4*ks + jj
 #pragma unroll
@@ -631,8 +637,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 for (int jj = 0; jj < 4; ++jj) qop[nt][ks][jj] = (4 * ks + jj < TPH) ? (int)qpk[nt][4 * ks + jj] : 0;
         const int8_t* kp = reinterpret_cast<const int8_t*>(imgh + dm.I.kp);
 #pragma unroll
-        for (int tt = 0; tt < 6; ++tt) {
-            if (tt < dm.nt16) {
+        for (int tt = 0; tt < MT16; ++tt) {
+            if (tt < nt16) {
                 int32x4_t acc[NTT];
 #pragma unroll
                 for (int nt = 0; nt < NTT; ++nt) acc[nt] = (int32x4_t){0, 0, 0, 0};
@@ -719,8 +725,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     for (int nt = 0; nt < NTT; ++nt) {
         float mx = TAQ_NEG_INF;
 #pragma unroll
-        for (int tt = 0; tt < 6; ++tt)
-            if (tt < dm.nt16) mx = fmaxf(mx, fmaxf(fmaxf(S[nt][tt][0], S[nt][tt][1]), fmaxf(S[nt][tt][2], S[nt][tt][3])));
+        for (int tt = 0; tt < MT16; ++tt)
+            if (tt < nt16) mx = fmaxf(mx, fmaxf(fmaxf(S[nt][tt][0], S[nt][tt][1]), fmaxf(S[nt][tt][2], S[nt][tt][3])));
         mxs[nt] = mx;
     }
     for (int ft = 0; ft < nfp; ++ft) {  // first pass over the protected tiles: their share of the row maximum
@@ -738,8 +744,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         offs[nt] = off;
         float Z = 0.f, eu = 0.f;
 #pragma unroll
-        for (int tt = 0; tt < 6; ++tt)
-            if (tt < dm.nt16) {
+        for (int tt = 0; tt < MT16; ++tt)
+            if (tt < nt16) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float arg = __builtin_fmaf(S[nt][tt][i], sc, off);
@@ -833,18 +839,18 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     // and leaves 0x6400 + code in the low half of the result: the bit pattern of the fp16 number 1024 + code.
     {
         const uint8_t* vt = imgh + dm.I.vt;
-        const _Float16* img_sv = reinterpret_cast<const _Float16*>(imgh + dm.I.s_vp);  // [96] high parts | [96] low parts
+        const _Float16* img_sv = reinterpret_cast<const _Float16*>(imgh + dm.I.s_vp);  // [ntok] high parts | [ntok] low parts
         const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
-            if (2 * s < dm.nt16) {
-                const bool second = 2 * s + 1 < dm.nt16;
+            if (2 * s < nt16) {
+                const bool second = 2 * s + 1 < nt16;
                 half8_t phi[NTT], plo[NTT];
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
                     if (a == 0 || second) {
                         const uint2 h4 = *reinterpret_cast<const uint2*>(img_sv + 16 * (2 * s + a) + 4 * q);
-                        const uint2 l4 = *reinterpret_cast<const uint2*>(img_sv + 96 + 16 * (2 * s + a) + 4 * q);
+                        const uint2 l4 = *reinterpret_cast<const uint2*>(img_sv + dm.I.ntok + 16 * (2 * s + a) + 4 * q);
                         const half2_t sh[2] = {*reinterpret_cast<const half2_t*>(&h4.x), *reinterpret_cast<const half2_t*>(&h4.y)};
                         const half2_t sl[2] = {*reinterpret_cast<const half2_t*>(&l4.x), *reinterpret_cast<const half2_t*>(&l4.y)};
 #pragma unroll
@@ -888,15 +894,29 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                     if (SUB > 1 && jt >= TPH) continue;
                     int j = 16 * jt + r16;
                     j = j < D ? j : D - 1;
-                    const uint2 w = *reinterpret_cast<const uint2*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 8 * q);
-                    half2_t v0, v1, v2, v3;
-                    biased4_to_half(w.x, v0, v1);
-                    biased4_to_half(w.y, v2, v3);
-                    const half8_t va = {v0[0], v0[1], v1[0], v1[1], v2[0], v2[1], v3[0], v3[1]};
+                    if (second) {  // two score tiles: 32 tokens deep, a lane's 8 codes are consecutive (vt_pos)
+                        const uint2 w = *reinterpret_cast<const uint2*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 8 * q);
+                        half2_t v0, v1, v2, v3;
+                        biased4_to_half(w.x, v0, v1);
+                        biased4_to_half(w.y, v2, v3);
+                        const half8_t va = {v0[0], v0[1], v1[0], v1[1], v2[0], v2[1], v3[0], v3[1]};
 #pragma unroll
-                    for (int nt = 0; nt < NTT; ++nt) {
-                        oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, phi[nt], oacc[nt][k], 0, 0, 0);
-                        oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, plo[nt], oacc[nt][k], 0, 0, 0);
+                        for (int nt = 0; nt < NTT; ++nt) {
+                            oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, phi[nt], oacc[nt][k], 0, 0, 0);
+                            oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, plo[nt], oacc[nt][k], 0, 0, 0);
+                        }
+                    } else {       // a last single tile: 16 tokens deep, in their natural order
+                        const unsigned w = *reinterpret_cast<const unsigned*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 4 * q);
+                        half2_t v0, v1;
+                        biased4_to_half(w, v0, v1);
+                        const half4_t va = {v0[0], v0[1], v1[0], v1[1]};
+#pragma unroll
+                        for (int nt = 0; nt < NTT; ++nt) {
+                            const half4_t ph = {phi[nt][0], phi[nt][1], phi[nt][2], phi[nt][3]};
+                            const half4_t pl = {plo[nt][0], plo[nt][1], plo[nt][2], plo[nt][3]};
+                            oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, ph, oacc[nt][k], 0, 0, 0);
+                            oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x16f16(va, pl, oacc[nt][k], 0, 0, 0);
+                        }
                     }
                 }
             }
@@ -1024,18 +1044,21 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 }
 
-template <int D, int NH, int NTT, int NG, int PG, int TOK, bool CORE>
+template <int D, int NH, int NTT, int NG, int PG, int TOK, bool CORE, int NT16 = 0>
 static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
+    if constexpr (NT16 == 0) {  // 65 to 80 text tokens: the instantiation without run-time guards around the score tiles
+        if (dm.nt16 == 5) return launch_fused_grid<D, NH, NTT, NG, PG, TOK, CORE, 5>(tab, dm, st);
+    }
     using F = FusedCfg<D, NH, NTT, NG, TOK>;
     static std::atomic<unsigned long long> lds_set{0};
     const size_t bytes = NG == 1 ? dm.I.bytes + TOK * F::TILE_RS + 3 * F::C * 4 + TOK * 4 + TOK * NH * 4  // = fused_lds_bytes
                                  : (size_t)NH * dm.I.head_bytes + TOK * F::TILE_RS + NH * D * 4 + TOK * 4 +
                                        (F::NT / 128) * (TOK / 16) * NH * F::TPH * 1024;  // = mid_lds_bytes at TOK = 32
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
-    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE>), 160 * 1024, lds_set);
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE, NT16>), 160 * 1024, lds_set);
     if (e != hipSuccess) return e;
     const int tiles = (dm.N + TOK - 1) / TOK;
-    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
+    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE, NT16>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 

@@ -42,13 +42,15 @@ struct KvLayout {
 // the direct-to-LDS copy).
 struct KvImage {
     int tph;        // 16-channel tiles per head = ceil(d/16)
-    int rows_k;     // 16*ceil(T/16) text-token rows of the K part
-    int cols_v;     // 32*ceil(T/32) token positions per V^T row
+    int nt16;       // ceil(T/16): score tiles of 16 text tokens
+    int ntok;       // 16*nt16: text tokens with padding; length of the per-token arrays below
+    int rows_k;     // = ntok: text-token rows of the K part
+    int cols_v;     // = ntok: token positions per V^T row (see vt_pos)
     size_t kp;      // i8  [rows_k][tph][4 quarter-lanes][4]  K codes in MFMA operand order (see kp_offset)
     size_t vt;      // u8  [d][cols_v]   V codes (+128) transposed, tokens in accumulator-register order
-    size_t s_k;     // f32 [96]  per-token K scale of this head, 0 on protected / padding tokens
-    size_t s_vp;    // f16 [2][96]  s_V * 2^kexp as an fp16 high part [0][t] and the fp16 remainder [1][t]
-    size_t bias;    // f32 [96]  0 for unprotected tokens, -inf for protected / padding (same in every head)
+    size_t s_k;     // f32 [ntok]  per-token K scale of this head, 0 on protected / padding tokens
+    size_t s_vp;    // f16 [2][ntok]  s_V * 2^kexp as an fp16 high part [0][t] and the fp16 remainder [1][t]
+    size_t bias;    // f32 [ntok]  0 for unprotected tokens, -inf for protected / padding (same in every head)
     size_t oscale;  // f32       2^-kexp / 255
     size_t vpre;    // f32       2^kexp
     size_t head_bytes;  // one head's block, a multiple of 256 bytes
@@ -66,19 +68,30 @@ __host__ __device__ static inline size_t kp_offset(int tph, int t, int j, int q)
     return (((size_t)t * tph + j) * 4 + q) * 4;
 }
 
+// Place of text token t in a V^T row of the image. Tokens come in steps of 32 (two score tiles of 16), permuted within
+// a step to the accumulator-register order of the score MFMA: token 32*s + 16*a + 4*q + e sits at 32*s + 8*q + 4*a + e,
+// so that a lane's 8 probabilities of the step meet 8 consecutive V codes. A last single tile (nt16 odd) keeps its
+// natural order 4*q + e: it is contracted with a 16-deep MFMA.
+__host__ __device__ static inline int vt_pos(int t, int nt16) {
+    if ((nt16 & 1) && (t >> 4) == nt16 - 1) return t;
+    return (t & ~31) + 8 * ((t >> 2) & 3) + 4 * ((t >> 4) & 1) + (t & 3);
+}
+
 static inline KvImage kv_image(const taq_shape& s) {
     KvImage I;
     const size_t H = s.H, d = s.C / s.H;
     I.tph = (int)((d + 15) / 16);
-    I.rows_k = 16 * ((s.T + 15) / 16);
-    I.cols_v = 32 * ((s.T + 31) / 32);
+    I.nt16 = (s.T + 15) / 16;
+    I.ntok = 16 * I.nt16;
+    I.rows_k = I.ntok;
+    I.cols_v = I.ntok;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 16); return o; };
     I.kp = take(I.rows_k * (size_t)I.tph * 16);
     I.vt = take(d * (size_t)I.cols_v);
-    I.s_k = take(96 * 4);
-    I.s_vp = take(96 * 4);
-    I.bias = take(96 * 4);
+    I.s_k = take(I.ntok * 4);
+    I.s_vp = take(I.ntok * 4);
+    I.bias = take(I.ntok * 4);
     I.oscale = take(4);
     I.vpre = take(4);
     I.head_bytes = align_up(off, 256);  // (at least 1 KiB: the kernels copy it in 1 KiB pieces, the last one overlapping)

@@ -454,7 +454,7 @@ __device__ __forceinline__ void kvh_finish(const kvh_int32x4_t (&acc)[TPH], int 
         sc_l[t] = sc;
         atomicMax(scmax, __float_as_uint(sc));
     }
-    const int pos = (t & ~31) + 8 * ((t >> 2) & 3) + 4 * ((t >> 4) & 1) + (t & 3);  // place of token t in a V^T row
+    const int pos = vt_pos(t, I.nt16);  // place of token t in a V^T row
 #pragma unroll
     for (int j = 0; j < TPH; ++j) {
         const int cl = 16 * j + 4 * q;
@@ -613,7 +613,7 @@ __global__ __launch_bounds__(512) void kv_head_kernel(const int8_t* __restrict__
     if (!has_image) return;
     __syncthreads();
     if (!side) {  // token scales of K and the 0 / -inf token bias
-        if (tid < 96) {
+        if (tid < I.ntok) {
             reinterpret_cast<float*>(img + I.s_k)[tid] = sc_l[tid];
             reinterpret_cast<float*>(img + I.bias)[tid] = sc_l[tid] != 0.f ? 0.f : TAQ_NEG_INF;  // an unprotected token's scale is never 0
         }
@@ -630,11 +630,11 @@ __global__ __launch_bounds__(512) void kv_head_kernel(const int8_t* __restrict__
         }
     }
     const float vpre = ldexpf(1.0f, kexp);
-    if (tid < 96) {  // s' = s_V * 2^kexp as two fp16 numbers, high part and remainder
+    if (tid < I.ntok) {  // s' = s_V * 2^kexp as two fp16 numbers, high part and remainder
         const float sp = sc_l[tid] * vpre;
         const __half hi = __float2half_rn(sp);
         reinterpret_cast<__half*>(img + I.s_vp)[tid] = hi;
-        reinterpret_cast<__half*>(img + I.s_vp)[96 + tid] = __float2half_rn(sp - __half2float(hi));
+        reinterpret_cast<__half*>(img + I.s_vp)[I.ntok + tid] = __float2half_rn(sp - __half2float(hi));
     }
     if (tid == 0) {
         reinterpret_cast<float*>(img + I.vpre)[0] = vpre;
