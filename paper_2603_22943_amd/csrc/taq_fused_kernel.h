@@ -76,7 +76,7 @@ struct FusedDims {
     const float* ws_so;      // f32 [B*N]     ... and their scales
 };
 
-template <int D, int NH, int NTT, int NG, int TOK = 32>
+template <int D, int NH, int NTT, int NG, int TOK = 32, bool DENSE = false>
 struct FusedCfg {
     static constexpr int G = TOK / (16 * NTT);    // wavefronts per head (token groups of 16*NTT tokens)
     static constexpr int H = NH * NG;             // heads of the layer; a workgroup owns NH of them
@@ -96,13 +96,15 @@ struct FusedCfg {
     // bytes of one head's image block at T = 96, in 1 KiB pieces (one direct-to-LDS load each)
     static constexpr int IMG_HEAD_MAX = 96 * TPH * 16 + D * 96 + 3 * 96 * 4 + 32;
     static constexpr int IMGC = (IMG_HEAD_MAX + 1023) / 1024;
-    static constexpr bool PREFETCH_W = TPH * KC <= 16 && NTT == 2 && NG == 1;  // a head's whole weight slice in registers
+    // DENSE: the instantiation meant to run two workgroups per compute unit (layers with more token tiles than compute
+    // units): at most 128 registers per lane, so the weights pass through a short ring instead of sitting in registers.
+    static constexpr bool PREFETCH_W = TPH * KC <= 16 && NTT == 2 && NG == 1 && !DENSE;  // a head's whole weight slice in registers
     // Otherwise a ring of RING weight loads stays in flight ahead of the projection MFMAs (K step outermost, so that
     // only one step's B operands are live); left to itself the compiler keeps one to ten loads ahead and the loop
     // waits on latency.
     static constexpr int NF = TPH * KC;  // weight loads (16 rows x 64 bytes) of one projection per wavefront
     // two wavefronts per SIMD (256 registers each), or three at ten heads (168)
-    static constexpr int RING_MAX = NH <= 8 ? (NTT == 1 ? 32 : 24) : (NTT == 1 ? 12 : 8);
+    static constexpr int RING_MAX = DENSE ? 6 : NH <= 8 ? (NTT == 1 ? 32 : 24) : (NTT == 1 ? 12 : 8);
     static constexpr int RING = (!PREFETCH_W && NG == 1) ? (NF < RING_MAX ? NF : RING_MAX) : 0;
 };
 
@@ -175,18 +177,21 @@ __device__ __forceinline__ void biased4_to_half(unsigned w, half2_t& a, half2_t&
 // heads), takes the per-token codes of `hidden` from the workspace, and stops after A^ V~, which it writes to
 // the workspace as float32; the per-token quantization of that result and to_out run as separate kernels.
 // NT16 > 0: the number of 16-token score tiles, ceil(T / 16), is this compile-time constant (5 for the 77 text tokens
-// of every configured workload: no run-time guards around the tiles); NT16 = 0: any T up to 96, guards at run time.
-template <int D, int NH, int NTT, int NG, int PG, int TOK = 32, bool CORE = false, int NT16 = 0>
+// of every configured workload: no run-time guards around the tiles) and the taps on intermediate results are
+// compiled out; NT16 = 0: any T up to 96, guards at run time, taps where the caller asks for them.
+template <int D, int NH, int NTT, int NG, int PG, int TOK = 32, bool CORE = false, int NT16 = 0, bool DENSE = false>
 __global__ __launch_bounds__(NG > 1 ? 512 : 64 * NH * (TOK / (16 * NTT)))
-__attribute__((amdgpu_waves_per_eu(1, NG > 1 ? 2 : (NH * (TOK / (16 * NTT)) + 3) / 4)))
+__attribute__((amdgpu_waves_per_eu(DENSE ? 4 : 1, DENSE ? 4 : NG > 1 ? 2 : (NH * (TOK / (16 * NTT)) + 3) / 4)))
 void fused_block_kernel(FusedTable tab, FusedDims dm) {
-    using F = FusedCfg<D, NH, NTT, NG, TOK>;
+    using F = FusedCfg<D, NH, NTT, NG, TOK, DENSE>;
+    static_assert(!DENSE || (NG == 1 && !CORE && NH * (TOK / (16 * NTT)) == 8), "two 8-wavefront workgroups per compute unit");
     static_assert(TOK == 32 || (TOK == 16 && NTT == 1), "a workgroup owns 32 image tokens, or 16 with one tile per wavefront");
     static_assert(!CORE || NG == 1, "the attention-core-only variant exists for the single-kernel shapes");
     constexpr int C = F::C, H = F::H, TPH = F::TPH, KS = F::KS, FS = F::FS, KC = F::KC, NT = F::NT;
     constexpr int SUB = F::SUB, TPS = F::TPS;
     constexpr bool LOGP = PG == TAQ_PROB_LOG2, ROWMAX = PG == TAQ_PROB_ROWMAX;  // grid of the probabilities, Eq. (3)
     constexpr int MT16 = NT16 ? NT16 : 6;  // score tiles the code is unrolled for
+    constexpr bool TAPS = NT16 == 0;       // taps of intermediate codes and scales (tests, profiling)
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, hl = (tid >> 6) % NH, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
@@ -331,11 +336,11 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             if (tid < 16 * TOK) {
                 const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq0, safe0);
                 *reinterpret_cast<unsigned*>(tileq + tok0 * F::TILE_RS + (it * 16 + part0) * 4) = pk;
-                if (dm.dbg.h_code && nq0 < N) *reinterpret_cast<unsigned*>(dm.dbg.h_code + row0 * C + (it * 16 + part0) * 4) = pk;
+                if (TAPS && dm.dbg.h_code && nq0 < N) *reinterpret_cast<unsigned*>(dm.dbg.h_code + row0 * C + (it * 16 + part0) * 4) = pk;
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (tid < 16 * TOK && dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc0;
+        if (TAPS && tid < 16 * TOK && dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc0;
         // ---- weight scales into LDS
     #pragma unroll
         for (int k = 0; k < SCV; ++k) {
@@ -396,7 +401,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         if (tid < NH * D / 4) reinterpret_cast<float4*>(wsc)[tid] = swv;
         const bool tap = by == 0 && nq0 < N;
         if (part0 == 0) s_h[tok0] = sc0;
-        if (tap && dm.dbg.s_h && part0 == 0) dm.dbg.s_h[row0] = sc0;
+        if (TAPS && tap && dm.dbg.s_h && part0 == 0) dm.dbg.s_h[row0] = sc0;
         const int img16 = (int)((NH * dm.I.head_bytes) >> 4);  // the workgroup's head blocks are contiguous
         const int32x4_t* gimg = reinterpret_cast<const int32x4_t*>(packed + dm.L.image + (size_t)b * dm.L.image_bytes +
                                                                    (size_t)by * NH * dm.I.head_bytes);
@@ -425,7 +430,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             pk.x = quant4_i8(p0.x, p0.y, p1.x, p1.y, cq0, safe0);
             pk.y = quant4_i8(p2.x, p2.y, p3.x, p3.y, cq0, safe0);
             *reinterpret_cast<uint2*>(tileq + tok0 * F::TILE_RS + (it * TPT + part0) * 8) = pk;
-            if (tap && dm.dbg.h_code) *reinterpret_cast<uint2*>(dm.dbg.h_code + row0 * C + (it * TPT + part0) * 8) = pk;
+            if (TAPS && tap && dm.dbg.h_code) *reinterpret_cast<uint2*>(dm.dbg.h_code + row0 * C + (it * TPT + part0) * 8) = pk;
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -609,7 +614,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         const float cq = dm.qmaxq * __builtin_amdgcn_rcpf(qsafe);
 #pragma unroll
         for (int j = 0; j < TPH; ++j) qpk[nt][j] = quant4_i8(qf[j][0], qf[j][1], qf[j][2], qf[j][3], cq, qsafe, dm.qmaxq);
-        if (dm.dbg.q_code && nvalid[nt]) {
+        if (TAPS && dm.dbg.q_code && nvalid[nt]) {
 #pragma unroll
             for (int j = 0; j < TPH; ++j)
                 if (16 * j + 4 * q < D) *reinterpret_cast<unsigned*>(dm.dbg.q_code + tok[nt] * C + h * D + 16 * j + 4 * q) = qpk[nt][j];
@@ -949,7 +954,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             }
             if (nvalid[nt] && valid) {
                 const float4 o4 = make_float4(oacc[nt][k][0], oacc[nt][k][1], oacc[nt][k][2], oacc[nt][k][3]);
-                if (dm.dbg.O) *reinterpret_cast<float4*>(dm.dbg.O + tok[nt] * C + h * D + 16 * jt + 4 * q) = o4;
+                if (TAPS && dm.dbg.O) *reinterpret_cast<float4*>(dm.dbg.O + tok[nt] * C + h * D + 16 * jt + 4 * q) = o4;
                 if constexpr (NG > 1 || CORE) *reinterpret_cast<float4*>(dm.ws_of + tok[nt] * C + h * D + 16 * jt + 4 * q) = o4;
             }
         }
@@ -976,9 +981,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 const unsigned pk = quant4_i8(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3], cq, osafe);
                 const int c = h * D + 16 * jt + 4 * q;
                 *reinterpret_cast<unsigned*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + c) = pk;
-                if (dm.dbg.o_code && nvalid[nt]) *reinterpret_cast<unsigned*>(dm.dbg.o_code + tok[nt] * C + c) = pk;
+                if (TAPS && dm.dbg.o_code && nvalid[nt]) *reinterpret_cast<unsigned*>(dm.dbg.o_code + tok[nt] * C + c) = pk;
             }
-        if (dm.dbg.s_o && nvalid[nt] && q == 0 && h == 0) dm.dbg.s_o[tok[nt]] = so[nt];
+        if (TAPS && dm.dbg.s_o && nvalid[nt] && q == 0 && h == 0) dm.dbg.s_o[tok[nt]] = so[nt];
     }
     __syncthreads();
 
@@ -1044,21 +1049,41 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     }
 }
 
-template <int D, int NH, int NTT, int NG, int PG, int TOK, bool CORE, int NT16 = 0>
+// Compute units of the current device (asked once per device).
+static inline int device_cu_count() {
+    static std::atomic<int> cus[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int n = cus[dev].load(std::memory_order_acquire);
+    if (n <= 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev].store(n, std::memory_order_release);
+    }
+    return n;
+}
+
+template <int D, int NH, int NTT, int NG, int PG, int TOK, bool CORE, int NT16 = 0, bool DENSE = false>
 static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     if constexpr (NT16 == 0) {  // 65 to 80 text tokens: the instantiation without run-time guards around the score tiles
-        if (dm.nt16 == 5) return launch_fused_grid<D, NH, NTT, NG, PG, TOK, CORE, 5>(tab, dm, st);
+        const bool taps = dm.dbg.h_code || dm.dbg.s_h || dm.dbg.q_code || dm.dbg.s_Q || dm.dbg.O || dm.dbg.o_code || dm.dbg.s_o;
+        if (dm.nt16 == 5 && !taps) return launch_fused_grid<D, NH, NTT, NG, PG, TOK, CORE, 5>(tab, dm, st);
     }
-    using F = FusedCfg<D, NH, NTT, NG, TOK>;
+    using F = FusedCfg<D, NH, NTT, NG, TOK, DENSE>;
     static std::atomic<unsigned long long> lds_set{0};
     const size_t bytes = NG == 1 ? dm.I.bytes + TOK * F::TILE_RS + 3 * F::C * 4 + TOK * 4 + TOK * NH * 4  // = fused_lds_bytes
                                  : (size_t)NH * dm.I.head_bytes + TOK * F::TILE_RS + NH * D * 4 + TOK * 4 +
                                        (F::NT / 128) * (TOK / 16) * NH * F::TPH * 1024;  // = mid_lds_bytes at TOK = 32
     if (bytes > 160 * 1024 || dm.I.head_bytes > (size_t)F::IMGC * 1024) return hipErrorInvalidValue;
-    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE, NT16>), 160 * 1024, lds_set);
+    if constexpr (!DENSE && NT16 == 5 && D == 40 && NH == 8 && NTT == 2 && NG == 1 && !CORE) {
+        // More token tiles than compute units and a working set of at most half a compute unit's LDS: the instantiation
+        // of which two workgroups share a compute unit (one is in its arithmetic while the other waits for memory).
+        if ((dm.N + TOK - 1) / TOK * dm.R * dm.B > device_cu_count() && bytes <= 80 * 1024)
+            return launch_fused_grid<D, NH, NTT, NG, PG, TOK, CORE, NT16, true>(tab, dm, st);
+    }
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE, NT16, DENSE>), 160 * 1024, lds_set);
     if (e != hipSuccess) return e;
     const int tiles = (dm.N + TOK - 1) / TOK;
-    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE, NT16>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
+    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE, NT16, DENSE>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 

@@ -124,6 +124,9 @@ def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linea
     print(f"    out: max_abs={max_abs:.3e} rel_l2={rel_l2:.3e}", flush=True)
     assert np.all(np.isfinite(g.out.astype(np.float32)))
     assert max_abs <= OUT_MAX_ABS and rel_l2 <= OUT_REL_L2
+    # the same call without taps (for T in 65..80 a kernel instantiation of its own): bit-identical output
+    g0 = G.GpuRun(L, taps=False, w_layout=w_layout, bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid, tok_tile=tok_tile)
+    assert np.array_equal(g0.out.view(np.uint16), g.out.view(np.uint16)), "output differs between the call with taps and without"
     return g
 
 
