@@ -133,6 +133,26 @@ __device__ __forceinline__ unsigned quant4_i8(float x0, float x1, float x2, floa
     return pk;
 }
 
+// The same for values x_i * f whose products have not been formed yet (f > 0 common to the four): the fast path
+// rounds the exact product x * (f * c), f * c rounded once, which lies within 2.5 * 2^-23 * 127 = 3.8e-5 of the exact
+// ratio of y = fl(x * f) to amax (one more rounding in f * c, one in y itself); with the defined quotient's 1.5e-5 the
+// two agree unless the product is within 5.3e-5 of a half-integer. Flagged lanes form y and follow the definition.
+__device__ __forceinline__ unsigned quant4_i8_scaled(float x0, float x1, float x2, float x3, float f, float c, float amax) {
+    const float magic = 12582912.0f;
+    const float fc = f * c;
+    const float m0 = __builtin_fmaf(x0, fc, magic), m1 = __builtin_fmaf(x1, fc, magic);
+    const float m2 = __builtin_fmaf(x2, fc, magic), m3 = __builtin_fmaf(x3, fc, magic);
+    const float e0 = __builtin_fmaf(x0, fc, magic - m0), e1 = __builtin_fmaf(x1, fc, magic - m1);
+    const float e2 = __builtin_fmaf(x2, fc, magic - m2), e3 = __builtin_fmaf(x3, fc, magic - m3);
+    const unsigned lo = __builtin_amdgcn_perm(__float_as_uint(m1), __float_as_uint(m0), 0x0c0c0400u);
+    const unsigned hi = __builtin_amdgcn_perm(__float_as_uint(m3), __float_as_uint(m2), 0x0c0c0400u);
+    unsigned pk = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+    if (fmaxf(fmaxf(fabsf(e0), fabsf(e1)), fmaxf(fabsf(e2), fabsf(e3))) > 0.49994f)
+        pk = pack4(symq_code_f(x0 * f, 127.f, amax), symq_code_f(x1 * f, 127.f, amax), symq_code_f(x2 * f, 127.f, amax),
+                   symq_code_f(x3 * f, 127.f, amax));
+    return pk;
+}
+
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 // All-reduce over the four quarter-wave lanes that hold one image token (l, l^16, l^32, l^48) with the
@@ -296,20 +316,18 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             const int i = tid + k * NT;
             scv[k] = i < 3 * C / 4 ? reinterpret_cast<const float4*>(rq.scales)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        // ---- per-token int8 codes of the hidden tile
-        float x[KC][4];
+        // ---- per-token int8 codes of the hidden tile. The row maximum is taken on the fp16 values themselves, two per
+        // instruction (a maximum is exact in any precision); the quantizer's FMAs read the fp16 operands directly.
         float amax = 0.f;
         if (tid < 16 * TOK) {
+            half2_t am2 = {(_Float16)0.f, (_Float16)0.f};
     #pragma unroll
             for (int it = 0; it < KC; ++it) {
-                const __half2* hh = reinterpret_cast<const __half2*>(&xin[it]);
-                const float2 p0 = __half22float2(hh[0]), p1 = __half22float2(hh[1]);
-                x[it][0] = p0.x;
-                x[it][1] = p0.y;
-                x[it][2] = p1.x;
-                x[it][3] = p1.y;
-                amax = fmaxf(amax, fmaxf(fmaxf(fabsf(p0.x), fabsf(p0.y)), fmaxf(fabsf(p1.x), fabsf(p1.y))));
+                const unsigned a0 = xin[it].x & 0x7fff7fffu, a1 = xin[it].y & 0x7fff7fffu;
+                am2 = __builtin_elementwise_max(am2, __builtin_elementwise_max(*reinterpret_cast<const half2_t*>(&a0),
+                                                                                 *reinterpret_cast<const half2_t*>(&a1)));
             }
+            amax = fmaxf((float)am2[0], (float)am2[1]);
         }
         // The hidden tile has arrived (the unpacking above waited for it). Only now are the 10x larger weight reads
         // issued: the texture path serves requests in arrival order, and the first barrier waits for nothing else.
@@ -334,7 +352,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 for (int f = it * RPS; f < (it + 1) * RPS && f < RING; ++f) wring[f] = load_w(rq.wq, f % TPH, wstep * (f / TPH));
             }
             if (tid < 16 * TOK) {
-                const unsigned pk = quant4_i8(x[it][0], x[it][1], x[it][2], x[it][3], cq0, safe0);
+                const half2_t x01 = *reinterpret_cast<const half2_t*>(&xin[it].x), x23 = *reinterpret_cast<const half2_t*>(&xin[it].y);
+                const unsigned pk = quant4_i8((float)x01[0], (float)x01[1], (float)x23[0], (float)x23[1], cq0, safe0);
                 *reinterpret_cast<unsigned*>(tileq + tok0 * F::TILE_RS + (it * 16 + part0) * 4) = pk;
                 if (TAPS && dm.dbg.h_code && nq0 < N) *reinterpret_cast<unsigned*>(dm.dbg.h_code + row0 * C + (it * 16 + part0) * 4) = pk;
             }
@@ -939,9 +958,15 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         for (int f = 0; f < RING; ++f) wring[f] = load_w(rq.wo, f % TPH, wstep * (f / TPH));
     }
     // ================= per-token int8 codes of O over all heads
+    // O = oacc * of, of = 2^-kexp / pmax (times range / Z on the row-range grid). Where nobody needs O itself (no tap, no
+    // workspace copy) the products are not formed: the row maximum is max|oacc| * of (a product with a positive
+    // constant is monotone, so this IS the maximum of the products), and the quantizer takes oacc and of apart.
+    constexpr bool KEEP_O = NG > 1 || CORE || TAPS;
     const float osc = reinterpret_cast<const float*>(imgh + dm.I.oscale)[0] * (1.0f / dm.pmax);
+    float of[NTT];
 #pragma unroll
     for (int nt = 0; nt < NTT; ++nt) {
+        of[nt] = ROWMAX ? osc * fz[nt] : osc;
         float omx = 0.f;
 #pragma unroll
         for (int k = 0; k < TPS; ++k) {
@@ -949,15 +974,16 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             const bool valid = jt < TPH && ((16 * jt + 16 <= D) || 16 * jt + 4 * q < D);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                oacc[nt][k][i] = valid ? oacc[nt][k][i] * (ROWMAX ? osc * fz[nt] : osc) : 0.f;
-                omx = fmaxf(omx, fabsf(oacc[nt][k][i]));
+                if constexpr (KEEP_O) oacc[nt][k][i] = valid ? oacc[nt][k][i] * of[nt] : 0.f;
+                omx = fmaxf(omx, valid ? fabsf(oacc[nt][k][i]) : 0.f);
             }
-            if (nvalid[nt] && valid) {
+            if (KEEP_O && nvalid[nt] && valid) {
                 const float4 o4 = make_float4(oacc[nt][k][0], oacc[nt][k][1], oacc[nt][k][2], oacc[nt][k][3]);
                 if (TAPS && dm.dbg.O) *reinterpret_cast<float4*>(dm.dbg.O + tok[nt] * C + h * D + 16 * jt + 4 * q) = o4;
                 if constexpr (NG > 1 || CORE) *reinterpret_cast<float4*>(dm.ws_of + tok[nt] * C + h * D + 16 * jt + 4 * q) = o4;
             }
         }
+        if constexpr (!KEEP_O) omx *= of[nt];
         omx = quad_allmax(omx);
         if (NG == 1 && !CORE && q == 0) omax[(tbase + 16 * nt + r16) * NH + hl] = __float_as_uint(omx);
         // head-group variant: this wavefront's share of the token's row maximum, for the kernel that quantizes the row
@@ -978,7 +1004,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
         for (int jt = 0; jt < TPH; ++jt)
             if (16 * jt + 4 * q < D) {
-                const unsigned pk = quant4_i8(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3], cq, osafe);
+                const unsigned pk = KEEP_O ? quant4_i8(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3], cq, osafe)
+                                           : quant4_i8_scaled(oacc[nt][jt][0], oacc[nt][jt][1], oacc[nt][jt][2], oacc[nt][jt][3], of[nt], cq, osafe);
                 const int c = h * D + 16 * jt + 4 * q;
                 *reinterpret_cast<unsigned*>(tileq + (tbase + 16 * nt + r16) * F::TILE_RS + c) = pk;
                 if (TAPS && dm.dbg.o_code && nvalid[nt]) *reinterpret_cast<unsigned*>(dm.dbg.o_code + tok[nt] * C + c) = pk;
