@@ -215,6 +215,12 @@ int taq_unpack_kv(const void* qkv_packed, const taq_shape* shape, int8_t* k_code
                   float* k_scales, float* v_scales, void* k_trig_f16, void* v_trig_f16,
                   void* hip_stream);
 
+/* Where the plain code sections sit inside qkv_packed, for tools that read the codes themselves: byte offsets of
+ * the K and the V section, each u8 [B][T][row_bytes]; row_bytes = C with 8-bit rows, C/2 with 4-bit rows (two's
+ * complement nibbles, element 2j in the low nibble of byte j, as Eq. (2)'s codes are packed), 0 with bits_kv = 16
+ * (no code sections). Protected rows hold zeros. Host-only; no GPU work. */
+int taq_kv_code_layout(const taq_shape* shape, size_t* k_code_offset, size_t* v_code_offset, size_t* row_bytes);
+
 /* Static, human-readable name of a status code. */
 const char* taq_status_string(int status);
 

@@ -63,6 +63,17 @@ int taq_kv_packed_bytes(const taq_shape* shape, size_t* bytes) {
     return TAQ_OK;
 }
 
+int taq_kv_code_layout(const taq_shape* shape, size_t* k_code_offset, size_t* v_code_offset, size_t* row_bytes) {
+    if (!k_code_offset || !v_code_offset || !row_bytes) return TAQ_ERR_INVALID_ARG;
+    int rc = check_shape(shape, false);
+    if (rc != TAQ_OK) return rc;
+    const KvLayout L = kv_layout(*shape);
+    *k_code_offset = L.k_code;
+    *v_code_offset = L.v_code;
+    *row_bytes = (size_t)L.Cb;
+    return TAQ_OK;
+}
+
 int taq_workspace_bytes(const taq_shape* shape, size_t* bytes) {
     if (!bytes) return TAQ_ERR_INVALID_ARG;
     int rc = check_shape(shape, false);

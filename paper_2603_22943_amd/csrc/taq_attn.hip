@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
         if (t < T && j < d && bits != 16 && slot_of[t] < 0) {
             const float sv = a.s_v[((size_t)b * H + h) * T + t];
             const float D = ((float)load_code(a.v_code, (size_t)b * T + t, C, h * d + j, bits) * sv) * vpre;
-            hi = (float)(_Float16)D;
+            hi = (float)(_Float16)__builtin_amdgcn_cvt_pkrtz(D, 0.f)[0];  // (an intrinsic: one value for both uses, see below)
             lo = D - hi;
         }
         const int p = perm_token(t);
@@ -311,8 +311,11 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
                 half8_t phi, plo;  // protected columns keep A: 255*A as fp16 high + low parts
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
+                    // high part by the conversion intrinsic (round toward zero), so that the one value that goes into
+                    // the MFMA is also the one subtracted: a plain cast of the product may be merged with the multiply
+                    // into a single-rounding instruction in one use and not in the other
                     const float x = (Sf[ft][8 * blk + e] * inv) * a.pmax;
-                    const _Float16 xh = (_Float16)x;
+                    const _Float16 xh = (_Float16)__builtin_amdgcn_cvt_pkrtz(x, 0.f)[0];
                     phi[e] = xh;
                     plo[e] = (_Float16)(x - (float)xh);
                 }

@@ -803,7 +803,9 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             for (int i = 0; i < 4; ++i) {
                 const float ex = __builtin_amdgcn_exp2f(__builtin_fmaf(facc[nt][i], sq2[nt], offs[nt]));
                 Zs[nt] += ex;
-                const _Float16 xh = (_Float16)ex;
+                // (high part by the conversion intrinsic: the value that enters the MFMA is the one subtracted, whatever
+                // instruction the compiler would pick for a plain cast in either place)
+                const _Float16 xh = (_Float16)__builtin_amdgcn_cvt_pkrtz(ex, 0.f)[0];
                 phi[nt][i] = xh;
                 plo[nt][i] = (_Float16)(ex - (float)xh);
             }

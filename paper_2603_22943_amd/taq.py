@@ -37,7 +37,7 @@ TAQ_STAGE_O_QUANT = 16
 TAQ_STAGE_TO_OUT = 32
 
 EXPORTS = [
-    "taq_kv_packed_bytes", "taq_workspace_bytes", "taq_quantize_weight", "taq_weight_bytes", "taq_pack_weight",
+    "taq_kv_packed_bytes", "taq_kv_code_layout", "taq_workspace_bytes", "taq_quantize_weight", "taq_weight_bytes", "taq_pack_weight",
     "taq_quantize_kv",
     "taq_quantize_kv_w8",
     "taq_cross_attn", "taq_cross_attn_ex", "taq_cross_attn_static", "taq_cross_attn_batched", "taq_unpack_kv",
@@ -89,6 +89,7 @@ def load() -> ctypes.CDLL:
     lib.taq_status_string.argtypes = [ci]
     lib.taq_kv_packed_bytes.argtypes = [shp, sz]
     lib.taq_workspace_bytes.argtypes = [shp, sz]
+    lib.taq_kv_code_layout.argtypes = [shp, sz, sz, sz]
     lib.taq_quantize_weight.argtypes = [vp, ci, ci, vp, vp, vp]
     lib.taq_weight_bytes.argtypes = [shp, sz]
     lib.taq_pack_weight.argtypes = [vp, shp, vp, vp]
@@ -135,6 +136,14 @@ def taq_kv_packed_bytes(shape: taq_shape) -> int:
     n = ctypes.c_size_t(0)
     _check(load().taq_kv_packed_bytes(ctypes.byref(shape), ctypes.byref(n)), "taq_kv_packed_bytes")
     return n.value
+
+
+def taq_kv_code_layout(shape: taq_shape):
+    """(byte offset of the K code section, of the V code section, bytes per (batch, token) row) inside qkv_packed."""
+    k, v, rb = ctypes.c_size_t(0), ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(load().taq_kv_code_layout(ctypes.byref(shape), ctypes.byref(k), ctypes.byref(v), ctypes.byref(rb)),
+           "taq_kv_code_layout")
+    return k.value, v.value, rb.value
 
 
 def taq_workspace_bytes(shape: taq_shape) -> int:

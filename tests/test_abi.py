@@ -54,6 +54,11 @@ def test_size_queries_are_host_only_and_consistent():
     a16 = T.taq_kv_packed_bytes(T.make_shape(B=2, N=64, C=96, H=4, T=77, Cc=64, bits_kv=16))
     assert a8 - a16 == pytest.approx(2 * 2 * 77 * 96, abs=1024)
     assert kv8 % 256 == 0 and ws % 256 == 0
+    # the plain code sections: C bytes per row at 8 bits, C/2 at 4 bits, none at 16; V behind K, both inside the buffer
+    k8, v8, rb8 = T.taq_kv_code_layout(s)
+    k4, v4, rb4 = T.taq_kv_code_layout(s4)
+    assert (rb8, rb4) == (320, 160) and v8 - k8 >= 2 * 77 * rb8 and v4 - k4 >= 2 * 77 * rb4 and v8 + 2 * 77 * rb8 <= kv8
+    assert T.taq_kv_code_layout(T.make_shape(B=2, N=64, C=96, H=4, T=77, Cc=64, bits_kv=16))[2] == 0
     # workspace holds at least the int8 Q~ codes, their float32 source and the float32 O
     assert ws >= 2 * 4096 * 320 * (1 + 4 + 1 + 4 + 1)
 

@@ -68,6 +68,45 @@ def test_config5_multi_checkpoint_batch():
         assert max_abs <= 2e-2 and rel_l2 <= 5e-3
 
 
+def test_unet_step_of_16_layers_from_one_graph_matches_the_oracle():
+    """The 16 cross-attention layers of one UNet step (configs[2]) captured into ONE HIP graph, as bench.py replays
+    them: after each of several replays (eager work of the library in between) every layer's output must be bit-identical
+    to its eager output, and that output must meet the oracle's within the block tolerance."""
+    layers = synth.config3()
+    runs = [G.GpuRun(L, taps=False, w_layout=1) for L in layers]
+    wss = [torch.empty(T.taq_workspace_bytes(r.shape), dtype=torch.uint8, device=G.DEV) for r in runs]
+    outs = [torch.zeros_like(r.out_d) for r in runs]
+
+    def enqueue():
+        for r, o, ws in zip(runs, outs, wss):
+            T.taq_cross_attn(r.hidden_d, r.packed, r.wq_code, r.wo_code, r.scales, r.mask_d, r.shape, o, ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        enqueue()
+    for rep in range(3):
+        for o in outs:
+            o.zero_()
+        r0 = runs[rep]
+        T.taq_cross_attn(r0.hidden_d, r0.packed, r0.wq_code, r0.wo_code, r0.scales, r0.mask_d, r0.shape)  # eager, in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (r, o) in enumerate(zip(runs, outs)):
+            assert np.array_equal(o.cpu().numpy().view(np.uint16), r.out.view(np.uint16)), (rep, i)
+    for i, (L, r) in enumerate(zip(layers, runs)):
+        ref, _ = G.oracle_run(L)
+        max_abs, rel_l2 = G.out_errors(r.out, ref)
+        print(f"[case] graph layer {i} {L.name}: max_abs={max_abs:.3e} rel_l2={rel_l2:.3e}", flush=True)
+        assert max_abs <= 2e-2 and rel_l2 <= 5e-3
+
+
 def test_hip_graph_replays_match_eager():
     """bench.py replays the steps from a HIP graph. Replay several times with eager work and
     synchronisations in between; every replay must reproduce the eager result bit for bit."""

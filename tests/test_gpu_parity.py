@@ -27,6 +27,12 @@ OUT_MAX_ABS = 2e-2
 OUT_REL_L2 = 5e-3
 
 
+def O_cross_attn(L, kv, aux, **kw):
+    """The oracle's block on a given K~/V~ (weight codes taken from a previous oracle run)."""
+    from oracle import taq_oracle as O
+    return O.cross_attn(L.hidden, kv, aux["wq_code"], aux["s_wq"], aux["wo_code"], aux["s_wo"], L.bias_o, return_aux=True, **kw)
+
+
 def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linear", tok_tile=0):
     print(f"[case] {label or L.name}: B={L.B} N={L.N} C={L.C} H={L.H} T={L.T} Cc={L.Cc} bits_kv={L.bits_kv} "
           f"bits_q={bits_q} bits_prob={bits_prob} grid={prob_grid} ntrig={L.mask.sum(axis=1).tolist()} w_layout={w_layout}", flush=True)
@@ -60,6 +66,18 @@ def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linea
         assert np.all(g.kv[name][~kv.mask] == 0)
         if kv.mask.any():
             assert np.mean(gap[kv.mask] == 0) > 0.98
+    # ---- from here on the oracle runs on the DEVICE's protected rows: where one of them differs from the oracle's own
+    # row by its allowed fp16 step, everything downstream of it (scores of a head, a channel of A^ V~) would differ by
+    # that step's effect, which is not an error of the attention path. With the rows shared, the bounds below stay
+    # at float32-versus-float64 level whatever the rows are.
+    rows_equal = np.array_equal(g.kv["K16"].astype(np.float64), kv.K16) and np.array_equal(g.kv["V16"].astype(np.float64), kv.V16)
+    if not rows_equal:
+        import dataclasses
+        kv_dev = dataclasses.replace(kv, K16=np.where(kv.mask[:, :, None], g.kv["K16"].astype(np.float64), 0.0),
+                                     V16=np.where(kv.mask[:, :, None], g.kv["V16"].astype(np.float64), 0.0))
+        ref_out, aux2 = O_cross_attn(L, kv_dev, aux, bits_q=bits_q, bits_prob=bits_prob, prob_grid=prob_grid)
+        aux = dict(aux, **aux2)
+        kv = kv_dev
     # ---- query side (Eq. 2 third line)
     assert np.array_equal(g.taps["h_code"].astype(np.int32), aux["h_code"])
     assert np.array_equal(g.taps["s_h"], aux["s_h"])
@@ -72,10 +90,8 @@ def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linea
     bad = ~np.isfinite(g.taps["O"])
     assert not bad.any(), ("non-finite A^ V~", int(bad.sum()), [np.unique(a)[:12].tolist() for a in np.where(bad)])
     dO = np.abs(g.taps["O"].astype(np.float64) - O_ref)
-    # float32 vs float64 arithmetic keeps O within ~1e-6 of its scale; a protected K/V row that differs from the
-    # oracle's by its allowed single fp16 step (5e-4 relative) shifts the scores of a head or a whole channel
-    rows_equal = np.array_equal(g.kv["K16"].astype(np.float64), kv.K16) and np.array_equal(g.kv["V16"].astype(np.float64), kv.V16)
-    far = 2e-5 if rows_equal else 1e-3
+    # float32 vs float64 arithmetic keeps O within ~1e-6 of its scale
+    far = 2e-5
     frac_far = float(np.mean(dO > far * scale_o))
     dcode = np.abs(g.taps["o_code"].astype(np.int32) - aux["o_code"])
     print(f"    O: max|d|/max|O|={dO.max() / scale_o:.3e} frac(>{far:g})={frac_far:.3e}  "
@@ -89,19 +105,19 @@ def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linea
     if prob_grid == "log2":
         last = (1 << bits_prob) - 1
         x = -np.log2(aux["A"])                                       # [B,N,H,T]
-        tol = 1e-5 * (1 + x) + (0.0 if rows_equal else 0.02)
+        tol = 1e-5 * (1 + x)
         near = (np.abs(x - np.floor(x) - 0.5) <= tol) & (np.floor(x) < last) & unprot
         step = np.where(near, np.exp2(-(np.floor(x) + 1)), 0.0)      # 2^-k - 2^-(k+1)
     elif prob_grid == "rowmax":
         s_P = aux["s_P"].astype(np.float64)[..., None]               # the row's own step, amax / pmax
         with np.errstate(divide="ignore", invalid="ignore"):         # a range that underflowed to 0: codes weigh nothing
             x = np.where(s_P > 0, aux["A"] / s_P, 0.0)
-        tie_rel = 1e-5 if rows_equal else 2e-3
+        tie_rel = 1e-5
         near = (np.abs(x - np.floor(x) - 0.5) <= tie_rel * x + 1e-6) & unprot
         step = near * s_P
     else:
         x = aux["A"] * pmax
-        tie_rel = 1e-5 if rows_equal else 2e-3
+        tie_rel = 1e-5
         near = (np.abs(x - np.floor(x) - 0.5) <= tie_rel * x + 1e-6) & unprot
         step = near / pmax
     vabs = np.abs(kv.v_code.astype(np.float64)).reshape(L.B, L.T, L.H, d) * \
@@ -109,7 +125,7 @@ def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linea
     slack = np.einsum("bnht,bthj->bnhj", step, vabs).reshape(L.B, L.N, L.C)
     print(f"    near-tie probabilities: {int(near.sum())} of {near.size}", flush=True)
     coarse = bits_prob == 4 or prob_grid == "log2"  # one grid step is a visible fraction of the output
-    assert np.all(dO <= slack + (far if coarse else 0.02) * scale_o), float((dO - slack).max() / scale_o)
+    assert np.all(dO <= slack + far * scale_o), float((dO - slack).max() / scale_o)
     assert frac_far < 5e-3
     # an int8 code of O may move by one where O is within rounding of a tie, plus however many
     # steps a flipped probability code moved O itself (with 4-bit V rows or a 4-bit probability
@@ -367,6 +383,29 @@ def test_log2_probability_grid_sharp_attention():
     L2 = synth.make_layer("plogs2", seed=78, B=1, N=90, C=96, H=4, Cc=64, T=40, bits_kv=8, trigger_positions=(4,))
     L2.Wk = (L2.Wk.astype(np.float32) * 6.0).astype(np.float16)
     check_layer(L2, "log2 grid sharp, kernel per stage", bits_prob=8, prob_grid="log2")
+
+
+@pytest.mark.parametrize("C,H,bits", [(320, 8, 4), (1280, 20, 4), (96, 4, 4), (320, 8, 8)])
+def test_raw_code_bytes_of_qkv_packed_match_the_oracle_packing(C, H, bits):
+    """The plain code sections of qkv_packed, read as bytes at the offsets the library reports: 4-bit rows must be the
+    oracle's nibble packing (element 2j in the low nibble of byte j) of the oracle's codes, 8-bit rows the codes
+    themselves; protected rows zeros."""
+    from oracle import taq_oracle as O
+    L = synth.make_layer("raw", seed=C + H + bits, B=2, N=8, C=C, H=H, Cc=96, T=77, bits_kv=bits,
+                         trigger_positions=(3, 40), trigger_scale=3.0)
+    s = G.shape_of(L)
+    packed = torch.full((T.taq_kv_packed_bytes(s),), 0xFF, dtype=torch.uint8, device=G.DEV)
+    T.taq_quantize_kv(G.dev(L.context), G.dev(L.mask), G.dev(L.Wk), G.dev(L.Wv), bits, s, packed)
+    torch.cuda.synchronize()
+    raw = packed.cpu().numpy()
+    k_off, v_off, rb = T.taq_kv_code_layout(s)
+    assert rb == (C if bits == 8 else C // 2)
+    kv = O.quantize_kv(L.context, L.mask, L.Wk, L.Wv, bits, H)
+    for off, code in ((k_off, kv.k_code), (v_off, kv.v_code)):
+        got = raw[off:off + L.B * L.T * rb].reshape(L.B, L.T, rb)
+        want = O.pack_int4(code) if bits == 4 else code.astype(np.int8).view(np.uint8)
+        assert np.array_equal(got, want)
+        assert np.all(got[kv.mask] == 0)
 
 
 def test_quantize_kv_with_cached_weight_codes_is_bit_identical():
