@@ -91,6 +91,8 @@ typedef struct taq_debug {
     float*  O;       /* f32 [B,N,C]  A^ V~ before its quantization                           */
     int8_t* o_code;  /* i8  [B,N,C]                                                          */
     float*  s_o;     /* f32 [B,N]                                                            */
+    uint8_t* p_code; /* u8  [B,N,H,T] codes of Q_a(A) in Eq. (3) (on the log2 grid: the exponent code);
+                        entries of protected columns are unspecified                         */
     unsigned stage_mask; /* 0 = whole block; else OR of TAQ_STAGE_* to run only those stages
                             (they then read what earlier calls left in `workspace`)          */
 } taq_debug;

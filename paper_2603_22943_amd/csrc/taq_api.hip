@@ -250,7 +250,7 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
                            static_cast<__half*>(out)};
             TAQ_TRY_HIP(launch_fused_block(&rq, 1, s, nullptr, st, q_code, s_q, o_f));
         } else {
-            TAQ_TRY_HIP(launch_attn_core(q_code, s_q, static_cast<const uint8_t*>(qkv_packed), s, o_f, st));
+            TAQ_TRY_HIP(launch_attn_core(q_code, s_q, static_cast<const uint8_t*>(qkv_packed), s, o_f, st, dbg ? dbg->p_code : nullptr));
         }
     }
     if (stages & TAQ_STAGE_O_QUANT)

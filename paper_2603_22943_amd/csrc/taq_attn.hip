@@ -66,6 +66,7 @@ struct CoreArgs {
     const __half* k16;      // [B][T][C] by slot
     const __half* v16;
     float* o_f;             // [B][N][C]
+    uint8_t* p_code;        // [B][N][H][T] tap of the probability codes, or NULL
     int N, C, H, T, bits;
     float sig2;             // softmax scale * log2(e)
     float pmax;             // linear grid: 255 or 15 (Eq. 3); log2 grid: 2^15, the factor that puts 2^-code into fp16's range
@@ -343,13 +344,20 @@ __global__ __launch_bounds__(256) void attn_core_kernel(CoreArgs a) {
                 half8_t p;  // Eq. (3): integer probability codes, exact in fp16
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
+                    float code;
                     if (a.plog) {
                         // -code = clip(rint(log2 A)) = clip(rint(arg - log2 Z)); weight 2^(15 - code), a power of
                         // two that fp16 holds exactly down to 2^-24 (smaller ones vanish: below 2^-39 of the row sum)
                         const float c = fminf(fmaxf(__builtin_rintf(S[tile][8 * blk + e] - lz), -a.plast), 0.f);
                         p[e] = (_Float16)ldexpf(1.0f, 15 + (int)c);
+                        code = -c;
                     } else {
-                        p[e] = (_Float16)__builtin_rintf((S[tile][8 * blk + e] * invc) * a.pmax);
+                        code = __builtin_rintf((S[tile][8 * blk + e] * invc) * a.pmax);
+                        p[e] = (_Float16)code;
+                    }
+                    if (a.p_code && nvalid) {  // tap: register e of this block holds text token t (accumulator order)
+                        const int t = 32 * tile + 16 * blk + 8 * (e >> 2) + 4 * half + (e & 3);
+                        if (t < T) a.p_code[(tok * H + h) * (size_t)T + t] = (uint8_t)(int)code;
                     }
                 }
 #pragma unroll
@@ -393,10 +401,11 @@ static hipError_t launch_core_dt(const CoreArgs& a, int B, hipStream_t st) {
 }
 
 hipError_t launch_attn_core(const int8_t* q_code, const float* s_q, const uint8_t* packed, const taq_shape& s,
-                            float* o_f, hipStream_t st) {
+                            float* o_f, hipStream_t st, uint8_t* p_code) {
     const KvLayout L = kv_layout(s);
     CoreArgs a;
     a.q_code = q_code;
+    a.p_code = p_code;
     a.s_q = s_q;
     a.ntrig = reinterpret_cast<const int*>(packed + L.ntrig);
     a.slot_of = reinterpret_cast<const int*>(packed + L.slot_of);

@@ -252,7 +252,7 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.pmax = logp ? 256.f : dm.plast;
     dm.L = kv_layout(s);
     dm.I = kv_image(s);
-    taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
+    taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
     dm.dbg = (dbg && R == 1) ? *dbg : none;
     dm.ws_of = core_of;
     dm.ws_omax = nullptr;
@@ -304,7 +304,7 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, float* o_f, 
     dm.pmax = logp ? 256.f : dm.plast;
     dm.L = kv_layout(s);
     dm.I = kv_image(s);
-    taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
+    taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
     dm.dbg = dbg ? *dbg : none;
     dm.dbg.o_code = nullptr;  // taps of the stages this kernel does not run are written by the kernel that runs them
     dm.dbg.s_o = nullptr;
@@ -338,7 +338,7 @@ hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const floa
     dm.T = s.T;
     dm.w_layout = s.w_layout;
     dm.w_pack_off = (unsigned)weight_pack_offset(s);
-    taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
+    taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
     dm.dbg = dbg ? *dbg : none;
     dm.ws_of = const_cast<float*>(o_f);
     dm.ws_omax = const_cast<float*>(o_max);

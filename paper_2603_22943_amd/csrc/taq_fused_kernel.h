@@ -867,6 +867,14 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         const uint8_t* vt = imgh + dm.I.vt;
         const _Float16* img_sv = reinterpret_cast<const _Float16*>(imgh + dm.I.s_vp);  // [ntok] high parts | [ntok] low parts
         const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
+        // tap: the codes of text tokens t, t + 1 for this lane's image token of tile nt (one wavefront per (head, token group))
+        auto tap_pcode = [&](int nt, int t, unsigned c0, unsigned c1) {
+            if (sub == 0 && nvalid[nt]) {
+                uint8_t* row = dm.dbg.p_code + (tok[nt] * H + h) * (size_t)T;
+                if (t < T) row[t] = (uint8_t)c0;
+                if (t + 1 < T) row[t + 1] = (uint8_t)c1;
+            }
+        };
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             if (2 * s < nt16) {
@@ -891,11 +899,13 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                                     const float c1 = __builtin_amdgcn_fmed3f(__builtin_rintf(S[nt][2 * s + a][2 * i2 + 1] - lz[nt]), -dm.plast, 0.f);
                                     const auto pw = __builtin_amdgcn_cvt_pkrtz(ldexpf(256.0f, (int)c0), ldexpf(256.0f, (int)c1));
                                     c = (half2_t){(_Float16)pw[0], (_Float16)pw[1]};
+                                    if (TAPS && dm.dbg.p_code) tap_pcode(nt, 16 * (2 * s + a) + 4 * q + 2 * i2, (unsigned)(int)(-c0), (unsigned)(int)(-c1));
                                 } else {
                                     const float m0 = __builtin_fmaf(S[nt][2 * s + a][2 * i2], kq[nt], 12608512.0f);
                                     const float m1 = __builtin_fmaf(S[nt][2 * s + a][2 * i2 + 1], kq[nt], 12608512.0f);
                                     const unsigned u = __builtin_amdgcn_perm(__float_as_uint(m1), __float_as_uint(m0), 0x05040100u);
                                     c = *reinterpret_cast<const half2_t*>(&u) - k1024;
+                                    if (TAPS && dm.dbg.p_code) tap_pcode(nt, 16 * (2 * s + a) + 4 * q + 2 * i2, u & 0xFFu, (u >> 16) & 0xFFu);
                                 }
                                 const half2_t wh = c * sh[i2];
                                 const half2_t wl = __builtin_elementwise_fma(c, sl[i2], __builtin_elementwise_fma(c, sh[i2], -wh));
@@ -1094,7 +1104,7 @@ static inline int device_cu_count() {
 template <int D, int NH, int NTT, int NG, int PG, int TOK, bool CORE, int NT16 = 0, bool DENSE = false>
 static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
     if constexpr (NT16 == 0) {  // 65 to 80 text tokens: the instantiation without run-time guards around the score tiles
-        const bool taps = dm.dbg.h_code || dm.dbg.s_h || dm.dbg.q_code || dm.dbg.s_Q || dm.dbg.O || dm.dbg.o_code || dm.dbg.s_o;
+        const bool taps = dm.dbg.h_code || dm.dbg.s_h || dm.dbg.q_code || dm.dbg.s_Q || dm.dbg.O || dm.dbg.o_code || dm.dbg.s_o || dm.dbg.p_code;
         if (dm.nt16 == 5 && !taps) return launch_fused_grid<D, NH, NTT, NG, PG, TOK, CORE, 5>(tab, dm, st);
     }
     using F = FusedCfg<D, NH, NTT, NG, TOK, DENSE>;

@@ -295,6 +295,6 @@ hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const floa
 
 // Attention core: scores, softmax, Eq. (3), A^ V~ for all (batch, head, token).
 hipError_t launch_attn_core(const int8_t* q_code, const float* s_q, const uint8_t* packed,
-                            const taq_shape& s, float* o_f, hipStream_t st);
+                            const taq_shape& s, float* o_f, hipStream_t st, uint8_t* p_code = nullptr);
 
 }  // namespace taq

@@ -62,7 +62,7 @@ class taq_shape(ctypes.Structure):
 class taq_debug(ctypes.Structure):
     _fields_ = [("h_code", ctypes.c_void_p), ("s_h", ctypes.c_void_p), ("q_code", ctypes.c_void_p),
                 ("s_Q", ctypes.c_void_p), ("O", ctypes.c_void_p), ("o_code", ctypes.c_void_p),
-                ("s_o", ctypes.c_void_p), ("stage_mask", ctypes.c_uint)]
+                ("s_o", ctypes.c_void_p), ("p_code", ctypes.c_void_p), ("stage_mask", ctypes.c_uint)]
 
 
 class taq_request(ctypes.Structure):
@@ -290,7 +290,8 @@ def make_debug(shape: taq_shape, device, stage_mask: int = 0, taps: bool = True)
             O=torch.empty((shape.B, shape.N, shape.C), dtype=torch.float32, device=device),
             o_code=torch.empty((shape.B, shape.N, shape.C), dtype=torch.int8, device=device),
             s_o=torch.empty((shape.B, shape.N), dtype=torch.float32, device=device),
+            p_code=torch.zeros((shape.B, shape.N, shape.H, shape.T), dtype=torch.uint8, device=device),
         )
     dbg = taq_debug(_ptr(t.get("h_code")), _ptr(t.get("s_h")), _ptr(t.get("q_code")), _ptr(t.get("s_Q")),
-                    _ptr(t.get("O")), _ptr(t.get("o_code")), _ptr(t.get("s_o")), stage_mask)
+                    _ptr(t.get("O")), _ptr(t.get("o_code")), _ptr(t.get("s_o")), _ptr(t.get("p_code")), stage_mask)
     return dbg, t

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_header_layout():
     assert ctypes.sizeof(T.taq_shape) == 14 * 4
     assert ctypes.sizeof(T.taq_request) == 7 * 8
-    assert ctypes.sizeof(T.taq_debug) == 7 * 8 + 8
+    assert ctypes.sizeof(T.taq_debug) == 8 * 8 + 8
 
 
 def test_status_strings():

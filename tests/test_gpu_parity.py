@@ -124,6 +124,15 @@ def check_layer(L, label="", w_layout=0, bits_q=8, bits_prob=8, prob_grid="linea
         np.transpose(kv.s_V.astype(np.float64), (0, 2, 1))[..., None]             # |V~| [B,T,H,d]
     slack = np.einsum("bnht,bthj->bnhj", step, vabs).reshape(L.B, L.N, L.C)
     print(f"    near-tie probabilities: {int(near.sum())} of {near.size}", flush=True)
+    # ---- the codes of Q_a(A) themselves (Eq. 3): identical to the oracle's off the near-tie set, one step apart on it
+    unp = np.broadcast_to(unprot, near.shape)
+    if prob_grid == "rowmax":
+        # a row whose unprotected columns together weigh under 2^-40 of it gets no codes from the kernels (their range
+        # is below float64 resolution of the output); the oracle still codes them: not compared
+        unp = unp & (aux["s_P"].astype(np.float64) * pmax > 2.0 ** -39)[..., None]
+    dp = np.abs(g.taps["p_code"].astype(np.int32) - aux["p_code"].astype(np.int32))
+    assert np.all(dp[unp & ~near] == 0), (int((dp[unp & ~near] != 0).sum()), int(dp[unp & ~near].max()))
+    assert np.all(dp[unp & near] <= 1)
     coarse = bits_prob == 4 or prob_grid == "log2"  # one grid step is a visible fraction of the output
     assert np.all(dO <= slack + far * scale_o), float((dO - slack).max() / scale_o)
     assert frac_far < 5e-3
