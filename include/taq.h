@@ -57,9 +57,13 @@ typedef enum taq_status {
 typedef struct taq_shape {
     int B, N, C, H, T, Cc;   /* d = C / H                                                   */
     int bits_kv;             /* 4 | 8 : width of unprotected K/V rows; 16 : keep every row fp16 */
-    int bits_prob;           /* 8 | 4 : probabilities on the 1/255 or 1/15 grid outside trigger columns */
-    int bits_q;              /* 8 | 4 : Q~ = Q_a(Q), qmax = 127 or 7 (codes stay one per byte)  */
-    int bits_proj;           /* 8 : W8A8 projections                                         */
+    int bits_prob;           /* 8 | 4 : probabilities on the 1/255 or 1/15 grid outside trigger columns;
+                                16 : A^ = A (Eq. 3 switched off)                                */
+    int bits_q;              /* 8 | 4 : Q~ = Q_a(Q), qmax = 127 or 7 (codes stay one per byte); 16 : Q~ = Q  */
+    int bits_proj;           /* 8 : W8A8 projections; 16 : unquantized projections, Wk / Wv / Wq / Wo are then the
+                                fp16 matrices themselves in every call (see taq_cross_attn).
+                                Any 16 among bits_prob / bits_q / bits_proj selects plain float32 kernels, one per
+                                stage: reference runs (Eq. 1's "everything else in full precision"), not speed.  */
     float softmax_scale;     /* 0 => 1/sqrt(d)                                               */
     int w_layout;            /* layout of the Wq / Wo buffers given to taq_cross_attn:
                                 0 : i8 [C, C] row-major codes only
@@ -170,8 +174,10 @@ int taq_quantize_kv_w8(const void* context, const uint8_t* trigger_mask, const i
  *   hidden       : f16 [B, N, C]
  *   qkv_packed   : as written by taq_quantize_kv for the same B, T, C, H, bits_kv
  *   Wq, Wo       : i8  [C, C] row-major (out x in) weight codes (taq_quantize_weight), or, with
- *                  shape->w_layout = 1, the buffers written by taq_pack_weight
- *   scales       : f32 [3*C] = s_wq[C] | s_wo[C] | bias_o[C] (bias of to_out; zeros if none)
+ *                  shape->w_layout = 1, the buffers written by taq_pack_weight; with shape->bits_proj = 16
+ *                  the unquantized f16 [C, C] matrices (passed through the same pointers)
+ *   scales       : f32 [3*C] = s_wq[C] | s_wo[C] | bias_o[C] (bias of to_out; zeros if none); with
+ *                  bits_proj = 16 only the bias part is read
  *   trigger_mask : u8 [B, T] or NULL. The protected-token list recorded in qkv_packed is
  *                  what the kernels use; this argument is accepted for symmetry only.
  *   out          : f16 [B, N, C]
@@ -208,6 +214,10 @@ int taq_cross_attn_static(const void* hidden, const void* qkv_packed, const int8
  * taq_workspace_bytes(). */
 int taq_cross_attn_batched(int R, const taq_request* table, const taq_shape* shape,
                            void* workspace, void* hip_stream);
+
+/* Mean squared difference of two fp16 arrays of n elements, as a float64 in device memory: the loss L of the
+ * token-sensitivity experiment (Section III-B, Eq. 1) on block outputs. x, y, out device memory; out 8-byte aligned. */
+int taq_mse_f16(const void* x_f16, const void* y_f16, size_t n, double* out, void* hip_stream);
 
 /* Expand qkv_packed into plain arrays (for tests). Any output may be NULL.
  *   k_codes, v_codes : i8  [B, T, C]  (int4 codes sign-extended; zeros on protected rows)

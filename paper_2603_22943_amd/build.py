@@ -21,7 +21,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtaq.so")
 SOURCES = ["taq_fused_d40.hip", "taq_fused_d80.hip", "taq_fused_d64.hip", "taq_fused_mid160.hip", "taq_fused_mid64.hip",
-           "taq_fused.hip", "taq_api.hip", "taq_quant.hip", "taq_gemm.hip", "taq_attn.hip"]
+           "taq_fused.hip", "taq_api.hip", "taq_quant.hip", "taq_gemm.hip", "taq_attn.hip", "taq_fp.hip"]
 
 
 def hipcc_path() -> str:

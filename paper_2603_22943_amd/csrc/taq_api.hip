@@ -14,7 +14,8 @@ int check_shape(const taq_shape* s, bool need_n) {
     if (s->B <= 0 || s->C <= 0 || s->H <= 0 || s->T <= 0 || s->Cc <= 0) return TAQ_ERR_INVALID_ARG;
     if (need_n && s->N <= 0) return TAQ_ERR_INVALID_ARG;
     if (s->bits_kv != 4 && s->bits_kv != 8 && s->bits_kv != 16) return TAQ_ERR_UNSUPPORTED_BITS;
-    if ((s->bits_prob != 8 && s->bits_prob != 4) || (s->bits_q != 8 && s->bits_q != 4) || s->bits_proj != 8)
+    if ((s->bits_prob != 8 && s->bits_prob != 4 && s->bits_prob != 16) || (s->bits_q != 8 && s->bits_q != 4 && s->bits_q != 16) ||
+        (s->bits_proj != 8 && s->bits_proj != 16))
         return TAQ_ERR_UNSUPPORTED_BITS;
     if (s->C % s->H != 0) return TAQ_ERR_BAD_SHAPE;
     const int d = s->C / s->H;
@@ -131,6 +132,23 @@ static int quantize_kv_impl(const void* context, const uint8_t* trigger_mask, co
     const int8_t* w_code = w_code_in;
     const float* s_w = s_w_in;
 
+    if (s.bits_proj == 16) {
+        // unquantized projections: float32 rows of K and V for every token from the fp16 matrices, Eq. (2) codes of the
+        // unprotected rows from those, protected rows by one rounding to fp16
+        if (!Wk || !Wv) return TAQ_ERR_INVALID_ARG;
+        TAQ_TRY_HIP(launch_kv_prep(nullptr, M, x_code, s_x, nullptr, nullptr, s.C, reinterpret_cast<int8_t*>(ws + W.w_code),
+                                   reinterpret_cast<float*>(ws + W.s_w), s.Cc, trigger_mask, s.B, s.T, s.bits_kv, ntrig,
+                                   trig_idx, slot_of, st));
+        TAQ_TRY_HIP(launch_gemm_fp(context, false, static_cast<const __half*>(Wk), nullptr, M, s.C, s.Cc, rows_f, nullptr, 2 * s.C, st));
+        TAQ_TRY_HIP(launch_gemm_fp(context, false, static_cast<const __half*>(Wv), nullptr, M, s.C, s.Cc, rows_f + s.C, nullptr, 2 * s.C, st));
+        TAQ_TRY_HIP(launch_kv_pack(rows_f, slot_of, s.B, s.T, s.C, s.H, s.bits_kv, pk + L.k_code, pk + L.v_code,
+                                   reinterpret_cast<float*>(pk + L.s_k), reinterpret_cast<float*>(pk + L.s_v), st));
+        TAQ_TRY_HIP(launch_kv_image(pk, s, st));
+        TAQ_TRY_HIP(launch_kv_rows_from_f32(rows_f, ntrig, trig_idx, s.B, s.T, s.C, reinterpret_cast<__half*>(pk + L.k16),
+                                            reinterpret_cast<__half*>(pk + L.v16), reinterpret_cast<__half*>(pk + L.v16t), st));
+        return TAQ_OK;
+    }
+
     // one launch: protected-token list, per-token int8 codes of the context (needed for unprotected tokens only) and,
     // unless the caller brings them, the 8-bit weight codes (Wk rows then Wv rows)
     int8_t* wc = reinterpret_cast<int8_t*>(ws + W.w_code);
@@ -177,7 +195,7 @@ int taq_quantize_kv_w8(const void* context, const uint8_t* trigger_mask, const i
     int rc = check_shape(shape, false);
     if (rc != TAQ_OK) return rc;
     if (!context || !trigger_mask || !Wkv_code || !s_wkv || !qkv_packed || !workspace) return TAQ_ERR_INVALID_ARG;
-    if (bits != shape->bits_kv) return TAQ_ERR_INVALID_ARG;
+    if (bits != shape->bits_kv || shape->bits_proj != 8) return TAQ_ERR_INVALID_ARG;  // weight codes: the W8A8 projections only
     if (misaligned(context) || misaligned(Wkv_code) || misaligned(s_wkv) || misaligned(qkv_packed) || misaligned(workspace))
         return TAQ_ERR_MISALIGNED;
     return quantize_kv_impl(context, trigger_mask, nullptr, nullptr, Wkv_code, s_wkv, *shape, qkv_packed, workspace,
@@ -211,6 +229,39 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
     const float* bias_o = scales + 2 * s.C;
     const int M = s.B * s.N;
     const unsigned stages = (dbg && dbg->stage_mask) ? dbg->stage_mask : ~0u;
+
+    if (fp_mode(s)) {
+        // Full-precision modes, one float32 kernel per stage. With bits_proj = 16 Wq / Wo are the fp16 matrices themselves
+        // and only the bias part of `scales` is read.
+        if (dbg && dbg->stage_mask) return TAQ_ERR_INVALID_ARG;
+        const bool w16 = s.bits_proj == 16;
+        if (w16) {
+            TAQ_TRY_HIP(launch_gemm_fp(hidden, false, reinterpret_cast<const __half*>(Wq), nullptr, M, s.C, s.C, q_f, nullptr, s.C, st));
+        } else {
+            TAQ_TRY_HIP(launch_rowquant_f16(static_cast<const __half*>(hidden), M, s.C, h_code, s_h, st));
+            TAQ_TRY_HIP(launch_gemm_i8(h_code, s_h, Wq, s_wq, nullptr, M, s.C, s.C, q_f, nullptr, s.C, st));
+        }
+        if (s.bits_q != 16) TAQ_TRY_HIP(launch_headquant_f32(q_f, M, s.C, s.H, s.bits_q, q_code, s_q, st));
+        TAQ_TRY_HIP(launch_attn_fp(q_f, q_code, s_q, static_cast<const uint8_t*>(qkv_packed), s, o_f, dbg ? dbg->p_code : nullptr, st));
+        if (w16) {
+            TAQ_TRY_HIP(launch_gemm_fp(o_f, true, reinterpret_cast<const __half*>(Wo), bias_o, M, s.C, s.C, nullptr,
+                                       static_cast<__half*>(out), s.C, st));
+        } else {
+            TAQ_TRY_HIP(launch_rowquant_f32(o_f, M, s.C, o_code, s_o, st));
+            TAQ_TRY_HIP(launch_gemm_i8(o_code, s_o, Wo, s_wo, bias_o, M, s.C, s.C, nullptr, static_cast<__half*>(out), s.C, st));
+        }
+        if (dbg) {
+            const size_t MC = (size_t)M * s.C;
+            if (dbg->h_code && !w16) TAQ_TRY_HIP(hipMemcpyAsync(dbg->h_code, h_code, MC, hipMemcpyDeviceToDevice, st));
+            if (dbg->s_h && !w16) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_h, s_h, (size_t)M * 4, hipMemcpyDeviceToDevice, st));
+            if (dbg->q_code && s.bits_q != 16) TAQ_TRY_HIP(hipMemcpyAsync(dbg->q_code, q_code, MC, hipMemcpyDeviceToDevice, st));
+            if (dbg->s_Q && s.bits_q != 16) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_Q, s_q, (size_t)M * s.H * 4, hipMemcpyDeviceToDevice, st));
+            if (dbg->O) TAQ_TRY_HIP(hipMemcpyAsync(dbg->O, o_f, MC * 4, hipMemcpyDeviceToDevice, st));
+            if (dbg->o_code && !w16) TAQ_TRY_HIP(hipMemcpyAsync(dbg->o_code, o_code, MC, hipMemcpyDeviceToDevice, st));
+            if (dbg->s_o && !w16) TAQ_TRY_HIP(hipMemcpyAsync(dbg->s_o, s_o, (size_t)M * 4, hipMemcpyDeviceToDevice, st));
+        }
+        return TAQ_OK;
+    }
 
     if (fused_supported(s) && !(dbg && dbg->stage_mask)) {
         // the whole block in one kernel; taps are written by the kernel itself
@@ -353,6 +404,15 @@ int taq_cross_attn_batched(int R, const taq_request* table, const taq_shape* sha
                                static_cast<uint8_t*>(workspace) + (size_t)r * per, hip_stream, nullptr);
         if (rc != TAQ_OK) return rc;
     }
+    return TAQ_OK;
+}
+
+int taq_mse_f16(const void* x_f16, const void* y_f16, size_t n, double* out, void* hip_stream) {
+    if (!x_f16 || !y_f16 || !out || n == 0) return TAQ_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(x_f16) & 1u) || (reinterpret_cast<uintptr_t>(y_f16) & 1u) || (reinterpret_cast<uintptr_t>(out) & 7u))
+        return TAQ_ERR_MISALIGNED;
+    TAQ_TRY_HIP(launch_mse_f16(static_cast<const __half*>(x_f16), static_cast<const __half*>(y_f16), n, out,
+                               static_cast<hipStream_t>(hip_stream)));
     return TAQ_OK;
 }
 

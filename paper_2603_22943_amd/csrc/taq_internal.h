@@ -115,7 +115,11 @@ static inline size_t fused_lds_bytes(const taq_shape& s, int tok = 32) {
 
 // Shapes the fused block kernel is instantiated for: (d, H) = (40, 8), (80, 8), (64, 10), as long as
 // its working set fits the 160 KiB of LDS of a compute unit.
+// Any of the full-precision modes (an unquantized projection, Q~ or probabilities): the float32 kernel-per-stage path.
+static inline bool fp_mode(const taq_shape& s) { return s.bits_proj == 16 || s.bits_q == 16 || s.bits_prob == 16; }
+
 static inline bool fused_supported(const taq_shape& s) {
+    if (fp_mode(s)) return false;
     if (s.bits_kv != 4 && s.bits_kv != 8) return false;
     if (s.C % s.H) return false;
     const int d = s.C / s.H;
@@ -132,6 +136,7 @@ static inline size_t mid_lds_bytes(const taq_shape& s) {
     return nh * kv_image(s).head_bytes + 32 * ((size_t)s.C + 16) + nh * d * 4 + 32 * 4 + 8 * nh * (size_t)((d + 15) / 16) * 1024;
 }
 static inline bool mid_supported(const taq_shape& s) {
+    if (fp_mode(s)) return false;
     if (s.bits_kv != 4 && s.bits_kv != 8) return false;
     if (s.C % s.H) return false;
     const int d = s.C / s.H;
@@ -265,6 +270,19 @@ hipError_t launch_kv_unpack(const uint8_t* packed, const taq_shape& s, int8_t* k
 hipError_t launch_gemm_i8(const int8_t* A, const float* sa, const int8_t* W, const float* sw,
                           const float* bias, int M, int N, int K, float* out_f32, __half* out_f16,
                           int ldo, hipStream_t st);
+
+// Full-precision stages (shape.bits_proj / bits_q / bits_prob = 16), float32 arithmetic:
+//   out[m][n] = sum_k A[m][k] * W[n][k] (+ bias[n]); A f16 or f32 [M][K], W f16 [N][K]; float32 and / or fp16 result
+hipError_t launch_gemm_fp(const void* A, bool a_is_f32, const __half* W, const float* bias, int M, int N, int K,
+                          float* out_f32, __half* out_f16, int ldo, hipStream_t st);
+//   protected K / V rows (fp16, compacted by slot, plus the transposed V copy) from float32 projection rows [B*T][2C]
+hipError_t launch_kv_rows_from_f32(const float* rows_f, const int* ntrig, const int* trig_idx, int B, int T, int C,
+                                   __half* k16, __half* v16, __half* v16t, hipStream_t st);
+//   scores, softmax, Eq. (3), A^ V~ with Q unquantized (q_f) or as codes and scales, probabilities at shape.bits_prob
+hipError_t launch_attn_fp(const float* q_f, const int8_t* q_code, const float* s_q, const uint8_t* packed, const taq_shape& s,
+                          float* o_f, uint8_t* p_code, hipStream_t st);
+//   mean squared difference of two fp16 arrays into a device double
+hipError_t launch_mse_f16(const __half* x, const __half* y, size_t n, double* out, hipStream_t st);
 
 // K~/V~ image for the fused kernel, from the codes and scales already in qkv_packed.
 hipError_t launch_kv_image(uint8_t* packed, const taq_shape& s, hipStream_t st);

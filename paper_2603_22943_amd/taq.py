@@ -40,7 +40,7 @@ EXPORTS = [
     "taq_kv_packed_bytes", "taq_kv_code_layout", "taq_workspace_bytes", "taq_quantize_weight", "taq_weight_bytes", "taq_pack_weight",
     "taq_quantize_kv",
     "taq_quantize_kv_w8",
-    "taq_cross_attn", "taq_cross_attn_ex", "taq_cross_attn_static", "taq_cross_attn_batched", "taq_unpack_kv",
+    "taq_cross_attn", "taq_cross_attn_ex", "taq_cross_attn_static", "taq_cross_attn_batched", "taq_unpack_kv", "taq_mse_f16",
     "taq_status_string",
 ]
 
@@ -100,6 +100,7 @@ def load() -> ctypes.CDLL:
     lib.taq_cross_attn_static.argtypes = [vp, vp, vp, vp, vp, vp, shp, vp, vp]
     lib.taq_cross_attn_batched.argtypes = [ci, ctypes.POINTER(taq_request), shp, vp, vp]
     lib.taq_unpack_kv.argtypes = [vp, shp, vp, vp, vp, vp, vp, vp, vp]
+    lib.taq_mse_f16.argtypes = [vp, vp, ctypes.c_size_t, vp, vp]
     for name in EXPORTS:
         getattr(lib, name).restype = ctypes.c_char_p if name == "taq_status_string" else ci
     _lib = lib
@@ -257,6 +258,16 @@ def taq_cross_attn_batched(requests: Sequence[dict], shape: taq_shape, workspace
                                 device=requests[0]["hidden"].device if R else "cuda")
     _check(load().taq_cross_attn_batched(R, table, ctypes.byref(shape), _ptr(workspace), _stream(stream)),
            "taq_cross_attn_batched")
+
+
+def taq_mse_f16(x: torch.Tensor, y: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Mean squared difference of two fp16 tensors of equal size -> float64 tensor of one element on the device."""
+    assert x.dtype == torch.float16 and y.dtype == torch.float16 and x.numel() == y.numel()
+    assert x.is_contiguous() and y.is_contiguous()
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=x.device)
+    _check(load().taq_mse_f16(_ptr(x), _ptr(y), x.numel(), _ptr(out), _stream(stream)), "taq_mse_f16")
+    return out
 
 
 def taq_unpack_kv(qkv_packed: torch.Tensor, shape: taq_shape, stream=None) -> dict:

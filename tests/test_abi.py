@@ -66,10 +66,10 @@ def test_size_queries_are_host_only_and_consistent():
 @pytest.mark.parametrize("kw,expect", [
     (dict(bits_kv=5), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(bits_prob=5), T.TAQ_ERR_UNSUPPORTED_BITS),
-    (dict(bits_prob=16), T.TAQ_ERR_UNSUPPORTED_BITS),
-    (dict(bits_q=16), T.TAQ_ERR_UNSUPPORTED_BITS),
+    (dict(bits_prob=2), T.TAQ_ERR_UNSUPPORTED_BITS),
+    (dict(bits_q=12), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(prob_grid=3), T.TAQ_ERR_INVALID_ARG),
-    (dict(bits_proj=16), T.TAQ_ERR_UNSUPPORTED_BITS),
+    (dict(bits_proj=4), T.TAQ_ERR_UNSUPPORTED_BITS),
     (dict(C=324), T.TAQ_ERR_BAD_SHAPE),  # C % H != 0
     (dict(C=96, H=8), T.TAQ_ERR_BAD_SHAPE),  # d = 12, not a multiple of 8
     (dict(C=2048, H=8), T.TAQ_ERR_BAD_SHAPE),  # d = 256 > 160
