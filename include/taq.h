@@ -133,7 +133,8 @@ int taq_workspace_bytes(const taq_shape* shape, size_t* bytes);
 int taq_quantize_weight(const void* W_f16, int rows, int cols, int8_t* codes, float* scales,
                         void* hip_stream);
 
-/* Optional re-layout of a [C, C] weight-code matrix for taq_cross_attn (shape->w_layout = 1): `out` receives
+/* (Helpers of this build, not operations of the paper: the paper prescribes no memory layout.)
+ * Optional re-layout of a [C, C] weight-code matrix for taq_cross_attn (shape->w_layout = 1): `out` receives
  * the row-major codes followed by a copy ordered the way the matrix cores read them for this shape's head
  * dimension. The method is unchanged (the paper does not prescribe a memory layout); only load efficiency is.
  *   codes : i8 [C, C] row-major (as written by taq_quantize_weight); may be the start of `out` itself
@@ -208,10 +209,11 @@ int taq_cross_attn_static(const void* hidden, const void* qkv_packed, const int8
                           const float* scales, const uint8_t* trigger_mask, const taq_shape* shape,
                           void* out, void* hip_stream);
 
-/* R independent requests of one shape, each with its own weights, K~/V~ and hidden
- * states (e.g. R personalised checkpoints served together). `table` is HOST memory,
- * R entries, read before the call returns. `workspace` must hold R times
- * taq_workspace_bytes(). */
+/* The same block (Section III-B: Eq. 2 third line, the attention definition, Eq. 3) for R independent requests of
+ * one shape, each with its own weights, K~/V~ and hidden states: the serving setting the paper motivates (Section I:
+ * many personalised checkpoints of one backbone behind one service; one quantized checkpoint and one K~/V~ per
+ * request). `table` is HOST memory, R entries, read before the call returns. `workspace` must hold R times
+ * taq_workspace_bytes(). Requests of the single-kernel shapes go out as grouped launches of up to 16. */
 int taq_cross_attn_batched(int R, const taq_request* table, const taq_shape* shape,
                            void* workspace, void* hip_stream);
 
