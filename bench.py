@@ -212,9 +212,9 @@ def prep_layer(L, dev, bits_q=8, bits_prob=8, prob_grid=T.TAQ_PROB_LINEAR):
     return d
 
 
-def attn_call(d):
+def attn_call(d, debug=None):
     return lambda: T.taq_cross_attn(d["hidden"], d["packed"], d["wq"], d["wo"], d["scales"], d["mask"], d["s"],
-                                    d["out"], d["ws"])
+                                    d["out"], d["ws"], debug=debug)
 
 
 def profile_config3(dev, use_graph, reps):
@@ -275,6 +275,34 @@ def other_configs(dev, use_graph):
                    "ceiling_frac_from_hbm_roofline": min(1.0, ops / nbytes * HBM_PEAK_GBS * 1e9 / (INT8_PEAK_TOPS * 1e12)),
                    "data": "cache-resident (one buffer set)"}
     return out, mf
+
+
+def gemm_stage_mfma(dev, use_graph):
+    """The int8 GEMM of the kernel-per-stage path alone (stage masks TO_Q / TO_OUT of taq_cross_attn): MFMA utilisation
+    at (M = 2048, C = 1280) and (M = 8192, C = 320), cache-resident (one buffer set, re-used by every call), next to the
+    ceiling that this GEMM's own bytes leave: A [M, C] + W [C, C] int8 in, [M, C] float32 (to_q) or fp16 (to_out) out,
+    at the HBM peak; the time of a launch (a few microseconds at these sizes) is not in the ceiling."""
+    res = {}
+    for key, L in (("M2048_C1280", synth.config4()[1]), ("M8192_C320", synth.config2())):
+        d = prep_layer(L, dev)
+        s = d["s"]
+        allbits = (T.TAQ_STAGE_HIDDEN_QUANT | T.TAQ_STAGE_TO_Q | T.TAQ_STAGE_Q_QUANT | T.TAQ_STAGE_ATTN_CORE
+                   | T.TAQ_STAGE_O_QUANT | T.TAQ_STAGE_TO_OUT)
+        attn_call(d, T.make_debug(s, dev, stage_mask=allbits, taps=False)[0])()  # valid stage buffers in the workspace
+        M = L.B * L.N
+        ops = 2.0 * M * L.C * L.C
+        for name, bit, out_bytes in (("to_q", T.TAQ_STAGE_TO_Q, 4), ("to_out", T.TAQ_STAGE_TO_OUT, 2)):
+            dbg = T.make_debug(s, dev, stage_mask=bit, taps=False)[0]
+            r = Runner([attn_call(d, dbg)] * 8, use_graph=use_graph)
+            r.run(16)
+            t = r.time_events(400)
+            nbytes = M * L.C + L.C * L.C + M * L.C * out_bytes
+            t_floor = max(ops / (INT8_PEAK_TOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9))
+            res[key + "_" + name] = {"us": round(t * 1e6, 2), "int8_GOP": ops / 1e9, "achieved_TOPS": ops / t / 1e12,
+                                     "frac_of_int8_peak": ops / t / 1e12 / INT8_PEAK_TOPS,
+                                     "ceiling_frac_from_hbm_roofline": ops / (INT8_PEAK_TOPS * 1e12) / t_floor,
+                                     "bytes": nbytes, "data": "cache-resident (one buffer set)"}
+    return res
 
 
 COPY_BYTES = 256 << 20  # the known-size copy of the traffic probe reads and writes this many bytes
@@ -502,6 +530,7 @@ def main():
     oc, mf = other_configs(dev, not a.no_graph)
     result["other_configs_us"] = oc
     result["roofline_mfma_int8_c1280"] = mf
+    result["gemm_i8_stage_mfma"] = gemm_stage_mfma(dev, not a.no_graph)
     if not a.no_cpu_baseline:
         result["cpu_baseline"], result["block_bops"] = cpu_baseline(L, a.cpu_seconds)
     print(json.dumps(result), flush=True)
