@@ -58,6 +58,14 @@ def parse():
                    help="for `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE`: a device copy of known size, then eager steps")
     p.add_argument("--summarize-sq", nargs="+", metavar="CSV",
                    help="rocprofv3 --pmc SQ_* counter CSVs of --profile-only runs -> profiles/fused_block_kernel_cfg2_pmc.json")
+    p.add_argument("--profile-gemm", action="store_true",
+                   help="run only the int8 GEMM of the kernel-per-stage path (to_q at M=2048 C=1280 and M=8192 C=320; for rocprofv3)")
+    p.add_argument("--summarize-trace", nargs="+", metavar=("STATS_CSV", "OUT_TXT"),
+                   help="STATS_CSV OUT_TXT COMMAND [NOTE...]: the taq:: rows of a rocprofv3 --kernel-trace --stats "
+                        "kernel_stats.csv -> profiles/OUT_TXT, with the command and notes as its header")
+    p.add_argument("--summarize-sq-by-kernel", nargs="+", metavar="CSV",
+                   help="rocprofv3 --pmc SQ_* counter CSVs of any run -> a per-kernel table of counter means on stdout")
+    p.add_argument("--kernel-filter", default="", help="comma-separated substrings: --summarize-sq-by-kernel keeps matching kernels")
     p.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                    help="turn the two counter_collection CSVs of the traffic probe into profiles/traffic.json")
     return p.parse_args()
@@ -238,7 +246,7 @@ def other_configs(dev, use_graph):
 
     def timed(calls, reps=40):
         r = Runner(calls, use_graph=use_graph)
-        r.run(2 * len(calls))
+        r.prewarm(20.0)  # the clocks drop between measurements (graph capture, set-up copies): ramp them up again
         return r.time_events(reps * len(calls)) * len(calls) * 1e6  # us per pass over `calls`
 
     import dataclasses
@@ -277,7 +285,7 @@ def other_configs(dev, use_graph):
     return out, mf
 
 
-def gemm_stage_mfma(dev, use_graph):
+def gemm_stage_mfma(dev, use_graph, only=("to_q", "to_out")):
     """The int8 GEMM of the kernel-per-stage path alone (stage masks TO_Q / TO_OUT of taq_cross_attn): MFMA utilisation
     at (M = 2048, C = 1280) and (M = 8192, C = 320), cache-resident (one buffer set, re-used by every call), next to the
     ceiling that this GEMM's own bytes leave: A [M, C] + W [C, C] int8 in, [M, C] float32 (to_q) or fp16 (to_out) out,
@@ -292,9 +300,11 @@ def gemm_stage_mfma(dev, use_graph):
         M = L.B * L.N
         ops = 2.0 * M * L.C * L.C
         for name, bit, out_bytes in (("to_q", T.TAQ_STAGE_TO_Q, 4), ("to_out", T.TAQ_STAGE_TO_OUT, 2)):
+            if name not in only:
+                continue
             dbg = T.make_debug(s, dev, stage_mask=bit, taps=False)[0]
             r = Runner([attn_call(d, dbg)] * 8, use_graph=use_graph)
-            r.run(16)
+            r.prewarm(20.0)
             t = r.time_events(400)
             nbytes = M * L.C + L.C * L.C + M * L.C * out_bytes
             t_floor = max(ops / (INT8_PEAK_TOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9))
@@ -325,7 +335,65 @@ def summarize_sq(csvs):
     out["wavefronts_per_launch"] = out.get("SQ_WAVES", 2048.0)
     path = os.path.join(ROOT, "profiles", "fused_block_kernel_cfg2_pmc.json")
     json.dump(out, open(path, "w"), indent=1)
+    waves = out["wavefronts_per_launch"]
+    with open(path[:-5] + ".txt", "w") as f:
+        f.write("# rocprofv3 hardware counters of taq::fused_block_kernel<40, 8, 2, 1, 0, 32, false, 5, false> at configs[1]\n"
+                "# (B=2 N=4096 C=320 H=8 T=77). Commands (run from /tmp on the MI355X box, one pass per counter set):\n"
+                "#   rocprofv3 --pmc <at most 8 SQ_ counters> --output-format csv -d outK -o p -- python3 bench.py --profile-only --no-graph --steps 64 --warmup 16\n"
+                "#   python3 bench.py --summarize-sq out1/p_counter_collection.csv out2/p_counter_collection.csv ...   (writes this file and the .json)\n"
+                "# mean over the dispatches of the kernel (first 4 skipped); per wavefront = mean / wavefronts per launch\n"
+                "# (SQ_*_CYCLES, SQ_WAIT* and SQ_ACTIVE* tick once per 4 clocks)\n"
+                "counter,mean_per_launch,per_wavefront\n")
+        for k, v in out.items():
+            if k != "wavefronts_per_launch":
+                f.write(f"{k},{v:.0f},{v / waves:.1f}\n")
     print(json.dumps(out))
+
+
+def summarize_trace(stats_csv, out_txt, command, notes):
+    """The rows of this library's kernels from a rocprofv3 --kernel-trace --stats kernel_stats.csv, as text."""
+    import csv
+    rows = [r for r in csv.DictReader(open(stats_csv)) if "taq::" in r["Name"]]
+    with open(os.path.join(ROOT, "profiles", out_txt), "w") as f:
+        f.write("# rocprofv3 --kernel-trace --stats, this library's kernels. Command (run from /tmp on the MI355X box):\n")
+        f.write("#   " + command + "\n")
+        f.write("#   python3 bench.py --summarize-trace <the run's kernel_stats.csv> " + out_txt + " '<command>' <notes>\n")
+        for n in notes:
+            f.write("# " + n + "\n")
+        f.write("kernel,calls,total_us,average_us,min_us,max_us,percent\n")
+        for r in rows:
+            name = r["Name"].split("(")[0].replace("void ", "")
+            f.write(f"{name},{r['Calls']},{float(r['TotalDurationNs']) / 1e3:.1f},{float(r['AverageNs']) / 1e3:.2f},"
+                    f"{float(r['MinNs']) / 1e3:.2f},{float(r['MaxNs']) / 1e3:.2f},{float(r['Percentage']):.2f}\n")
+    print(open(os.path.join(ROOT, "profiles", out_txt)).read())
+
+
+def summarize_sq_by_kernel(csvs, keep=()):
+    """Per kernel (template arguments kept, parameter list dropped) and grid size: the mean over its dispatches of every
+    counter found in the CSVs, per launch and per wavefront. Text on stdout, for a summary file under profiles/."""
+    import csv
+    print("# rocprofv3 hardware counters per kernel of this library. Commands (run from /tmp on the MI355X box, one pass per\n"
+          "# counter set, at most 8 SQ_ counters each; <workload> is one of bench.py's --profile-config3 / --profile-gemm /\n"
+          "# --profile-only, launched eagerly):\n"
+          "#   rocprofv3 --pmc <counters> --output-format csv -d outK -o p -- python3 bench.py <workload> --no-graph\n"
+          "#   python3 bench.py --summarize-sq-by-kernel out1/p_counter_collection.csv out2/p_counter_collection.csv ... [--kernel-filter a,b]\n"
+          "# mean over all dispatches of the kernel at that grid; SQ_*_CYCLES, SQ_WAIT* and SQ_ACTIVE* tick once per 4 clocks")
+    acc = {}
+    for path in csvs:
+        for r in csv.DictReader(open(path)):
+            name = r["Kernel_Name"].split("(")[0].replace("void ", "").replace("taq::", "")
+            if "taq::" not in r["Kernel_Name"] or (keep and not any(k in name for k in keep)):
+                continue
+            key = (name, r.get("Grid_Size", ""), r.get("Workgroup_Size", ""))
+            acc.setdefault(key, {}).setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+    for key in sorted(acc, key=lambda k: (k[0], k[1])):
+        cs = acc[key]
+        n = min(len(v) for v in cs.values())
+        waves = sum(cs["SQ_WAVES"]) / len(cs["SQ_WAVES"]) if "SQ_WAVES" in cs else float("nan")
+        print(f"{key[0]}  grid {key[1]} wg {key[2]}  dispatches {n}  wavefronts {waves:.0f}")
+        for c in sorted(cs):
+            m = sum(cs[c]) / len(cs[c])
+            print(f"    {c:30s} {m:14.1f} per launch {m / waves:10.1f} per wavefront")
 
 
 def summarize_pmc(fetch_csv, write_csv):
@@ -353,6 +421,24 @@ def summarize_pmc(fetch_csv, write_csv):
     out["fused_bytes_per_launch"] = out["fetch"]["fused_bytes_per_launch"] + out["write"]["fused_bytes_per_launch"]
     path = os.path.join(ROOT, "profiles", "fused_block_kernel_cfg2_hbm_traffic.json")
     json.dump(out, open(path, "w"), indent=1)
+    with open(path[:-5] + ".md", "w") as f:
+        f.write("# HBM traffic of taq::fused_block_kernel<40, 8, 2, ...> at configs[1] (B=2 N=4096 C=320 H=8 T=77)\n\n"
+                "Commands (run from /tmp on the MI355X box; each counter in a pass of its own):\n\n"
+                "    rocprofv3 --pmc FETCH_SIZE --output-format csv -d fetch -o p -- python3 bench.py --traffic-probe --steps 64\n"
+                "    rocprofv3 --pmc WRITE_SIZE --output-format csv -d write -o p -- python3 bench.py --traffic-probe --steps 64\n"
+                "    python3 bench.py --summarize-pmc fetch/p_counter_collection.csv write/p_counter_collection.csv\n\n"
+                "`--traffic-probe` first runs four device copies of 256 MiB (known size), then 64 eager `taq_cross_attn`\n"
+                "calls over the ring of buffer sets. `--summarize-pmc` scales each counter by what it read for the copy and\n"
+                "writes this file and `fused_block_kernel_cfg2_hbm_traffic.json`:\n\n"
+                "| counter | copy of 256 MiB reads as | scale factor | fused kernel reads as | bytes per launch |\n|---|---|---|---|---|\n")
+        for name, counter in (("fetch", "FETCH_SIZE"), ("write", "WRITE_SIZE")):
+            o = out[name]
+            f.write(f"| {counter} | {o['copy_counter_KiB']:.1f} KiB | {o['scale_factor']:.3f} | {o['fused_counter_KiB']:.1f} KiB | "
+                    f"{o['fused_bytes_per_launch'] / 1e6:.2f} MB |\n")
+        tokens, C = 8192, 320
+        f.write(f"\nTotal {out['fused_bytes_per_launch'] / 1e6:.2f} MB per launch; the algorithmic bytes of the launch are "
+                f"{(tokens * 4 * C + 2 * C * C + 2 * (2 * 77 * C + 2 * 4 * 8 * 77)) / 1e6:.2f} MB (hidden in and out "
+                f"{tokens * 4 * C / 1e6:.2f} MB, the rest weights and K~/V~).\n")
     print(json.dumps(out))
 
 
@@ -360,6 +446,12 @@ def main():
     a = parse()
     if a.summarize_sq:
         summarize_sq(a.summarize_sq)
+        return
+    if a.summarize_trace:
+        summarize_trace(a.summarize_trace[0], a.summarize_trace[1], a.summarize_trace[2], a.summarize_trace[3:])
+        return
+    if a.summarize_sq_by_kernel:
+        summarize_sq_by_kernel(a.summarize_sq_by_kernel, tuple(k for k in a.kernel_filter.split(",") if k))
         return
     if a.summarize_pmc:
         summarize_pmc(*a.summarize_pmc)
@@ -374,6 +466,9 @@ def main():
     torch.cuda.set_device(0)
     if a.profile_config3:
         profile_config3(dev, not a.no_graph, reps=50)
+        return
+    if a.profile_gemm:
+        print(json.dumps({"gemm_i8_stage_mfma": gemm_stage_mfma(dev, not a.no_graph, only=("to_q",))}), flush=True)
         return
     L = synth.config2()
     s = T.make_shape(B=L.B, N=L.N, C=L.C, H=L.H, T=L.T, Cc=L.Cc, bits_kv=L.bits_kv, w_layout=1)

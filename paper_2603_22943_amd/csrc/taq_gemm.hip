@@ -80,10 +80,13 @@ __global__ __launch_bounds__(256) void gemm_i8_lds_kernel(const int8_t* __restri
     const int m0 = blockIdx.x * (16 * MB), n0 = blockIdx.y * (16 * NB);
     const int KC = K >> 6;
     // global loads: four consecutive lanes fetch the 64 contiguous bytes of one row; MFMA operands: lane (r16, q) holds
-    // codes 16q .. 16q+15 of row r16. Segment g of row r sits at r * 64 + (g ^ (r >> 2 & 3)) * 16 inside its block, which
-    // makes the wave-wide 16-byte stores contiguous and spreads any 16 lanes of an operand read over all 64 banks.
+    // codes 16q .. 16q+15 of row r16. Segment g of row r sits at r * 64 + (g ^ f(r)) * 16 inside its block, with
+    // f(r) = (r >> 1 ^ r >> 2) & 3: the wave-wide 16-byte stores stay contiguous, and the 16-byte operand reads of any
+    // eight consecutive lanes fall into eight different 16-byte columns of a 128-byte bank row (of any sixteen lanes:
+    // sixteen columns of a 256-byte row).
     const int lrow = lane >> 2, lseg = lane & 3;
-    const int st_off = lrow * 64 + ((lseg ^ (lrow >> 2 & 3)) << 4), ld_off = r16 * 64 + ((q ^ (r16 >> 2 & 3)) << 4);
+    const int st_off = lrow * 64 + ((lseg ^ ((lrow >> 1 ^ lrow >> 2) & 3)) << 4);
+    const int ld_off = r16 * 64 + ((q ^ ((r16 >> 1 ^ r16 >> 2) & 3)) << 4);
     // this wavefront's loads of a stage: blocks wave, wave + 4, ... (token blocks first, then weight blocks)
     const int8_t* src[NLD];
 #pragma unroll
