@@ -541,8 +541,8 @@ def main():
     # taq_quantize_kv, once per prompt
     kv_runner = Runner([lambda: T.taq_quantize_kv(ctx, mask, Wk, Wv, L.bits_kv, s, packed, ws0)] * 4,
                        use_graph=not a.no_graph)
-    kv_runner.run(8)
-    kv_s = kv_runner.time_wall(64) / 64
+    kv_runner.prewarm(10.0)
+    kv_s = kv_runner.time_events(512)
     result["quantize_kv_us"] = kv_s * 1e6
     # same with the to_k / to_v weight codes formed once per checkpoint
     kc, ks_ = T.taq_quantize_weight(Wk)
@@ -550,8 +550,8 @@ def main():
     wkv, swkv = torch.cat([kc, vc]).contiguous(), torch.cat([ks_, vs_]).contiguous()
     kv8_runner = Runner([lambda: T.taq_quantize_kv_w8(ctx, mask, wkv, swkv, L.bits_kv, s, packed, ws0)] * 4,
                         use_graph=not a.no_graph)
-    kv8_runner.run(8)
-    result["quantize_kv_cached_weight_codes_us"] = kv8_runner.time_wall(64) / 64 * 1e6
+    kv8_runner.prewarm(10.0)
+    result["quantize_kv_cached_weight_codes_us"] = kv8_runner.time_events(512) * 1e6
     result["value_with_quantize_kv_every_step"] = tokens / (wall / a.steps + kv_s)
 
     # ---- roofline of the dominant kernel. taq_cross_attn at this shape is ONE kernel (the fused block), so its

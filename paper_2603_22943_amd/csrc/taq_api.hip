@@ -278,7 +278,7 @@ int taq_cross_attn_ex(const void* hidden, const void* qkv_packed, const int8_t* 
         FusedReq rq = {static_cast<const __half*>(hidden), static_cast<const uint8_t*>(qkv_packed), Wq, Wo, scales,
                        static_cast<__half*>(out)};
         TAQ_TRY_HIP(launch_fused_mid(rq, s, o_f, q_f, dbg, st));
-        if (M <= 1024) {  // few token tiles: every to_out workgroup quantizes its 32 rows of A^ V~ itself
+        if (M <= 1024) {  // few token tiles: every to_out workgroup quantizes its 16 rows of A^ V~ itself
             TAQ_TRY_HIP(launch_to_out_tail(rq, s, o_f, q_f, nullptr, nullptr, dbg, st));
         } else {          // many: quantize each row once, in a kernel of its own
             TAQ_TRY_HIP(launch_rowquant_f32(o_f, M, s.C, o_code, s_o, st));

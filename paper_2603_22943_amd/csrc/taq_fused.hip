@@ -113,18 +113,19 @@ hipError_t launch_pack_weight(const int8_t* codes, const taq_shape& s, int8_t* o
 }
 
 // Per-token quantization of A^ V~ and to_out for the head-group shapes (C = 1280):
-// Y^T[c][n] = Wo[c][:] . o_code[n][:]. A workgroup owns 32 image tokens and OT output tiles of 16 channels; one
+// Y^T[c][n] = Wo[c][:] . o_code[n][:]. A workgroup owns 16 TG image tokens and OT output tiles of 16 channels; one
 // wavefront per (output tile, token group of 16), so that each wavefront has only C/64 weight loads in front of its
-// MFMAs. FUSEQ: the float32 rows of A^ V~ and the partial row maxima come from the workspace and every workgroup of
-// a token tile forms the same int8 codes of its 32 rows (32 threads per row) in LDS: one kernel less, worth it while
+// MFMAs. (TG = 1: what a workgroup pulls through its compute unit's vector memory path, its rows plus one 20 KiB weight
+// slice per wavefront, is half of TG = 2's 480 KiB, and that transfer is most of the kernel's time.) FUSEQ: the float32 rows of A^ V~ and the partial row maxima come from the workspace and every workgroup of
+// a token tile forms the same int8 codes of its rows (32 threads per row) in LDS: one kernel less, worth it while
 // the layer has few token tiles. Otherwise the codes and scales were formed once by the row quantizer kernel.
 // Same operand layout and epilogue as the last phase of the fused kernel.
-template <int C, int OT, bool FUSEQ, int TT = 1>
-__global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, FusedDims dm) {
-    constexpr int KC = C / 64, NT = 128 * OT, TILE_RS = C + 16;
-    constexpr int TOKS = 32 * TT;  // image tokens per workgroup (TT = 2: every weight load serves two 32-token tiles)
-    static_assert(NT == 1024 && C % 128 == 0, "32 threads per token row");
-    static_assert(TT == 1 || !FUSEQ, "the in-kernel quantizer maps 32 threads to each of 32 rows");
+template <int C, int OT, bool FUSEQ, int TT = 1, int TG = 2>
+__global__ __launch_bounds__(64 * OT * TG) void to_out_tail_kernel(FusedTable tab, FusedDims dm) {
+    constexpr int KC = C / 64, NT = 64 * OT * TG, TILE_RS = C + 16;
+    constexpr int TOKS = 16 * TG * TT;  // image tokens per workgroup: every weight load serves TT token groups of 16
+    static_assert(C % 128 == 0, "32 threads per token row");
+    static_assert(!FUSEQ || NT == 32 * TOKS, "the in-kernel quantizer maps 32 threads to each row");
     constexpr int CH = C / 128;  // float4 pieces of a row per thread
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
@@ -195,7 +196,7 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
     for (int ks = 0; ks < KC; ++ks) {
 #pragma unroll
         for (int g = 0; g < TT; ++g) {
-            const int32x4_t hb = *reinterpret_cast<const int32x4_t*>(tileq + (32 * g + tl) * TILE_RS + 64 * ks + 16 * q);
+            const int32x4_t hb = *reinterpret_cast<const int32x4_t*>(tileq + (16 * TG * g + tl) * TILE_RS + 64 * ks + 16 * q);
             acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa[ks], hb, acc[g], 0, 0, 0);
         }
     }
@@ -204,9 +205,9 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
     const float4 b4 = *reinterpret_cast<const float4*>(rq.scales + 2 * C + c);
 #pragma unroll
     for (int g = 0; g < TT; ++g) {
-        const int n = n0 + 32 * g + tl;
+        const int n = n0 + 16 * TG * g + tl;
         const size_t tok = (size_t)b * N + (n < N ? n : N - 1);
-        const float so = s_o[32 * g + tl];
+        const float so = s_o[16 * TG * g + tl];
         const float y0 = (float)acc[g][0] * (so * w4.x) + b4.x;
         const float y1 = (float)acc[g][1] * (so * w4.y) + b4.y;
         const float y2 = (float)acc[g][2] * (so * w4.z) + b4.z;
@@ -218,14 +219,15 @@ __global__ __launch_bounds__(128 * OT) void to_out_tail_kernel(FusedTable tab, F
     }
 }
 
-template <int C, int OT, bool FUSEQ, int TT>
+template <int C, int OT, bool FUSEQ, int TT, int TG>
 static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hipStream_t st) {
-    const size_t bytes = 32 * TT * (C + 16) + 32 * TT * 4;
+    constexpr int TOKS = 16 * TG * TT;
+    const size_t bytes = TOKS * (C + 16) + TOKS * 4;
     static std::atomic<unsigned long long> lds_set{0};
-    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&to_out_tail_kernel<C, OT, FUSEQ, TT>), 160 * 1024, lds_set);
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&to_out_tail_kernel<C, OT, FUSEQ, TT, TG>), 160 * 1024, lds_set);
     if (e != hipSuccess) return e;
-    const int tiles = (dm.N + 32 * TT - 1) / (32 * TT);
-    hipLaunchKernelGGL((to_out_tail_kernel<C, OT, FUSEQ, TT>), dim3(tiles * dm.B, C / 16 / OT), dim3(128 * OT), bytes, st, tab, dm);
+    const int tiles = (dm.N + TOKS - 1) / TOKS;
+    hipLaunchKernelGGL((to_out_tail_kernel<C, OT, FUSEQ, TT, TG>), dim3(tiles * dm.B, C / 16 / OT), dim3(64 * OT * TG), bytes, st, tab, dm);
     return hipGetLastError();
 }
 
@@ -345,8 +347,8 @@ hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const floa
     dm.omax_n = mid_omax_n(s);
     dm.ws_ocode = o_code;
     dm.ws_so = s_o;
-    // codes from the row quantizer (large layers): 64 tokens per workgroup, so that a weight load serves two token tiles
-    if (s.C == 1280) return o_code ? launch_tail_cfg<1280, 8, false, 2>(tab, dm, st) : launch_tail_cfg<1280, 8, true, 1>(tab, dm, st);
+    // codes from the row quantizer (large layers): 64 tokens per workgroup, so that a weight load serves four token groups
+    if (s.C == 1280) return o_code ? launch_tail_cfg<1280, 8, false, 4, 1>(tab, dm, st) : launch_tail_cfg<1280, 8, true, 1, 1>(tab, dm, st);
     return hipErrorInvalidValue;
 }
 
