@@ -214,8 +214,17 @@ hipError_t launch_gemm_i8(const int8_t* A, const float* sa, const int8_t* W, con
                           int M, int N, int K, float* out_f32, __half* out_f16, int ldo, hipStream_t st) {
     if (M <= 0 || N <= 0) return hipSuccess;
     if (K % 64 == 0 && N % 4 == 0 && ldo % 4 == 0) {
-        dim3 grid((M + 127) / 128, (N + 79) / 80);
-        hipLaunchKernelGGL((gemm_i8_lds_kernel<8, 5, 4>), grid, dim3(256), 0, st, A, sa, W, sw, bias, M, N, K, out_f32, out_f16, ldo);
+        // While 128-token tiles would give every compute unit at most one workgroup, 64-token tiles (two workgroups per
+        // unit, each hiding the other's waits) are faster: 7.8 -> 7.0 us at (8192, 320), 11.7 -> 11.2 us at (2048, 1280);
+        // with more tiles than that the larger tile's fewer weight reads win (12.1 vs 12.9 us at (8192, 640)).
+        const long tiles128 = (long)((M + 127) / 128) * ((N + 79) / 80);
+        if (tiles128 <= 256) {
+            dim3 grid((M + 63) / 64, (N + 79) / 80);
+            hipLaunchKernelGGL((gemm_i8_lds_kernel<4, 5, 4>), grid, dim3(256), 0, st, A, sa, W, sw, bias, M, N, K, out_f32, out_f16, ldo);
+        } else {
+            dim3 grid((M + 127) / 128, (N + 79) / 80);
+            hipLaunchKernelGGL((gemm_i8_lds_kernel<8, 5, 4>), grid, dim3(256), 0, st, A, sa, W, sw, bias, M, N, K, out_f32, out_f16, ldo);
+        }
         return hipGetLastError();
     }
     dim3 grid((M + 63) / 64, (N + 63) / 64);  // (M, which may be large, along x)
