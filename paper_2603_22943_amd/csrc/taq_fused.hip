@@ -245,6 +245,7 @@ hipError_t launch_fused_block(const FusedReq* reqs, int R, const taq_shape& s, c
     dm.nt16 = (s.T + 15) / 16;
     dm.w_layout = s.w_layout;
     dm.w_pack_off = (unsigned)weight_pack_offset(s);
+    dm.w_bytes = (unsigned)(s.w_layout ? weight_pack_bytes(s) : (size_t)s.C * s.C);
     const int d = s.C / s.H;
     const float sigma = s.softmax_scale != 0.f ? s.softmax_scale : 1.0f / sqrtf((float)d);
     dm.sig2 = sigma * 1.4426950408889634f;
@@ -297,6 +298,7 @@ hipError_t launch_fused_mid(const FusedReq& rq, const taq_shape& s, float* o_f, 
     dm.nt16 = (s.T + 15) / 16;
     dm.w_layout = s.w_layout;
     dm.w_pack_off = (unsigned)weight_pack_offset(s);
+    dm.w_bytes = (unsigned)(s.w_layout ? weight_pack_bytes(s) : (size_t)s.C * s.C);
     const int d = s.C / s.H;
     const float sigma = s.softmax_scale != 0.f ? s.softmax_scale : 1.0f / sqrtf((float)d);
     dm.sig2 = sigma * 1.4426950408889634f;
@@ -340,6 +342,7 @@ hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const floa
     dm.T = s.T;
     dm.w_layout = s.w_layout;
     dm.w_pack_off = (unsigned)weight_pack_offset(s);
+    dm.w_bytes = (unsigned)(s.w_layout ? weight_pack_bytes(s) : (size_t)s.C * s.C);
     taq_debug none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0u};
     dm.dbg = dbg ? *dbg : none;
     dm.ws_of = const_cast<float*>(o_f);

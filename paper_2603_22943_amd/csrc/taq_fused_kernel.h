@@ -45,6 +45,12 @@ __device__ __forceinline__ unsigned pack4(int a, int b, int c, int d) {
     return (unsigned)(a & 0xFF) | ((unsigned)(b & 0xFF) << 8) | ((unsigned)(c & 0xFF) << 16) | ((unsigned)(d & 0xFF) << 24);
 }
 
+// Buffer descriptor of a weight matrix: base address, no stride (raw byte offsets), `bytes` addressable, 32-bit data
+// format; out-of-range reads return zero.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t weight_rsrc(const int8_t* p, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(p), 0, (int)bytes, 0x00020000);
+}
+
 __device__ __forceinline__ float byte_to_float(unsigned w, int e) { return (float)(int)(int8_t)((w >> (8 * e)) & 0xFF); }
 
 // ------------------------------------------------------------------------------------------
@@ -59,6 +65,7 @@ struct FusedDims {
     int nt16;          // ceil(T/16)
     int w_layout;      // 1: Wq / Wo carry an operand-ordered copy at w_pack_off
     unsigned w_pack_off;
+    unsigned w_bytes;  // bytes of each weight buffer (row-major codes, plus the operand-ordered copy if present)
     float sig2;        // softmax scale * log2(e)
     float qmaxq;       // 127 or 7: grid of Q~ (Eq. 2, third line)
     float pmax;        // linear grid: 255 or 15 (Eq. 3); log2 grid: 256, which brings 2^-code * s_V to the linear grid's magnitudes
@@ -252,12 +259,17 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     for (int j = 0; j < TPH; ++j) {
         const int c = h * D + 16 * j + r16;
         wrow[j] = dm.w_layout ? (int)dm.w_pack_off + ((h * TPH + j) * KC) * 1024 + lane * 16 : (c < C ? c : C - 1) * C + 16 * q;
+        // Weight rows past the head (the upper lanes of a partly filled last tile) are not fetched: their products are
+        // dropped anyway, and at d = 40 they are a sixth of the bytes every CU pulls through its L2. Their lanes carry
+        // an offset past the end of the buffer, for which a buffer load returns zero without a memory access.
+        if (!((D % 16 == 0) || 16 * j + 16 <= D || r16 < D - 16 * j)) wrow[j] = 0x7fffffff;
     }
-    // Weight rows past the head (the upper lanes of a partly filled last tile) are not fetched: their products are
-    // dropped anyway, and at d = 40 they are a sixth of the bytes every CU pulls through its L2.
-    auto load_w = [&](const int8_t* base, int j, int off) -> int32x4_t {
-        if ((D % 16 == 0) || 16 * j + 16 <= D || r16 < D - 16 * j) return *reinterpret_cast<const int32x4_t*>(base + wrow[j] + off);
-        return (int32x4_t){0, 0, 0, 0};
+    // Buffer loads: the descriptor (base, size) and the step sit in scalar registers and the lane's part is a 32-bit
+    // offset, so a load costs no vector address arithmetic (a 64-bit vector add per load otherwise) and the lanes
+    // without a row need neither a branch nor registers cleared by hand.
+    const __amdgpu_buffer_rsrc_t rs_wq = weight_rsrc(rq.wq, dm.w_bytes), rs_wo = weight_rsrc(rq.wo, dm.w_bytes);
+    auto load_w = [&](const __amdgpu_buffer_rsrc_t rs, int j, int off) -> int32x4_t {
+        return (int32x4_t)__builtin_amdgcn_raw_buffer_load_b128(rs, wrow[j], off, 0);
     };
     int32x4_t wreg[F::PREFETCH_W ? TPH : 1][F::PREFETCH_W ? KC : 1];
     constexpr int RING = CORE ? 0 : F::RING, NF = F::NF;
@@ -345,11 +357,11 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         for (int it = 0; it < KC; ++it) {
             if (F::PREFETCH_W) {
     #pragma unroll
-                for (int j = 0; j < TPH; ++j) wreg[j][it] = load_w(rq.wq, j, wstep * it);
+                for (int j = 0; j < TPH; ++j) wreg[j][it] = load_w(rs_wq, j, wstep * it);
             }
             if constexpr (RING > 0) {  // the first RING loads of to_q, in the order the MFMAs use them
     #pragma unroll
-                for (int f = it * RPS; f < (it + 1) * RPS && f < RING; ++f) wring[f] = load_w(rq.wq, f % TPH, wstep * (f / TPH));
+                for (int f = it * RPS; f < (it + 1) * RPS && f < RING; ++f) wring[f] = load_w(rs_wq, f % TPH, wstep * (f / TPH));
             }
             if (tid < 16 * TOK) {
                 const half2_t x01 = *reinterpret_cast<const half2_t*>(&xin[it].x), x23 = *reinterpret_cast<const half2_t*>(&xin[it].y);
@@ -506,7 +518,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
                 for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hbk[nt], pacc[nt][j], 0, 0, 0);
                 // the slot is free again: the load RING places ahead takes it
-                if (f + RING < NF) wring[f % RING] = load_w(rq.wq, (f + RING) % TPH, wstep * ((f + RING) / TPH));
+                if (f + RING < NF) wring[f % RING] = load_w(rs_wq, (f + RING) % TPH, wstep * ((f + RING) / TPH));
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -517,7 +529,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
             for (int ks = 0; ks < KC; ++ks) {
-                const int32x4_t wa = load_w(rq.wq, j, wstep * ks);
+                const int32x4_t wa = load_w(rs_wq, j, wstep * ks);
 #pragma unroll
                 for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
             }
@@ -646,7 +658,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     __builtin_amdgcn_s_waitcnt(0x0F70);
     if constexpr (RING > 0 && NTT == 1) {  // ... or its first RING loads
 #pragma unroll
-        for (int f = 0; f < RING; ++f) wring[f] = load_w(rq.wo, f % TPH, wstep * (f / TPH));
+        for (int f = 0; f < RING; ++f) wring[f] = load_w(rs_wo, f % TPH, wstep * (f / TPH));
     }
 
     // ================= scores: x[t][n] = (K~ Q~^T)[t][n] * s_K[t]   (times sQ * sigma * log2 e later)
@@ -963,11 +975,11 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
         for (int j = 0; j < TPH; ++j)
 #pragma unroll
-            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = load_w(rq.wo, j, wstep * ks);
+            for (int ks = 0; ks < KC; ++ks) wreg[j][ks] = load_w(rs_wo, j, wstep * ks);
     }
     if constexpr (RING > 0 && NTT == 2) {  // two token tiles per wavefront: the attention needs the registers; the first
 #pragma unroll                         // RING loads of to_out travel while A^ V~ is quantized
-        for (int f = 0; f < RING; ++f) wring[f] = load_w(rq.wo, f % TPH, wstep * (f / TPH));
+        for (int f = 0; f < RING; ++f) wring[f] = load_w(rs_wo, f % TPH, wstep * (f / TPH));
     }
     // ================= per-token int8 codes of O over all heads
     // O = oacc * of, of = 2^-kexp / pmax (times range / Z on the row-range grid). Where nobody needs O itself (no tap, no
@@ -1044,7 +1056,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                 const int32x4_t wa = wring[f % RING];
 #pragma unroll
                 for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hbk[nt], pacc[nt][j], 0, 0, 0);
-                if (f + RING < NF) wring[f % RING] = load_w(rq.wo, (f + RING) % TPH, wstep * ((f + RING) / TPH));
+                if (f + RING < NF) wring[f % RING] = load_w(rs_wo, (f + RING) % TPH, wstep * ((f + RING) / TPH));
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -1060,7 +1072,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
             for (int ks = 0; ks < KC; ++ks) {
-                const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : load_w(rq.wo, j, wstep * ks);
+                const int32x4_t wa = F::PREFETCH_W ? wreg[j][ks] : load_w(rs_wo, j, wstep * ks);
 #pragma unroll
                 for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wa, hb[nt][ks], pacc[nt][j], 0, 0, 0);
             }
