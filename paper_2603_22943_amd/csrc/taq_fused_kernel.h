@@ -222,16 +222,17 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, hl = (tid >> 6) % NH, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
-    // Head-group variant: blockIdx.y is the head group (the order in which workgroups meet the 8 XCDs, head group
-    // fastest or token tile fastest, made no measurable difference at these sizes).
-    const int bx = (int)blockIdx.x;              // (token tile, batch / request) index
-    const int by = NG > 1 ? (int)blockIdx.y : 0;  // head group
+    // Grid: x = batch element, y = request, z = token tile; head-group variant (one request): x = batch element,
+    // y = token tile, z = head group. Workgroups are dispatched x fastest, so consecutive ones (which round-robin over
+    // the 8 XCDs) share a token tile index and differ in the batch element / request: one XCD, few K~/V~ images. The
+    // indices come straight from the grid: no integer divisions in front of the first loads.
+    const int b = (int)blockIdx.x;
+    const int ri = NG > 1 ? 0 : (int)blockIdx.y;
+    const int tile = NG > 1 ? (int)blockIdx.y : (int)blockIdx.z;
+    const int by = NG > 1 ? (int)blockIdx.z : 0;  // head group
     const int h = by * NH + hl;  // head of the layer; hl = head within the workgroup
     const int tbase = (((tid >> 6) / NH) % F::G) * 16 * NTT;  // first tile row of this wavefront's tokens
     const int sub = SUB == 1 ? 0 : (tid >> 6) / (NH * F::G);  // which share of the channel tiles of A^ V~
-    const int RB = dm.R * dm.B;
-    const int rb = bx % RB, tile = bx / RB;  // batch / request index fastest: one XCD, one K~/V~ image
-    const int ri = rb / dm.B, b = rb % dm.B;
     const FusedReq rq = tab.req[ri];
     const int N = dm.N, T = dm.T;
     const int nt16 = NT16 ? NT16 : dm.nt16;
@@ -1134,7 +1135,9 @@ static hipError_t launch_fused_grid(const FusedTable& tab, const FusedDims& dm, 
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE, NT16, DENSE>), 160 * 1024, lds_set);
     if (e != hipSuccess) return e;
     const int tiles = (dm.N + TOK - 1) / TOK;
-    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE, NT16, DENSE>), dim3(tiles * dm.R * dm.B, NG), dim3(F::NT), bytes, st, tab, dm);
+    if (tiles > 65535 || dm.R > 65535 || (NG > 1 && dm.R != 1)) return hipErrorInvalidValue;
+    const dim3 grid = NG > 1 ? dim3(dm.B, tiles, NG) : dim3(dm.B, dm.R, tiles);
+    hipLaunchKernelGGL((fused_block_kernel<D, NH, NTT, NG, PG, TOK, CORE, NT16, DENSE>), grid, dim3(F::NT), bytes, st, tab, dm);
     return hipGetLastError();
 }
 

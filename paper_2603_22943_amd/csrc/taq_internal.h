@@ -124,6 +124,7 @@ static inline bool fused_supported(const taq_shape& s) {
     if (s.C % s.H) return false;
     const int d = s.C / s.H;
     if (!((d == 40 && s.H == 8) || (d == 80 && s.H == 8) || (d == 64 && s.H == 10))) return false;
+    if (s.N > 16 * 65535) return false;  // token tiles are a y / z dimension of the grid
     return fused_lds_bytes(s) <= 160 * 1024;
 }
 
@@ -141,6 +142,7 @@ static inline bool mid_supported(const taq_shape& s) {
     if (s.C % s.H) return false;
     const int d = s.C / s.H;
     if (!((d == 160 && s.H == 8) || (d == 64 && s.H == 20))) return false;
+    if (s.N > 16 * 65535) return false;  // token tiles are a y dimension of the grid
     return mid_lds_bytes(s) <= 160 * 1024;
 }
 
