@@ -238,6 +238,31 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     const int nt16 = NT16 ? NT16 : dm.nt16;
     const int n0 = tile * TOK;
 
+    // ---- The hidden tile's loads are issued before anything else: they are the head of the kernel's one unavoidable
+    // latency chain (HBM), and everything below (scalar loads of layout fields, of the protected-token count from
+    // global memory, address arithmetic for the weights) would otherwise sit in front of them.
+    constexpr bool HQ1 = NG == 1 && !CORE;         // single-kernel variant: 16 threads per token, 8-byte loads
+    constexpr int TPT = NG > 1 ? NT / TOK : 16;    // threads per token
+    constexpr int CH = NG > 1 ? C / (8 * TPT) : 1; // head-group variant: 16-byte pieces of a hidden row per thread
+    const int tok0 = tid / TPT, part0 = tid % TPT;
+    const int nq0 = n0 + tok0;
+    const size_t row0 = (size_t)b * N + (nq0 < N ? nq0 : N - 1);
+    uint2 xin[HQ1 ? KC : 1];
+    uint4 xin4[NG > 1 ? CH : 1];
+    if constexpr (HQ1) {
+        if (tid < 16 * TOK) {
+            const uint2* xr = reinterpret_cast<const uint2*>(rq.hidden + row0 * C);
+#pragma unroll
+            for (int it = 0; it < KC; ++it) xin[it] = xr[it * 16 + part0];
+        }
+    }
+    if constexpr (NG > 1) {
+        const uint4* xr = reinterpret_cast<const uint4*>(rq.hidden + row0 * C);
+#pragma unroll
+        for (int it = 0; it < CH; ++it) xin4[it] = xr[it * TPT + part0];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
     // ---- LDS carve-up
     unsigned char* img = smem;                                  // K~/V~ image blocks of this workgroup's heads
     const size_t img_bytes = (size_t)NH * dm.I.head_bytes;
@@ -313,15 +338,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     if constexpr (NG == 1 && !CORE) {
         // ---- phase 0: issue every global read up front, oldest first in the order of use (loads return in
         // order): hidden tile, weight scales, this head's to_q weight slice, the K~/V~ image
-        const int tok0 = tid >> 4, part0 = tid & 15;  // 16 threads per token, 4 channels per load (first 16*TOK threads)
-        const int nq0 = n0 + tok0;
-        const size_t row0 = (size_t)b * N + (nq0 < N ? nq0 : N - 1);
-        uint2 xin[KC];
-        if (tid < 16 * TOK) {
-            const uint2* xr = reinterpret_cast<const uint2*>(rq.hidden + row0 * C);
-    #pragma unroll
-            for (int it = 0; it < KC; ++it) xin[it] = xr[it * 16 + part0];
-        }
+        // (16 threads per token, 4 channels per load: the first 16*TOK threads hold the tile, requested above)
         constexpr int SCV = (3 * C / 4 + NT - 1) / NT;
         float4 scv[SCV];
     #pragma unroll
@@ -391,26 +408,15 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     int32x4_t wpre[TJ][KW];
     int32x4_t imv[IMV];
     if constexpr (NG > 1) {
-        constexpr int TPT = NT / TOK;        // threads per token: 16 or 32
-        constexpr int CH = C / (8 * TPT);    // 16-byte pieces of a hidden row per thread
         static_assert(NG == 1 || (TW % 2 == 0 && KC % KP == 0 && C % (8 * TPT) == 0 && (TPT == 16 || TPT == 32)), "head-group split");
         const int wv = tid >> 6, js = wv & 1, kp = wv >> 1;
-        const int tok0 = tid / TPT, part0 = tid % TPT;
-        const int nq0 = n0 + tok0;
-        const size_t row0 = (size_t)b * N + (nq0 < N ? nq0 : N - 1);
-        uint4 xin[CH];
-        {
-            const uint4* xr = reinterpret_cast<const uint4*>(rq.hidden + row0 * C);
-#pragma unroll
-            for (int it = 0; it < CH; ++it) xin[it] = xr[it * TPT + part0];
-        }
         float4 swv = make_float4(0.f, 0.f, 0.f, 0.f);  // s_wq of this workgroup's heads: NH*D floats
         if (tid < NH * D / 4) swv = reinterpret_cast<const float4*>(rq.scales + (size_t)by * NH * D)[tid];
         // ---- per-token int8 codes of the hidden tile (every head group of a token tile computes the same codes)
         float amax = 0.f;
 #pragma unroll
         for (int it = 0; it < CH; ++it) {
-            const __half2* hh2 = reinterpret_cast<const __half2*>(&xin[it]);
+            const __half2* hh2 = reinterpret_cast<const __half2*>(&xin4[it]);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float2 p = __half22float2(hh2[e]);
@@ -455,7 +461,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                     imv[f - TJ * KW] = gimg[i < img16 ? i : img16 - 1];
                 }
             }
-            const __half2* hh2 = reinterpret_cast<const __half2*>(&xin[it]);
+            const __half2* hh2 = reinterpret_cast<const __half2*>(&xin4[it]);
             const float2 p0 = __half22float2(hh2[0]), p1 = __half22float2(hh2[1]);
             const float2 p2 = __half22float2(hh2[2]), p3 = __half22float2(hh2[3]);
             uint2 pk;
