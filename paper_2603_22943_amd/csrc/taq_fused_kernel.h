@@ -247,10 +247,11 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     const int tok0 = tid / TPT, part0 = tid % TPT;
     const int nq0 = n0 + tok0;
     const size_t row0 = (size_t)b * N + (nq0 < N ? nq0 : N - 1);
+    const bool HOLDS = NT == 16 * TOK || tid < 16 * TOK;  // this thread holds a piece of the tile (all do, at 8 heads)
     uint2 xin[HQ1 ? KC : 1];
     uint4 xin4[NG > 1 ? CH : 1];
     if constexpr (HQ1) {
-        if (tid < 16 * TOK) {
+        if (HOLDS) {
             const uint2* xr = reinterpret_cast<const uint2*>(rq.hidden + row0 * C);
 #pragma unroll
             for (int it = 0; it < KC; ++it) xin[it] = xr[it * 16 + part0];
@@ -349,7 +350,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         // ---- per-token int8 codes of the hidden tile. The row maximum is taken on the fp16 values themselves, two per
         // instruction (a maximum is exact in any precision); the quantizer's FMAs read the fp16 operands directly.
         float amax = 0.f;
-        if (tid < 16 * TOK) {
+        if (HOLDS) {
             half2_t am2 = {(_Float16)0.f, (_Float16)0.f};
     #pragma unroll
             for (int it = 0; it < KC; ++it) {
@@ -370,7 +371,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         const float sc0 = zero0 ? 1.f : amax / 127.f;
         const float safe0 = zero0 ? 1.f : amax;
         const float cq0 = 127.f * __builtin_amdgcn_rcpf(safe0);
-        if (tid < 16 * TOK && part0 == 0) s_h[tok0] = sc0;
+        if (HOLDS && part0 == 0) s_h[tok0] = sc0;
     #pragma unroll
         for (int it = 0; it < KC; ++it) {
             if (F::PREFETCH_W) {
@@ -381,7 +382,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     #pragma unroll
                 for (int f = it * RPS; f < (it + 1) * RPS && f < RING; ++f) wring[f] = load_w(rs_wq, f % TPH, wstep * (f / TPH));
             }
-            if (tid < 16 * TOK) {
+            if (HOLDS) {
                 const half2_t x01 = *reinterpret_cast<const half2_t*>(&xin[it].x), x23 = *reinterpret_cast<const half2_t*>(&xin[it].y);
                 const unsigned pk = quant4_i8((float)x01[0], (float)x01[1], (float)x23[0], (float)x23[1], cq0, safe0);
                 *reinterpret_cast<unsigned*>(tileq + tok0 * F::TILE_RS + (it * 16 + part0) * 4) = pk;
@@ -389,7 +390,7 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (TAPS && tid < 16 * TOK && dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc0;
+        if (TAPS && HOLDS && dm.dbg.s_h && part0 == 0 && nq0 < N) dm.dbg.s_h[row0] = sc0;
         // ---- weight scales into LDS
     #pragma unroll
         for (int k = 0; k < SCV; ++k) {
