@@ -129,9 +129,9 @@ __global__ __launch_bounds__(64 * OT * TG) void to_out_tail_kernel(FusedTable ta
     constexpr int CH = C / 128;  // float4 pieces of a row per thread
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r16 = lane & 15, q = lane >> 4;
-    const int gt = (int)blockIdx.y * OT + (wave % OT);  // output tile of the layer: channels 16*gt .. 16*gt+15
+    const int gt = (int)blockIdx.z * OT + (wave % OT);  // output tile of the layer: channels 16*gt .. 16*gt+15
     const int tl = (wave / OT) * 16 + r16;              // this lane's token within the 32-token tile
-    const int b = blockIdx.x % dm.B, tile = blockIdx.x / dm.B;
+    const int b = blockIdx.x, tile = blockIdx.y;  // (grid: batch element, token tile, group of OT output tiles)
     const FusedReq rq = tab.req[0];
     const int N = dm.N, n0 = tile * TOKS;
     int8_t* tileq = reinterpret_cast<int8_t*>(smem);               // [TOKS][C+16]
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(64 * OT * TG) void to_out_tail_kernel(FusedTable ta
         const float sc = zero ? 1.f : amax / 127.f;
         const float safe = zero ? 1.f : amax;
         const float cq = 127.f * __builtin_amdgcn_rcpf(safe);
-        const bool tap = blockIdx.y == 0 && nq < N;
+        const bool tap = blockIdx.z == 0 && nq < N;
         if (part == 0) s_o[tk] = sc;
         if (tap && dm.dbg.s_o && part == 0) dm.dbg.s_o[row] = sc;
 #pragma unroll
@@ -227,7 +227,8 @@ static hipError_t launch_tail_cfg(const FusedTable& tab, const FusedDims& dm, hi
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&to_out_tail_kernel<C, OT, FUSEQ, TT, TG>), 160 * 1024, lds_set);
     if (e != hipSuccess) return e;
     const int tiles = (dm.N + TOKS - 1) / TOKS;
-    hipLaunchKernelGGL((to_out_tail_kernel<C, OT, FUSEQ, TT, TG>), dim3(tiles * dm.B, C / 16 / OT), dim3(64 * OT * TG), bytes, st, tab, dm);
+    if (tiles > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((to_out_tail_kernel<C, OT, FUSEQ, TT, TG>), dim3(dm.B, tiles, C / 16 / OT), dim3(64 * OT * TG), bytes, st, tab, dm);
     return hipGetLastError();
 }
 
