@@ -759,6 +759,38 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
         }
     };
 
+    // The LDS operands of O^T = V~^T A^^T (this wavefront's V~ codes and the split V scales) are read now, into
+    // registers: issued next to their use, each read's round trip would stand between the softmax and its MFMAs.
+    // (Only where registers are plentiful: the instantiation that also holds its weight slices in registers.)
+    constexpr bool PRE_V = F::PREFETCH_W && NG == 1;
+    uint2 vw2[PRE_V ? 3 : 1][PRE_V ? TPS : 1];  // V~^T codes of 32-token step s (s = 0, 1, 2; a single last tile uses .x only)
+    uint2 svh[PRE_V ? MT16 : 1], svl[PRE_V ? MT16 : 1];  // fp16 high parts and remainders of s_V * 2^kexp, four text tokens of each tile
+    const uint8_t* vt = imgh + dm.I.vt;
+    const _Float16* img_sv = reinterpret_cast<const _Float16*>(imgh + dm.I.s_vp);  // [ntok] high parts | [ntok] low parts
+    if constexpr (PRE_V) {
+#pragma unroll
+        for (int tt = 0; tt < MT16; ++tt) {
+            svh[tt] = svl[tt] = make_uint2(0u, 0u);
+            if (tt < nt16) {
+                svh[tt] = *reinterpret_cast<const uint2*>(img_sv + 16 * tt + 4 * q);
+                svl[tt] = *reinterpret_cast<const uint2*>(img_sv + dm.I.ntok + 16 * tt + 4 * q);
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < 3; ++s)
+#pragma unroll
+            for (int k = 0; k < TPS; ++k) {
+                vw2[s][k] = make_uint2(0u, 0u);
+                const int jt = sub + SUB * k;
+                if (2 * s >= nt16 || (SUB > 1 && jt >= TPH)) continue;
+                int j = 16 * jt + r16;
+                j = j < D ? j : D - 1;
+                if (2 * s + 1 < nt16) vw2[s][k] = *reinterpret_cast<const uint2*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 8 * q);
+                else vw2[s][k].x = *reinterpret_cast<const unsigned*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 4 * q);
+            }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
     // ================= softmax over the text tokens; Eq. (3); weights of O^T = V~^T A^^T
     float kq[NTT];   // code = rint(E * kq): pmax / Z per image token (row-range grid: pmax / largest unprotected E)
     float kqp[NTT];  // protected columns: weight = E * kqp = pmax * A
@@ -884,8 +916,6 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     // The code itself is formed with one FMA: P * kq + (1.5 * 2^23 + 0x6400) rounds P * kq half-to-even to an integer
     // and leaves 0x6400 + code in the low half of the result: the bit pattern of the fp16 number 1024 + code.
     {
-        const uint8_t* vt = imgh + dm.I.vt;
-        const _Float16* img_sv = reinterpret_cast<const _Float16*>(imgh + dm.I.s_vp);  // [ntok] high parts | [ntok] low parts
         const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
         // tap: the codes of text tokens t, t + 1 for this lane's image token of tile nt (one wavefront per (head, token group))
         auto tap_pcode = [&](int nt, int t, unsigned c0, unsigned c1) {
@@ -903,8 +933,14 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
                     if (a == 0 || second) {
-                        const uint2 h4 = *reinterpret_cast<const uint2*>(img_sv + 16 * (2 * s + a) + 4 * q);
-                        const uint2 l4 = *reinterpret_cast<const uint2*>(img_sv + dm.I.ntok + 16 * (2 * s + a) + 4 * q);
+                        uint2 h4, l4;
+                        if constexpr (PRE_V) {
+                            h4 = svh[2 * s + a < MT16 ? 2 * s + a : 0];
+                            l4 = svl[2 * s + a < MT16 ? 2 * s + a : 0];
+                        } else {
+                            h4 = *reinterpret_cast<const uint2*>(img_sv + 16 * (2 * s + a) + 4 * q);
+                            l4 = *reinterpret_cast<const uint2*>(img_sv + dm.I.ntok + 16 * (2 * s + a) + 4 * q);
+                        }
                         const half2_t sh[2] = {*reinterpret_cast<const half2_t*>(&h4.x), *reinterpret_cast<const half2_t*>(&h4.y)};
                         const half2_t sl[2] = {*reinterpret_cast<const half2_t*>(&l4.x), *reinterpret_cast<const half2_t*>(&l4.y)};
 #pragma unroll
@@ -951,7 +987,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                     int j = 16 * jt + r16;
                     j = j < D ? j : D - 1;
                     if (second) {  // two score tiles: 32 tokens deep, a lane's 8 codes are consecutive (vt_pos)
-                        const uint2 w = *reinterpret_cast<const uint2*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 8 * q);
+                        const uint2 w = PRE_V ? vw2[PRE_V ? s : 0][PRE_V ? k : 0]
+                                              : *reinterpret_cast<const uint2*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 8 * q);
                         half2_t v0, v1, v2, v3;
                         biased4_to_half(w.x, v0, v1);
                         biased4_to_half(w.y, v2, v3);
@@ -962,7 +999,8 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
                             oacc[nt][k] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, plo[nt], oacc[nt][k], 0, 0, 0);
                         }
                     } else {       // a last single tile: 16 tokens deep, in their natural order
-                        const unsigned w = *reinterpret_cast<const unsigned*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 4 * q);
+                        const unsigned w = PRE_V ? vw2[PRE_V ? s : 0][PRE_V ? k : 0].x
+                                                 : *reinterpret_cast<const unsigned*>(vt + (size_t)j * dm.I.cols_v + 32 * s + 4 * q);
                         half2_t v0, v1;
                         biased4_to_half(w, v0, v1);
                         const half4_t va = {v0[0], v0[1], v1[0], v1[1]};
