@@ -120,8 +120,11 @@ hipError_t launch_pack_weight(const int8_t* codes, const taq_shape& s, int8_t* o
 // a token tile forms the same int8 codes of its rows (32 threads per row) in LDS: one kernel less, worth it while
 // the layer has few token tiles. Otherwise the codes and scales were formed once by the row quantizer kernel.
 // Same operand layout and epilogue as the last phase of the fused kernel.
+// (At most 128 registers per lane, so that two 8-wavefront workgroups share a compute unit: the 256-token layers have
+// 320 workgroups, and with one per compute unit the last 64 of them ran as a second round after the first had finished.)
 template <int C, int OT, bool FUSEQ, int TT = 1, int TG = 2>
-__global__ __launch_bounds__(64 * OT * TG) void to_out_tail_kernel(FusedTable tab, FusedDims dm) {
+__global__ __launch_bounds__(64 * OT * TG) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void to_out_tail_kernel(FusedTable tab, FusedDims dm) {
     constexpr int KC = C / 64, NT = 64 * OT * TG, TILE_RS = C + 16;
     constexpr int TOKS = 16 * TG * TT;  // image tokens per workgroup: every weight load serves TT token groups of 16
     static_assert(C % 128 == 0, "32 threads per token row");
@@ -166,8 +169,10 @@ __global__ __launch_bounds__(64 * OT * TG) void to_out_tail_kernel(FusedTable ta
         float amax = 0.f;
         for (int i = part; i < dm.omax_n; i += 32) amax = fmaxf(amax, dm.ws_omax[row * dm.omax_n + i]);
         __builtin_amdgcn_sched_barrier(0);
+        // (the first KPRE weight loads now, the rest once the rows' registers are free: 128 registers per lane in all)
+        constexpr int KPRE = KC < 12 ? KC : 12;
 #pragma unroll
-        for (int ks = 0; ks < KC; ++ks) wa[ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow + wstep * ks);
+        for (int ks = 0; ks < KPRE; ++ks) wa[ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow + wstep * ks);
         __builtin_amdgcn_sched_barrier(0);
         amax = row16_allmax(amax);
         {   // the other 16 lanes of this token
@@ -187,6 +192,9 @@ __global__ __launch_bounds__(64 * OT * TG) void to_out_tail_kernel(FusedTable ta
             *reinterpret_cast<unsigned*>(tileq + tk * TILE_RS + (it * 32 + part) * 4) = pk;
             if (tap && dm.dbg.o_code) *reinterpret_cast<unsigned*>(dm.dbg.o_code + row * C + (it * 32 + part) * 4) = pk;
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = KPRE; ks < KC; ++ks) wa[ks] = *reinterpret_cast<const int32x4_t*>(rq.wo + wrow + wstep * ks);
     }
     __syncthreads();
     int32x4_t acc[TT];
