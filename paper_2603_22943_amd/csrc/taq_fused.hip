@@ -360,7 +360,7 @@ hipError_t launch_to_out_tail(const FusedReq& rq, const taq_shape& s, const floa
     dm.ws_ocode = o_code;
     dm.ws_so = s_o;
     // codes from the row quantizer (large layers): 64 tokens per workgroup, so that a weight load serves four token groups
-    if (s.C == 1280) return o_code ? launch_tail_cfg<1280, 8, false, 4, 1>(tab, dm, st) : launch_tail_cfg<1280, 8, true, 1, 1>(tab, dm, st);
+    if (s.C == 1280) return o_code ? launch_tail_cfg<1280, 8, false, 3, 1>(tab, dm, st) : launch_tail_cfg<1280, 8, true, 1, 1>(tab, dm, st);
     return hipErrorInvalidValue;
 }
 
