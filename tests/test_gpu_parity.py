@@ -475,6 +475,18 @@ def test_rowmax_probability_grid_when_a_trigger_takes_the_whole_row():
         check_layer(L, f"rowmax grid dominant trigger x{scale} C={C}", bits_prob=8, prob_grid="rowmax")
 
 
+@pytest.mark.parametrize("T_", [64, 65, 80, 81])
+@pytest.mark.parametrize("C,H,N", [(320, 8, 70), (640, 8, 45), (1280, 8, 40)])
+def test_text_lengths_around_the_five_tile_specialisation(C, H, N, T_):
+    """The fused kernels have an instantiation for exactly five 16-token score tiles (65..80 text tokens, taps compiled
+    out) beside the general one: both ends of that range and the first length on either side of it, on the single-kernel
+    and the head-group path. check_layer runs the call with and without taps (the general and the specialised build
+    inside the range) and requires identical outputs."""
+    L = synth.make_layer("tlen", seed=C + N + T_, B=2, N=N, C=C, H=H, Cc=64, T=T_, bits_kv=8 if T_ % 2 else 4,
+                         trigger_positions=(0, T_ - 1), trigger_scale=3.0, bias=True)
+    check_layer(L, f"C={C} N={N} T={T_}")
+
+
 @pytest.mark.parametrize("C,H,B,N,bits_kv", [(1280, 8, 2, 530, 8), (1280, 20, 1, 1050, 4)])
 def test_head_group_layers_with_more_than_1024_tokens_ragged(C, H, B, N, bits_kv):
     """Above 1024 image tokens in total the head-group path quantizes A^ V~ with the row quantizer kernel and runs
