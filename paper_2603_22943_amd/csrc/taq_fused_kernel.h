@@ -498,16 +498,19 @@ void fused_block_kernel(FusedTable tab, FusedDims dm) {
     if constexpr (CORE) {
         // no projection: Q~ comes from the workspace
     } else if constexpr (F::PREFETCH_W) {
+        // K step outermost: the order in which the weight loads were issued, so that the MFMAs follow the weights as they
+        // arrive and only one step's worth is left to do after the last load
 #pragma unroll
-        for (int j = 0; j < TPH; ++j) {
+        for (int j = 0; j < TPH; ++j)
 #pragma unroll
             for (int nt = 0; nt < NTT; ++nt) pacc[nt][j] = (int32x4_t){0, 0, 0, 0};
 #pragma unroll
-            for (int ks = 0; ks < KC; ++ks)
+        for (int ks = 0; ks < KC; ++ks)
+#pragma unroll
+            for (int j = 0; j < TPH; ++j)
 #pragma unroll
                 for (int nt = 0; nt < NTT; ++nt)
                     pacc[nt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wreg[j][ks], hb[nt][ks], pacc[nt][j], 0, 0, 0);
-        }
     } else if constexpr (NG == 1 && RING > 0) {
 #pragma unroll
         for (int j = 0; j < TPH; ++j)
